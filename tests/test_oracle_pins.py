@@ -1,0 +1,512 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+Nothing here touches the HIP path.  Every check compares the oracle with
+something that is not the oracle: a worked example of the paper, a closed
+form, a probability printed in Table 1 / Table 2, an invariant, or a brute
+force written in a different form (sets / table look-up) in pure Python.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import tm_oracle as O
+from paper_2009_04861_amd import synth
+
+
+def make(m=2, n=4, o=3, N=4, T=3, s=3.0, seed=11, init=True):
+    return O.Oracle(m, n, o, N, T, s, seed, init=init)
+
+
+def lits(x):
+    x = np.asarray(x, dtype=np.uint8)
+    return np.concatenate([x, 1 - x]).astype(np.uint8)
+
+
+# --------------------------------------------------------------------------
+# Clause evaluation (Eq. 1) and voting (Eq. 2 / Eq. 3)
+# --------------------------------------------------------------------------
+
+def test_paper_clause_example_x1_and_not_x2():
+    # Section 2.1: C = x1 AND NOT x2 outputs 1 iff x1 = 1 and x2 = 0.
+    t = make(m=2, n=2, o=2, N=5, init=False)
+    t.state[:] = 1                      # everything excluded ...
+    t.state[0, 0] = 6                   # ... clause 0 includes x1
+    t.state[0, 2 + 1] = 10              # ... and NOT x2
+    X = np.array(list(itertools.product([0, 1], repeat=2)), dtype=np.uint8)
+    out = t.clause_outputs(X)[:, 0]
+    want = [(1 if (a == 1 and b == 0) else 0) for a, b in X]
+    assert out.tolist() == want
+
+
+def test_include_boundary_is_state_greater_than_N():
+    # Section 2.2: the counter is increased to reinforce Include, so the
+    # upper half of the 2N states is Include: state N excludes, N+1 includes.
+    t = make(m=2, n=2, o=1, N=7, init=False)
+    t.state[:] = 1
+    X = np.array([[0]], dtype=np.uint8)
+    t.state[0, 0] = 7
+    assert t.clause_outputs(X)[0, 0] == 1    # x excluded -> empty clause -> 1
+    t.state[0, 0] = 8
+    assert t.clause_outputs(X)[0, 0] == 0    # x included, x = 0 -> 0
+
+
+def test_clause_outputs_brute_force_sets():
+    # independent formulation: clause true iff its included literal set is a
+    # subset of the set of true literals
+    rng = np.random.default_rng(0)
+    for o in (1, 5, 12, 33):
+        t = make(m=3, n=4, o=o, N=6, init=False)
+        t.state[:] = rng.integers(1, 13, size=t.state.shape)
+        X = rng.integers(0, 2, size=(64, o), dtype=np.uint8)
+        out = t.clause_outputs(X)
+        for i in range(X.shape[0]):
+            true_lits = {k for k in range(o) if X[i, k]} | {o + k for k in range(o) if not X[i, k]}
+            for g in range(t.C):
+                inc = {k for k in range(2 * o) if t.state[g, k] >= 7}
+                assert out[i, g] == (1 if inc <= true_lits else 0)
+
+
+def xor_machine(o=12, n=4, T=15):
+    """Two banks of hand-set clauses realising the XOR classifier: positive
+    clauses of class 1 are x0 AND NOT x1, NOT x0 AND x1; its negative clauses
+    x0 AND x1, NOT x0 AND NOT x1; class 0 is the mirror image."""
+    t = O.Oracle(2, n, o, 100, T, 3.9, 1, init=False)
+    t.state[:] = 1
+    inc = 150
+
+    def setc(g, a, b):      # a, b: +1 plain, -1 negated  for features 0 and 1
+        t.state[g, 0 if a > 0 else o + 0] = inc
+        t.state[g, 1 if b > 0 else o + 1] = inc
+
+    # class 1: odd j positive -> j=1,3 ; even j negative -> j=0,2
+    setc(1 * n + 1, +1, -1); setc(1 * n + 3, -1, +1)
+    setc(1 * n + 0, +1, +1); setc(1 * n + 2, -1, -1)
+    # class 0 mirrored
+    setc(0 * n + 1, +1, +1); setc(0 * n + 3, -1, -1)
+    setc(0 * n + 0, +1, -1); setc(0 * n + 2, -1, +1)
+    return t
+
+
+def test_xor_classifier_all_4096_inputs():
+    t = xor_machine()
+    X = np.array(list(itertools.product([0, 1], repeat=12)), dtype=np.uint8)
+    xor = (X[:, 0] ^ X[:, 1]).astype(np.int32)
+    sums = t.class_sums(X)
+    assert np.array_equal(sums[:, 1], np.where(xor == 1, 1, -1))
+    assert np.array_equal(sums[:, 0], np.where(xor == 1, -1, 1))
+    assert np.array_equal(t.predict(X), xor)
+
+
+def test_polarity_odd_positive_even_negative():
+    # one satisfied clause at a time: its vote is +1 for odd j, -1 for even j
+    for j in range(4):
+        t = make(m=2, n=4, o=2, N=5, T=9, init=False)
+        t.state[:] = 10                   # everything included -> all clauses 0
+        t.state[4 + j, :] = 1             # clause j of class 1 empty -> 1
+        s = t.class_sums(np.array([[1, 0]], dtype=np.uint8), clamp=False)
+        assert s[0, 1] == (1 if j % 2 == 1 else -1) and s[0, 0] == 0
+
+
+def test_class_sum_clamped_to_T_and_argmax_ties_low_index():
+    t = make(m=3, n=8, o=2, N=5, T=2, init=False)
+    t.state[:] = 1                        # all clauses empty -> all output 1
+    # class 0: silence negative clauses -> raw +4 ; class 1: silence positive -> raw -4
+    for j in range(8):
+        if j % 2 == 0:
+            t.state[0 * 8 + j, :] = 10
+        else:
+            t.state[1 * 8 + j, :] = 10
+    X = np.array([[1, 0]], dtype=np.uint8)
+    assert t.class_sums(X, clamp=False).tolist() == [[4, -4, 0]]
+    assert t.class_sums(X, clamp=True).tolist() == [[2, -2, 0]]
+    assert t.predict(X).tolist() == [0]
+    # tie between class 0 and 2 after silencing class 0 fully -> lowest index
+    t.state[0:8, :] = 10
+    assert t.class_sums(X).tolist() == [[0, -2, 0]]
+    assert t.predict(X).tolist() == [0]
+
+
+# --------------------------------------------------------------------------
+# Gate (Algorithm 1: clip, error, rand() <= e/2T ; Section 2.2 last paragraph)
+# --------------------------------------------------------------------------
+
+def test_gate_endpoints_exact():
+    t = make(T=5)
+    for g in range(8):
+        for i in range(500):
+            # target 1, v >= T  -> e = 0 -> never ("no clauses are reinforced")
+            assert t.gate(g, i, 0, 5, 1) == 0
+            assert t.gate(g, i, 0, 99, 1) == 0          # clipped
+            # target 1, v <= -T -> e = 2T -> always
+            assert t.gate(g, i, 0, -5, 1) == 1
+            assert t.gate(g, i, 0, -99, 1) == 1
+            # target 0 mirrors
+            assert t.gate(g, i, 0, -5, 0) == 0
+            assert t.gate(g, i, 0, 7, 0) == 1
+
+
+@pytest.mark.parametrize("T", [4, 15, 50])
+def test_gate_frequency_is_e_over_2T(T):
+    t = make(T=T)
+    n = 20000
+    for v, target in [(0, 1), (T // 2, 1), (-T // 2, 1), (T // 2, 0), (1 - T, 0)]:
+        vc = max(-T, min(T, v))
+        e = T - vc if target else T + vc
+        p = e / (2.0 * T)
+        hits = sum(t.gate(3, i, 2, v, target) for i in range(n))
+        assert abs(hits / n - p) < 4.5 * np.sqrt(p * (1 - p) / n) + 1e-9, (v, target, hits / n, p)
+
+
+def test_gate_draw_depends_on_clause_example_epoch():
+    t = make(T=8)
+    a = [t.gate(1, i, 0, 0, 1) for i in range(256)]
+    assert a != [t.gate(2, i, 0, 0, 1) for i in range(256)]
+    assert a != [t.gate(1, i, 1, 0, 1) for i in range(256)]
+    assert a != [t.gate(1, i + 256, 0, 0, 1) for i in range(256)]
+    t2 = make(T=8, seed=12)
+    assert a != [t2.gate(1, i, 0, 0, 1) for i in range(256)]
+
+
+# --------------------------------------------------------------------------
+# Type I feedback (Table 1) and Type II feedback (Table 2)
+# --------------------------------------------------------------------------
+
+def table1(action_include, C, lit, s):
+    """(P reward, P inaction, P penalty) typed from Table 1 of the paper."""
+    hi, lo = (s - 1.0) / s, 1.0 / s
+    if action_include:
+        if C == 1 and lit == 1: return (hi, lo, 0.0)
+        if C == 1 and lit == 0: return None                     # NA
+        return (0.0, hi, lo)
+    else:
+        if C == 1 and lit == 1: return (0.0, lo, hi)
+        return (lo, hi, 0.0)
+
+
+def table2(action_include, C, lit):
+    """(P reward, P inaction, P penalty) typed from Table 2 of the paper."""
+    if (not action_include) and C == 1 and lit == 0:
+        return (0.0, 0.0, 1.0)
+    return (0.0, 1.0, 0.0)
+
+
+def delta_of(outcome, action_include):
+    # Section 2.2: reinforcing Include (reward Include / penalise Exclude)
+    # increases the counter, reinforcing Exclude decreases it.
+    if outcome == "inaction": return 0
+    if outcome == "reward": return +1 if action_include else -1
+    return -1 if action_include else +1
+
+
+@pytest.mark.parametrize("s", [2.0, 3.9, 10.0])
+def test_type1_frequencies_match_table1(s):
+    o, N = 16, 50
+    t = O.Oracle(2, 2, o, N, 5, s, 5, init=False)
+    trials = 1500
+    for C in (0, 1):
+        for include in (False, True):
+            for litv in (0, 1):
+                cell = table1(include, C, litv, s)
+                if cell is None:
+                    continue
+                start = N + 10 if include else N - 10
+                up = down = 0
+                lit = np.full(2 * o, litv, dtype=np.uint8)
+                for i in range(trials):
+                    st = np.full(2 * o, start, dtype=np.int32)
+                    t.type1(st, lit, C, 1, i, 3)
+                    d = st - start
+                    assert np.all(np.abs(d) <= 1)
+                    up += int((d == 1).sum()); down += int((d == -1).sum())
+                tot = trials * 2 * o
+                p_up = cell[0] if include else cell[2]      # reward Include / penalty Exclude -> +1
+                p_dn = cell[2] if include else cell[0]      # penalty Include / reward Exclude -> -1
+                for cnt, p in ((up, p_up), (down, p_dn)):
+                    tol = 4.5 * np.sqrt(max(p * (1 - p), 1e-12) / tot) + 2.0 ** -15
+                    assert abs(cnt / tot - p) <= tol, (C, include, litv, cnt / tot, p)
+                    if p == 0.0:
+                        assert cnt == 0
+
+
+def test_type1_s_equal_1_is_deterministic():
+    # 1/s = 1 and (s-1)/s = 0: every weak event happens, no strong one does
+    o, N = 40, 9
+    t = O.Oracle(2, 2, o, N, 5, 1.0, 3, init=False)
+    rng = np.random.default_rng(1)
+    lit = rng.integers(0, 2, size=2 * o).astype(np.uint8)
+    start = rng.integers(2, 2 * N, size=2 * o).astype(np.int32)
+    st = start.copy(); t.type1(st, lit, 0, 0, 0, 0)
+    assert np.array_equal(st, start - 1)
+    st = start.copy(); t.type1(st, lit, 1, 0, 0, 0)
+    assert np.array_equal(st, np.where(lit == 1, start, start - 1))
+
+
+def test_type1_saturates_at_1_and_2N():
+    o, N = 64, 3
+    t = O.Oracle(2, 2, o, N, 5, 2.0, 3, init=False)
+    lit = np.ones(2 * o, dtype=np.uint8)
+    st = np.full(2 * o, 2 * N, dtype=np.int32)
+    for i in range(50):
+        t.type1(st, lit, 1, 0, i, 0)
+    assert np.all(st == 2 * N)
+    st = np.full(2 * o, 1, dtype=np.int32)
+    for i in range(50):
+        t.type1(st, lit, 0, 0, i, 0)
+    assert np.all(st == 1)
+    # and they do move when not saturated
+    st = np.full(2 * o, 2, dtype=np.int32)
+    for i in range(50):
+        t.type1(st, lit, 0, 0, i, 0)
+    assert np.all(st == 1)
+
+
+def test_type1_paper_worked_example():
+    # Section 2.2, XOR walk-through: input (x1=0, x2=1), target 1; clause C1
+    # includes x1 and outputs 0; the TA of x1 gets Inaction w.p. (s-1)/s and
+    # Penalty (towards Exclude) w.p. 1/s.
+    s, N, o = 3.9, 100, 2
+    t = O.Oracle(2, 4, o, N, 15, s, 9, init=False)
+    lit = lits([0, 1])
+    trials, pen = 40000, 0
+    for i in range(trials):
+        st = np.array([N + 1, 1, 1, N + 1], dtype=np.int32)   # includes x1 and NOT x2
+        t.type1(st, lit, 0, 1, i, 0)
+        assert st[0] in (N, N + 1)
+        pen += int(st[0] == N)
+    p = 1 / s
+    assert abs(pen / trials - p) < 4.5 * np.sqrt(p * (1 - p) / trials)
+
+
+def test_type1_uniform_is_per_literal_and_16_bit():
+    # the decisions of different literals are independent draws: the joint
+    # frequency of two literals both moving equals the product
+    o, N, s = 8, 50, 2.0
+    t = O.Oracle(2, 2, o, N, 5, s, 21, init=False)
+    lit = np.zeros(2 * o, dtype=np.uint8)
+    n, both, a, b = 30000, 0, 0, 0
+    for i in range(n):
+        st = np.full(2 * o, N, dtype=np.int32)
+        t.type1(st, lit, 0, 0, i, 1)
+        ma, mb = st[0] != N, st[o + 3] != N
+        a += ma; b += mb; both += (ma and mb)
+    assert abs(a / n - 0.5) < 0.015 and abs(b / n - 0.5) < 0.015
+    assert abs(both / n - 0.25) < 0.015
+    assert t.threshold() == 32768
+    assert O.Oracle(2, 2, 4, 8, 5, 10.0, 1).threshold() == 6554
+    assert O.Oracle(2, 2, 4, 8, 5, 1.0, 1).threshold() == 65536
+
+
+def test_type2_exact_table2():
+    o, N = 6, 5
+    t = O.Oracle(2, 2, o, N, 5, 3.0, 1, init=False)
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        lit = rng.integers(0, 2, size=2 * o).astype(np.uint8)
+        start = rng.integers(1, 2 * N + 1, size=2 * o).astype(np.int32)
+        for C in (0, 1):
+            st = start.copy()
+            t.type2(st, lit, C)
+            for k in range(2 * o):
+                include = start[k] > N
+                if include and C == 1 and lit[k] == 0:
+                    want = start[k]                     # NA cell: cannot occur with C = 1; untouched
+                else:
+                    pr, pi, pp = table2(include, C, lit[k])
+                    want = start[k] + (delta_of("penalty", include) if pp == 1.0 else 0)
+                assert st[k] == want
+
+
+def test_type1_table_lookup_reformulation():
+    """Table-driven re-statement: look the cell up in Table 1, turn the
+    literal's 16-bit uniform into reward / inaction / penalty, move the
+    counter by the rule of Section 2.2.  The uniform is rebuilt here from
+    Philox words exactly as the oracle's header defines the slot of a literal."""
+    o, N, s, seed = 37, 6, 3.0, 77
+    t = O.Oracle(2, 2, o, N, 5, s, seed, init=False)
+    thr = int(np.floor(65536.0 / s + 0.5))
+    Wf = (o + 31) // 32
+    rng = np.random.default_rng(5)
+    key = [seed & 0xffffffff, seed >> 32]
+    for trial in range(40):
+        g, i, epoch = int(rng.integers(0, 4)), int(rng.integers(0, 1000)), int(rng.integers(0, 50))
+        lit = lits(rng.integers(0, 2, size=o))
+        start = rng.integers(1, 2 * N + 1, size=2 * o).astype(np.int32)
+        C = int(all(lit[k] == 1 for k in range(2 * o) if start[k] > N))
+        st = start.copy()
+        t.type1(st, lit, C, g, i, epoch)
+        for k in range(2 * o):
+            h = 1 if k >= o else 0
+            f = k - h * o
+            lw, j = h * Wf + f // 32, f % 32
+            u = 0
+            for b in range(16):
+                w = O.philox([(4 * lw + b // 4) | (O.TYPE1 << 28), g, i, epoch], key)[b % 4]
+                u |= ((w >> j) & 1) << b
+            include = start[k] > N
+            cell = table1(include, C, int(lit[k]), s)
+            assert cell is not None
+            if cell[1] == 1.0 / s:                 # the strong column: inaction has probability 1/s
+                outcome = "inaction" if u < thr else ("reward" if include else "penalty")
+            else:                                  # the weak columns: the event has probability 1/s
+                outcome = ("penalty" if include else "reward") if u < thr else "inaction"
+            want = min(2 * N, max(1, start[k] + delta_of(outcome, include)))
+            assert st[k] == want, (trial, k)
+
+
+# --------------------------------------------------------------------------
+# Initial states, negative class, bounds
+# --------------------------------------------------------------------------
+
+def test_init_states_are_N_or_N_plus_1_half_half():
+    t = O.Oracle(3, 6, 100, 128, 10, 4.0, 5)
+    assert set(np.unique(t.state)) == {128, 129}
+    assert abs((t.state == 129).mean() - 0.5) < 0.02
+    t2 = O.Oracle(3, 6, 100, 128, 10, 4.0, 6)
+    assert (t.state != t2.state).mean() > 0.4
+
+
+def test_neg_class_uniform_over_other_classes():
+    t = O.Oracle(5, 2, 4, 8, 5, 3.0, 2)
+    for y in range(5):
+        c = np.array([t.neg_class(1, i, y) for i in range(8000)])
+        assert y not in c and c.min() >= 0 and c.max() <= 4
+        counts = np.bincount(c, minlength=5)
+        for k in range(5):
+            if k != y:
+                assert abs(counts[k] / 8000 - 0.25) < 0.03
+    t2 = O.Oracle(2, 2, 4, 8, 5, 3.0, 2)
+    assert all(t2.neg_class(0, i, 0) == 1 and t2.neg_class(0, i, 1) == 0 for i in range(100))
+
+
+# --------------------------------------------------------------------------
+# Tallies, previous-output bits, training loops
+# --------------------------------------------------------------------------
+
+def small_problem(q=200, o=12, seed=3):
+    Xtr, ytr, Xte, yte = synth.noisy_xor(q, q, o=o, seed=seed)
+    return Xtr, ytr, Xte, yte
+
+
+def test_sync_tallies_equal_recomputed_class_sums():
+    X, y, _, _ = small_problem()
+    t = O.Oracle(2, 10, 12, 100, 15, 3.9, 1)
+    tally, ostar = t.sync_tallies(X)
+    assert np.array_equal(tally, t.class_sums(X, clamp=False))
+    assert np.array_equal(ostar.T, t.clause_outputs(X))
+
+
+@pytest.mark.parametrize("example_major", [True, False])
+def test_async_epoch_invariants(example_major):
+    X, y, _, _ = small_problem()
+    t = O.Oracle(2, 10, 12, 20, 15, 3.9, 1)
+    tally, ostar = t.sync_tallies(X)
+    sign = np.where(np.arange(t.C) % t.n % 2 == 1, 1, -1)
+    for epoch in range(6):
+        t.async_epoch(X, y, tally, ostar, epoch, example_major)
+        assert t.state.min() >= 1 and t.state.max() <= 2 * t.N
+        # the tally is always the signed sum of the stored previous outputs
+        want = np.stack([(ostar[c * t.n:(c + 1) * t.n] * sign[c * t.n:(c + 1) * t.n, None]).sum(0)
+                         for c in range(t.m)], axis=1)
+        assert np.array_equal(tally, want)
+    # "if the clauses stop changing the sums become exact": a pass of pure
+    # refreshes (done here by the pre-calculation routine) gives Eq. 3 exactly
+    tally2, ostar2 = t.sync_tallies(X)
+    assert np.array_equal(tally2, t.class_sums(X, clamp=False))
+    # and the stale tallies differ from the exact ones only through stale bits
+    stale = (ostar != ostar2)
+    assert np.array_equal(tally - tally2,
+                          np.stack([((ostar.astype(int) - ostar2)[c * t.n:(c + 1) * t.n]
+                                     * sign[c * t.n:(c + 1) * t.n, None]).sum(0) for c in range(t.m)], axis=1))
+    assert stale.mean() < 0.5
+
+
+def test_frozen_step_with_exact_snapshot_equals_first_example_of_sync_training():
+    # With one example and the snapshot equal to the exact vote sums, a frozen
+    # Algorithm-1 step gives every clause of the two trained classes the same
+    # feedback as the standard TM step does.
+    X, y, _, _ = small_problem(q=1)
+    for m in (2, 4):
+        a = O.Oracle(m, 6, 12, 20, 4, 3.0, 8)
+        b = O.Oracle(m, 6, 12, 20, 4, 3.0, 8)
+        tally, ostar = a.sync_tallies(X)
+        a.feedback_step(X, y, tally.copy(), tally, ostar, 0, 0, 1)
+        b.sync_epoch(X, y, 0)
+        assert np.array_equal(a.state, b.state)
+
+
+def test_feedback_only_touches_target_and_negative_class():
+    rng = np.random.default_rng(0)
+    X = rng.integers(0, 2, size=(50, 9), dtype=np.uint8)
+    y = rng.integers(0, 5, size=50).astype(np.int32)
+    t = O.Oracle(5, 4, 9, 10, 6, 2.5, 4)
+    for i in range(50):
+        before = t.state.copy()
+        tally, ostar = t.sync_tallies(X)
+        t.feedback_step(X, y, tally.copy(), tally, ostar, 3, i, 1)
+        changed = {g // t.n for g in range(t.C) if not np.array_equal(before[g], t.state[g])}
+        assert changed <= {int(y[i]), t.neg_class(3, i, int(y[i]))}
+
+
+def test_type2_only_for_mismatched_polarity_and_type1_otherwise():
+    # s = 1 makes Type I purely decreasing and Type II is purely increasing,
+    # so the direction of every change tells which feedback a clause received.
+    rng = np.random.default_rng(2)
+    X = rng.integers(0, 2, size=(30, 6), dtype=np.uint8)
+    y = rng.integers(0, 2, size=30).astype(np.int32)
+    t = O.Oracle(2, 6, 6, 10, 50, 1.0, 4)
+    for i in range(30):
+        before = t.state.copy()
+        tally, ostar = t.sync_tallies(X)
+        t.feedback_step(X, y, tally.copy(), tally, ostar, 0, i, 1)
+        for g in range(t.C):
+            c, j = divmod(g, t.n)
+            d = t.state[g] - before[g]
+            target = int(y[i] == c)
+            if target ^ (j & 1):          # Type II: y xor polarity (Algorithm 1)
+                assert np.all(d >= 0)
+            else:
+                assert np.all(d <= 0)
+
+
+def _mean_late_accuracy(step, t, Xte, yte, epochs=60, last=15):
+    accs = []
+    for epoch in range(epochs):
+        step(epoch)
+        if epoch >= epochs - last:
+            accs.append((t.predict(Xte) == yte).mean())
+    return float(np.mean(accs))
+
+
+def test_noisy_xor_is_learned_by_synchronous_training():
+    # 40 % label noise makes single-epoch accuracy fluctuate, so average late epochs
+    Xtr, ytr, Xte, yte = synth.noisy_xor(2000, 2000, seed=99)
+    t = O.Oracle(2, 10, 12, 100, 15, 3.9, 1)
+    acc = _mean_late_accuracy(lambda ep: t.sync_epoch(Xtr, ytr, ep), t, Xte, yte)
+    assert acc > 0.90, acc
+    assert t.state.min() >= 1 and t.state.max() <= 200
+
+
+def test_noisy_xor_is_learned_by_algorithm1_with_stale_tallies():
+    # every clause gates on the tallies as they stood at the start of the epoch
+    Xtr, ytr, Xte, yte = synth.noisy_xor(2000, 2000, seed=99)
+    t = O.Oracle(2, 10, 12, 100, 15, 3.9, 1)
+    tally, ostar = t.sync_tallies(Xtr)
+    acc = _mean_late_accuracy(
+        lambda ep: t.feedback_step(Xtr, ytr, tally.copy(), tally, ostar, ep, 0, len(ytr)), t, Xte, yte)
+    assert acc > 0.90, acc
+
+
+def test_sequential_algorithm1_is_schedule_independent_between_loop_orders():
+    # a clause's visit to example i sees the refreshes of lower-numbered
+    # clauses from this epoch and of the others from the previous one in both
+    # loop orders, so the two sequential schedules coincide exactly
+    Xtr, ytr, _, _ = synth.noisy_xor(300, 10, seed=5)
+    a = O.Oracle(2, 10, 12, 100, 15, 3.9, 1)
+    b = O.Oracle(2, 10, 12, 100, 15, 3.9, 1)
+    ta, oa = a.sync_tallies(Xtr)
+    tb, ob = b.sync_tallies(Xtr)
+    for ep in range(5):
+        a.async_epoch(Xtr, ytr, ta, oa, ep, True)
+        b.async_epoch(Xtr, ytr, tb, ob, ep, False)
+    assert np.array_equal(a.state, b.state) and np.array_equal(ta, tb) and np.array_equal(oa, ob)
