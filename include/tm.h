@@ -1,0 +1,163 @@
+/*
+ * tm.h - C boundary of the asynchronous Tsetlin machine library for gfx950.
+ *
+ * The library implements the data-parallel hot path of "Massively Parallel and
+ * Asynchronous Tsetlin Machine Architecture Supporting Almost Constant-Time
+ * Scaling": clause evaluation over bit-packed literals (Eq. 1), signed voting
+ * (Eq. 2 / Eq. 3), per-example voting tallies (Section 3.1) and the
+ * decentralised clause update of Algorithm 1 with Type I / Type II feedback
+ * (Tables 1 and 2).
+ *
+ * Symbols follow the paper: o Boolean features, 2o literals, m classes,
+ * n clauses per class, C = m*n clauses, 2N states per Tsetlin automaton (TA),
+ * voting margin T, specificity s, q examples.  Wf = ceil(o/32).
+ *
+ * Conventions shared by all entry points
+ *   - Every pointer marked "device" is device memory of the GPU named in
+ *     tm_config.device and is owned by the caller.  The library never
+ *     allocates or frees device memory; it keeps raw pointers between
+ *     tm_create / tm_bind_train and tm_destroy and the caller must keep the
+ *     buffers alive for that time.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Unless stated otherwise a call only enqueues work on that stream and
+ *     returns; results are ready when the stream reaches that point.
+ *   - Features are bit-packed by the caller: X is uint32 [q][Wf], feature k of
+ *     example i is bit (k & 31) of X[i*Wf + (k >> 5)]; padding bits are 0.
+ *   - Clause g = c*n + j belongs to class c and has positive polarity iff j is
+ *     odd (Section 2.1).  Literal k < o is x_k, literal o+k is NOT x_k.
+ *   - Every function returns TM_OK or a negative error code; nothing is
+ *     thrown, printed or aborted.  A handle must not be used from two host
+ *     threads at once.
+ */
+#ifndef TM_H_
+#define TM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    TM_OK = 0,
+    TM_EINVAL = -1, /* bad argument or configuration                        */
+    TM_ESTATE = -2, /* call needs bound training data (tm_bind_train) first */
+    TM_EHIP = -3,   /* a HIP call failed; see tm_last_hip_error             */
+    TM_ELIMIT = -4  /* size outside what the kernels support                */
+};
+
+/* Largest supported number of features (2*ceil(o/32) literal words must fit
+ * the 64 lanes x 20 register slots of one wavefront). */
+#define TM_MAX_FEATURES 20480
+
+typedef struct tm_handle tm_handle; /* opaque */
+
+/* Problem statement of the paper (Section 2.1, Section 2.2, Algorithm 1). */
+typedef struct {
+    int32_t n_classes;         /* m >= 2                                              */
+    int32_t clauses_per_class; /* n, even and >= 2: half positive, half negative      */
+    int32_t n_features;        /* o, 1 .. TM_MAX_FEATURES                             */
+    int32_t states_per_action; /* N, 1 .. 128; a TA has 2N states, Include iff > N    */
+    int32_t T;                 /* voting margin, >= 1                                 */
+    double s;                  /* specificity, >= 1.0                                 */
+    uint64_t seed;             /* key of the counter-based random generator           */
+    int32_t device;            /* HIP device ordinal                                  */
+} tm_config;
+
+/* Size in bytes of the model state buffer (bit-sliced TA states + include
+ * masks) for a configuration.  Host-only computation.  TM_EINVAL / TM_ELIMIT
+ * on a bad configuration. */
+int tm_state_bytes(const tm_config *cfg, size_t *out);
+
+/* Size in bytes of the training workspace for q examples (voting tallies,
+ * previous-output bits - one bit per example per clause -, transposed copy of
+ * X, per-example negative class, counters).  Host-only computation. */
+int tm_train_ws_bytes(const tm_config *cfg, int64_t q, size_t *out);
+
+/* Creates a machine whose state lives in state_buf (device, at least
+ * tm_state_bytes, 256-byte aligned).  Every TA starts at state N or N+1 with
+ * probability 1/2 (the paper does not fix the start).  Enqueues the
+ * initialisation on `stream`. */
+int tm_create(const tm_config *cfg, void *state_buf, void *stream, tm_handle **out);
+
+/* Frees the host-side handle only.  Device buffers stay with the caller. */
+int tm_destroy(tm_handle *h);
+
+/* Binds a training set: X device uint32 [q][Wf], y device int32 [q] with
+ * labels 0..m-1, ws device workspace of tm_train_ws_bytes(cfg, q) bytes
+ * (256-byte aligned).  Builds the transposed copy of X and runs the tally
+ * pre-calculation of Section 3.1 (every clause on every example; fills the
+ * previous-output bits and the tallies).  Synchronises the stream once to
+ * report labels out of range as TM_EINVAL.  q >= 1. */
+int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, void *ws,
+                  void *stream);
+
+/* One pass of Algorithm 1 with batch size b = q over the bound examples: every
+ * clause visits examples 0..q-1 in order, gates on the (possibly outdated)
+ * tally, applies Type I or Type II feedback, re-evaluates, and refreshes tally
+ * and previous-output bit.  Multi-class: class y_i is trained towards 1 and
+ * one other class, drawn per (epoch, example), towards 0.  Advances the
+ * handle's epoch counter (part of the random counter) by one. */
+int tm_fit_epoch(tm_handle *h, void *stream);
+
+/* Eq. 3 per class, clamped to [-T, T]: sums device int32 [q][m].
+ * X need not be the bound training set.  q may be 0. */
+int tm_class_sums(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, void *stream);
+
+/* Classification: pred device int32 [q] = lowest class index attaining the
+ * largest clamped class sum (two classes in one bank, Eq. 2, generalised to
+ * one bank per class).  `sums_scratch` is device int32 [q][m] scratch. */
+int tm_predict(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, int32_t *sums_scratch,
+               void *stream);
+
+/* ---- hooks used by tests, checkpoints and measurements ---------------- */
+
+/* TA states as bytes: device uint8 [C][2o], value = state - 1 (0 .. 2N-1). */
+int tm_get_ta_state(tm_handle *h, uint8_t *out, void *stream);
+/* Inverse of tm_get_ta_state; values above 2N-1 are clamped.  Also rebuilds
+ * the include masks.  Tallies of bound data become outdated (call
+ * tm_sync_tallies). */
+int tm_set_ta_state(tm_handle *h, const uint8_t *in, void *stream);
+
+/* Clause outputs (Eq. 1) as a bit matrix: bits device uint32 [C][ceil(q/32)],
+ * example i of clause g is bit (i & 31) of bits[g*ceil(q/32) + (i >> 5)];
+ * bits beyond q are 0. */
+int tm_clause_outputs(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *bits, void *stream);
+
+/* Re-runs the tally pre-calculation (Section 3.1) on the bound data. */
+int tm_sync_tallies(tm_handle *h, void *stream);
+
+/* Copies the live tallies (unclamped) to out, device int32 [q][m]. */
+int tm_get_tallies(tm_handle *h, int32_t *out, void *stream);
+
+/* Copies the stored previous clause outputs o* of Algorithm 1 to bits, same
+ * layout as tm_clause_outputs for the bound q. */
+int tm_get_prev_outputs(tm_handle *h, uint32_t *bits, void *stream);
+
+/* Algorithm 1 restricted to examples i0 .. i0+cnt-1 with the gate reading a
+ * caller-supplied snapshot (device int32 [q][m]) instead of the live tallies;
+ * refreshes still go to the live tallies.  Uses the current epoch counter
+ * without advancing it.  Same kernel as tm_fit_epoch; results do not depend
+ * on scheduling. */
+int tm_feedback_step(tm_handle *h, const int32_t *tally_snapshot, int64_t i0, int64_t cnt,
+                     void *stream);
+
+/* Epoch counter used for the random counter of the next tm_fit_epoch. */
+int tm_set_epoch(tm_handle *h, uint32_t epoch);
+int tm_get_epoch(tm_handle *h, uint32_t *epoch);
+
+/* Device-side event counters of the training kernel since the last call of
+ * this function (or since tm_bind_train): out is HOST uint64 [4]:
+ * [0] visited (clause, example) pairs, [1] fired gates, [2] Type I feedbacks,
+ * [3] tally changes.  Synchronises the stream. */
+int tm_read_counters(tm_handle *h, uint64_t *out, void *stream);
+
+/* Text for an error code; hipError_t of the last failed HIP call on a handle. */
+const char *tm_strerror(int code);
+int tm_last_hip_error(tm_handle *h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TM_H_ */

@@ -1,0 +1,1031 @@
+// HIP kernels and C boundary of the asynchronous Tsetlin machine (gfx950).
+//
+// Memory layout (all device memory is caller-owned):
+//   state buffer   planes uint32 [C][W][8]  bit-sliced TA counters, W = 2*Wf literal words
+//                  inc    uint32 [C][W]     include masks (= plane 7), compact copy for evaluation
+//   train workspace
+//                  tally  int32  [m][qp]    voting tallies, qp = q rounded up to 64
+//                  ostar  uint32 [C][Qw]    previous clause outputs, 1 bit per (clause, example), Qw = qp/32
+//                  XT     uint32 [Wf][qp]   transposed features (word-major) for lane = example evaluation
+//                  negcls int32  [qp]       class trained towards 0 for each example, this epoch
+//                  counters uint64 [8], flag int32
+//   literal word lw < Wf holds x_(32 lw + j), literal word Wf + fw holds NOT x_(32 fw + j).
+//
+// Two evaluation layouts are used:
+//   k_eval   lane = clause : include masks in VGPRs, example words arrive through
+//            scalar loads, one v_bfi per feature word and pair; clause votes are
+//            summed with wave ballot + popcount (inference, tally pre-calculation).
+//   k_train  one wavefront = one clause (Algorithm 1: "every clause runs in its own
+//            thread"); lane = literal word for feedback, lane = example for the
+//            evaluation of a block of 64 examples.
+#include <hip/hip_runtime.h>
+#include <algorithm>
+#include <math.h>
+#include <new>
+#include <stdint.h>
+#include <string.h>
+
+#include "../../include/tm.h"
+#include "tm_device.hpp"
+
+namespace tsetlin {
+
+struct Dims {
+    int m, n, o, N, T, C, Wf, W;
+    uint32_t thr;      // 16-bit threshold: P(u < thr) = 1/s
+    uint32_t tailmask; // valid bits of the last feature word
+    RngKey key;
+};
+
+// ------------------------------------------------------------------------
+// small utility kernels
+// ------------------------------------------------------------------------
+
+__global__ void k_fill_u32(uint32_t *p, int64_t nwords, uint32_t v)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nwords; i += stride) p[i] = v;
+}
+
+// Initial TA states: state N or N+1 with probability 1/2, i.e. stored value
+// 127 or 128.  One thread per (clause, literal word).
+__global__ void k_init_state(Dims d, uint32_t *planes, uint32_t *inc)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)d.C * d.W) return;
+    const int g = (int)(t / d.W);
+    const int lw = (int)(t - (int64_t)g * d.W);
+    const int fw = lw >= d.Wf ? lw - d.Wf : lw;
+    const uint32_t valid = (fw == d.Wf - 1) ? d.tailmask : ~0u;
+    const U4 r = draw(d.key, STREAM_INIT, 4u * (uint32_t)lw, (uint32_t)g, 0, 0);
+    const uint32_t top = r.x & valid;
+    uint32_t *p = planes + t * 8;
+#pragma unroll
+    for (int b = 0; b < 7; ++b) p[b] = ~top;
+    p[7] = top;
+    inc[t] = top;
+}
+
+// bytes (state - 1) -> bit planes; one thread per (clause, literal word)
+__global__ void k_set_state(Dims d, const uint8_t *in, uint32_t *planes, uint32_t *inc)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)d.C * d.W) return;
+    const int g = (int)(t / d.W);
+    const int lw = (int)(t - (int64_t)g * d.W);
+    const bool neg = lw >= d.Wf;
+    const int fw = neg ? lw - d.Wf : lw;
+    uint32_t p[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const uint8_t *row = in + (int64_t)g * 2 * d.o + (neg ? d.o : 0);
+    for (int j = 0; j < 32; ++j) {
+        const int f = fw * 32 + j;
+        uint32_t stored = 127u; // padding automata: excluded, never touched
+        if (f < d.o) {
+            uint32_t v = row[f];
+            if (v > (uint32_t)(2 * d.N - 1)) v = (uint32_t)(2 * d.N - 1);
+            stored = v + (uint32_t)(128 - d.N);
+        }
+#pragma unroll
+        for (int b = 0; b < 8; ++b) p[b] |= ((stored >> b) & 1u) << j;
+    }
+#pragma unroll
+    for (int b = 0; b < 8; ++b) planes[t * 8 + b] = p[b];
+    inc[t] = p[7];
+}
+
+__global__ void k_get_state(Dims d, const uint32_t *planes, uint8_t *out)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)d.C * d.W) return;
+    const int g = (int)(t / d.W);
+    const int lw = (int)(t - (int64_t)g * d.W);
+    const bool neg = lw >= d.Wf;
+    const int fw = neg ? lw - d.Wf : lw;
+    uint32_t p[8];
+#pragma unroll
+    for (int b = 0; b < 8; ++b) p[b] = planes[t * 8 + b];
+    uint8_t *row = out + (int64_t)g * 2 * d.o + (neg ? d.o : 0);
+    for (int j = 0; j < 32; ++j) {
+        const int f = fw * 32 + j;
+        if (f >= d.o) break;
+        uint32_t stored = 0;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) stored |= ((p[b] >> j) & 1u) << b;
+        row[f] = (uint8_t)(stored - (uint32_t)(128 - d.N));
+    }
+}
+
+// XT[fw][i] = X[i][fw], zero for q <= i < qp
+__global__ void k_transpose_x(const uint32_t *X, uint32_t *XT, int64_t q, int64_t qp, int Wf)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= qp * Wf) return;
+    const int fw = (int)(t / qp);
+    const int64_t i = t - (int64_t)fw * qp;
+    XT[t] = (i < q) ? X[i * Wf + fw] : 0u;
+}
+
+__global__ void k_check_labels(const int32_t *y, int64_t q, int m, int32_t *flag)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < q && (y[i] < 0 || y[i] >= m)) *flag = 1;
+}
+
+// The class trained towards output 0 for example i in this epoch: uniform over
+// the m-1 classes other than y_i, a function of (seed, epoch, i) only so that
+// all clauses agree without communicating.
+__global__ void k_negcls(Dims d, const int32_t *y, int32_t *negcls, int64_t q, int64_t qp, uint32_t epoch)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= qp) return;
+    int32_t r = -1;
+    if (i < q) {
+        const U4 u = draw(d.key, STREAM_NEGCLASS, 0, 0, (uint64_t)i, epoch);
+        const int32_t dd = (int32_t)(((uint64_t)u.x * (uint64_t)(d.m - 1)) >> 32);
+        r = dd + (dd >= y[i] ? 1 : 0);
+    }
+    negcls[i] = r;
+}
+
+// sums[i][c] = clamp(sums[i][c], -T, T)
+__global__ void k_clamp(int32_t *sums, int64_t n, int T)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n) sums[t] = min(max(sums[t], -T), T);
+}
+
+// pred[i] = lowest class index with the largest (already clamped) sum
+__global__ void k_argmax(const int32_t *sums, int32_t *pred, int64_t q, int m)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= q) return;
+    int best = 0;
+    int32_t bv = sums[i * m];
+    for (int c = 1; c < m; ++c) {
+        const int32_t v = sums[i * m + c];
+        if (v > bv) {
+            bv = v;
+            best = c;
+        }
+    }
+    pred[i] = best;
+}
+
+// out[i][c] = tally[c][i]
+__global__ void k_tally_out(const int32_t *tally, int32_t *out, int64_t q, int64_t qp, int m)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= q * m) return;
+    const int64_t i = t / m;
+    const int c = (int)(t - i * m);
+    out[t] = tally[(int64_t)c * qp + i];
+}
+
+// dst[g][0..words) = src[g][0..words) for row strides that differ
+__global__ void k_copy_rows(const uint32_t *src, int64_t src_stride, uint32_t *dst, int64_t dst_stride,
+                            int64_t rows, int64_t words)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= rows * words) return;
+    const int64_t r = t / words, w = t - r * words;
+    dst[r * dst_stride + w] = src[r * src_stride + w];
+}
+
+// ------------------------------------------------------------------------
+// k_eval: clause evaluation, lane = clause   (Eq. 1, Eq. 3, Section 3.1)
+// ------------------------------------------------------------------------
+
+// inc  [C][W] include masks, X [q][Wf] examples (both read-only, passed as
+// restrict kernel arguments so that the example words can be fetched with
+// scalar loads); bits [C][bits_stride] clause outputs or null; signed vote
+// sums are atomically added to acc[i*acc_si + c*acc_sc] unless acc is null.
+struct EvalArgs {
+    int64_t q;
+    int Wf, W, C, n, m;
+    int64_t bits_stride;
+    int64_t acc_si, acc_sc;
+    int64_t ex_per_wave; // multiple of 256
+};
+
+// A wavefront owns 64 consecutive clauses (a "tile") and a range of examples.
+// CH feature words of the include masks (plain and negated half) sit in
+// 2*CH VGPRs per lane; the words of one example are wave-uniform and come in
+// through scalar loads, so the violation test of a feature word,
+//   (inc_neg & x) | (inc_pos & ~x),
+// is a single v_bfi_b32 with x as the scalar selector.  A lane keeps one
+// "violated" flag bit per example for a batch of 256 examples; this is what
+// lets masks wider than the register budget be streamed in chunks.
+template <int CH>
+__global__ __launch_bounds__(64) void k_eval(const uint32_t *__restrict__ inc, const uint32_t *__restrict__ X,
+                                             uint32_t *__restrict__ bits, int32_t *__restrict__ acc,
+                                             const EvalArgs a)
+{
+    const int lane = threadIdx.x;
+    const int tile = blockIdx.x;
+    const int g = tile * 64 + lane;
+    const bool gv = g < a.C;
+    const int64_t e_begin = (int64_t)blockIdx.y * a.ex_per_wave;
+    const int64_t e_end = min(a.q, e_begin + a.ex_per_wave);
+    if (e_begin >= e_end) return;
+
+    const int nch = (a.Wf + CH - 1) / CH;
+    const uint32_t *mrow = inc + (int64_t)(gv ? g : 0) * a.W;
+    uint32_t mp[CH], mn[CH];
+
+    auto load_masks = [&](int w0) {
+#pragma unroll
+        for (int w = 0; w < CH; ++w) {
+            const bool ok = gv && (w0 + w < a.Wf);
+            mp[w] = ok ? mrow[w0 + w] : 0u;
+            mn[w] = ok ? mrow[a.Wf + w0 + w] : 0u;
+        }
+    };
+    if (nch == 1) load_masks(0);
+
+    const int g_first = tile * 64;
+    const int g_last = min(a.C, g_first + 64) - 1;
+    const int c_first = g_first / a.n, c_last = g_last / a.n;
+    const int my_class = gv ? g / a.n : -1;
+
+    for (int64_t b0 = e_begin; b0 < e_end; b0 += 256) {
+        const int nb = (int)min((int64_t)256, e_end - b0);
+        uint32_t flags[8];
+#pragma unroll
+        for (int fb = 0; fb < 8; ++fb) flags[fb] = 0;
+
+        for (int ch = 0; ch < nch; ++ch) {
+            const int w0 = ch * CH;
+            if (nch > 1) load_masks(w0);
+            const bool full = (w0 + CH <= a.Wf);
+#pragma unroll
+            for (int fb = 0; fb < 8; ++fb) {
+                const int ne = min(32, nb - fb * 32);
+                for (int e = 0; e < ne; ++e) {
+                    const uint32_t *xr = X + (b0 + fb * 32 + e) * a.Wf + w0; // wave-uniform
+                    uint32_t viol = 0;
+                    if (full) {
+#pragma unroll
+                        for (int w = 0; w < CH; ++w) {
+                            const uint32_t x = xr[w];
+                            viol |= (x & mn[w]) | (~x & mp[w]);
+                        }
+                    } else {
+#pragma unroll
+                        for (int w = 0; w < CH; ++w) {
+                            if (w0 + w < a.Wf) {
+                                const uint32_t x = xr[w];
+                                viol |= (x & mn[w]) | (~x & mp[w]);
+                            }
+                        }
+                    }
+                    flags[fb] |= (viol != 0) ? (1u << e) : 0u;
+                }
+            }
+        }
+
+        if (bits) {
+#pragma unroll
+            for (int fb = 0; fb < 8; ++fb) {
+                const int ne = min(32, nb - fb * 32);
+                if (ne > 0 && gv) {
+                    const uint32_t lowmask = ne >= 32 ? ~0u : ((1u << ne) - 1u);
+                    bits[(int64_t)g * a.bits_stride + (b0 >> 5) + fb] = ~flags[fb] & lowmask;
+                }
+            }
+        }
+
+        if (acc) {
+            for (int cc = c_first; cc <= c_last; ++cc) {
+                const uint64_t cm = ballot(my_class == cc);
+                const uint64_t cmpos = cm & 0xAAAAAAAAAAAAAAAAull; // odd index within class: positive polarity
+                const uint64_t cmneg = cm & 0x5555555555555555ull;
+                int accv[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int fb = 0; fb < 8; ++fb) {
+                    const int ne = min(32, nb - fb * 32);
+                    for (int e = 0; e < ne; ++e) {
+                        const uint64_t sat = ballot(((flags[fb] >> e) & 1u) == 0u);
+                        const int s = __builtin_popcountll(sat & cmpos) - __builtin_popcountll(sat & cmneg);
+                        accv[fb >> 1] = (lane == (fb & 1) * 32 + e) ? s : accv[fb >> 1];
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int64_t i = b0 + k * 64 + lane;
+                    if (i < e_end && accv[k] != 0) atomicAdd(acc + i * a.acc_si + (int64_t)cc * a.acc_sc, accv[k]);
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------
+// k_train: Algorithm 1, one wavefront per clause
+// ------------------------------------------------------------------------
+
+struct TrainArgs {
+    Dims d;
+    SatConst sat;
+    uint32_t *planes;
+    uint32_t *inc;
+    int32_t *tally;
+    const int32_t *vhat; // [q][m] snapshot the gate reads instead of the live tally, or null
+    uint32_t *ostar;
+    unsigned long long *counters;
+    int64_t q, qp, Qw, i_begin, i_end;
+    uint32_t epoch;
+};
+
+// Clause outputs for the 64 examples i0 .. i0+63, lane = example: bit l of the
+// result is C(X_{i0+l}) for the include masks currently held in plane 7 of the
+// calling wavefront (lane = literal word).  Only non-zero mask words are
+// visited; the loop stops as soon as all 64 examples are violated.
+template <int WPL>
+__device__ __forceinline__ uint64_t eval64(const uint32_t (&p)[WPL][8], const uint32_t *__restrict__ XT,
+                                           int64_t qp, int64_t i0, int lane, int Wf)
+{
+    uint32_t viol = 0;
+    bool dead = false;
+    const uint32_t *col = XT + i0 + lane;
+#pragma unroll
+    for (int r = 0; r < WPL; ++r) {
+        uint64_t nz = ballot(p[r][7] != 0u);
+        while (nz != 0 && !dead) {
+            int l[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { // a repeated word is harmless (OR is idempotent)
+                l[k] = __builtin_ctzll(nz);
+                const uint64_t rest = nz & (nz - 1);
+                nz = rest ? rest : nz;
+                if (k == 3) nz = rest;
+            }
+            uint32_t x[4], M[4], flip[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int lw = r * 64 + l[k];
+                const bool neg = lw >= Wf;
+                const int fw = neg ? lw - Wf : lw;
+                M[k] = readlane(p[r][7], l[k]);
+                flip[k] = neg ? 0u : ~0u; // plain literal violated where x = 0, negated where x = 1
+                x[k] = col[(int64_t)fw * qp];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) viol |= M[k] & (x[k] ^ flip[k]);
+            dead = (ballot(viol == 0u) == 0);
+        }
+    }
+    return ballot(viol == 0u);
+}
+
+template <int WPL, bool FULL>
+__global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
+                                              const int32_t *__restrict__ y, const int32_t *__restrict__ negcls,
+                                              const TrainArgs a)
+{
+    const Dims &d = a.d;
+    const int lane = threadIdx.x;
+    const int g = blockIdx.x;
+    const int c = g / d.n;
+    const bool pos = ((g - c * d.n) & 1) != 0; // odd index within the class: positive polarity
+    const int sign = pos ? 1 : -1;
+    const int T = d.T;
+
+    uint32_t p[WPL][8];
+#pragma unroll
+    for (int r = 0; r < WPL; ++r) {
+        const int lw = r * 64 + lane;
+        if (lw < d.W) {
+            const uint4 *src = reinterpret_cast<const uint4 *>(a.planes + ((int64_t)g * d.W + lw) * 8);
+            const uint4 v0 = src[0], v1 = src[1];
+            p[r][0] = v0.x; p[r][1] = v0.y; p[r][2] = v0.z; p[r][3] = v0.w;
+            p[r][4] = v1.x; p[r][5] = v1.y; p[r][6] = v1.z; p[r][7] = v1.w;
+        } else {
+#pragma unroll
+            for (int b = 0; b < 8; ++b) p[r][b] = 0u;
+        }
+    }
+
+    // lowest Philox block of the Type I comparator that can matter: bits of the
+    // uniform below the lowest set bit of thr never decide u < thr
+    const int tz = d.thr ? __builtin_ctz(d.thr) : 16;
+    const int first_blk = min(tz >> 2, 4);
+    const uint32_t ge_init = d.thr >= 65536u ? 0u : ~0u;
+
+    unsigned long long n_pairs = 0, n_fired = 0, n_type1 = 0, n_changes = 0;
+
+    for (int64_t i0 = a.i_begin & ~(int64_t)63; i0 < a.i_end; i0 += 64) {
+        const int64_t i = i0 + lane;
+        const bool inr = i >= a.i_begin && i < a.i_end;
+        int yi = -1, ng = -1;
+        if (inr) {
+            yi = y[i];
+            ng = negcls[i];
+        }
+        const bool target = (yi == c);
+        const bool cand = inr && (target || ng == c);
+        bool fire = false;
+        if (cand) {
+            const int v = a.vhat ? a.vhat[i * d.m + c]
+                                 : __hip_atomic_load(&a.tally[(int64_t)c * a.qp + i], __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+            const int vc = min(max(v, -T), T);
+            const int e = target ? T - vc : T + vc; // Algorithm 1: error of the recorded vote sum
+            if (e > 0) {
+                const U4 r = draw(d.key, STREAM_GATE, 0, (uint32_t)g, (uint64_t)i, a.epoch);
+                fire = (uint64_t)r.x * (uint64_t)(2 * (int64_t)T) < ((uint64_t)e << 32);
+            }
+        }
+        uint64_t fmask = ballot(fire);
+        const uint64_t tmask = ballot(target);
+        const uint64_t rmask = ballot(inr);
+        n_pairs += __builtin_popcountll(rmask);
+        n_fired += __builtin_popcountll(fmask);
+
+        uint64_t obits = eval64<WPL>(p, XT, a.qp, i0, lane, d.Wf);
+
+        while (fmask) {
+            const int l = __builtin_ctzll(fmask);
+            fmask &= fmask - 1;
+            const int64_t ii = i0 + l;
+            const bool tgt = (tmask >> l) & 1;
+            const bool Cout = (obits >> l) & 1; // clause output on the state before the update
+            const uint32_t *xrow = X + ii * d.Wf;
+            uint32_t changed = 0;
+            if (tgt != pos) {
+                // Type II feedback (Table 2): where the clause is 1 and the literal 0, push Exclude towards Include
+                if (Cout) {
+#pragma unroll
+                    for (int r = 0; r < WPL; ++r) {
+                        const int lw = r * 64 + lane;
+                        const bool act = lw < d.W;
+                        const bool neg = lw >= d.Wf;
+                        const int fw = act ? (neg ? lw - d.Wf : lw) : 0;
+                        const uint32_t valid = act ? (fw == d.Wf - 1 ? d.tailmask : ~0u) : 0u;
+                        const uint32_t lit = (xrow[fw] ^ (neg ? ~0u : 0u)) & valid;
+                        const uint32_t m = ~lit & ~p[r][7] & valid; // excluded automata (below the top bit) cannot overflow
+                        const uint32_t old7 = p[r][7];
+                        ripple_inc(p[r], m);
+                        changed |= p[r][7] ^ old7;
+                    }
+                }
+            } else {
+                // Type I feedback (Table 1)
+                ++n_type1;
+#pragma unroll
+                for (int r = 0; r < WPL; ++r) {
+                    const int lw = r * 64 + lane;
+                    const bool act = lw < d.W;
+                    const bool neg = lw >= d.Wf;
+                    const int fw = act ? (neg ? lw - d.Wf : lw) : 0;
+                    const uint32_t valid = act ? (fw == d.Wf - 1 ? d.tailmask : ~0u) : 0u;
+                    const uint32_t lit = (xrow[fw] ^ (neg ? ~0u : 0u)) & valid;
+                    // bit-sliced comparison of 32 16-bit uniforms with thr, least significant bit first:
+                    // ge = [u >= thr]; bit b of literal j's uniform is bit j of random word b
+                    uint32_t ge = ge_init;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        if (t >= first_blk) {
+                            const U4 R = draw(d.key, STREAM_TYPE1, 4u * (uint32_t)lw + (uint32_t)t, (uint32_t)g,
+                                              (uint64_t)ii, a.epoch);
+                            const uint32_t w[4] = {R.x, R.y, R.z, R.w};
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                const uint32_t K = ((d.thr >> (4 * t + k)) & 1u) ? 0u : ~0u;
+                                const uint32_t df = w[k] ^ ge; // majority(w, ge, K): thr bit 1 -> w & ge, 0 -> w | ge
+                                ge = (df & K) | (~df & w[k]);
+                            }
+                        }
+                    }
+                    const uint32_t old7 = p[r][7];
+                    if (Cout) { // strong: literals that are 1 move towards Include with probability (s-1)/s
+                        const uint32_t m = lit & ge & ~at_value<FULL>(p[r], a.sat.kmax, true);
+                        ripple_inc(p[r], m);
+                    }
+                    // weak: everything else moves towards Exclude with probability 1/s
+                    const uint32_t wk = (Cout ? ~lit : ~0u) & ~ge & valid & ~at_value<FULL>(p[r], a.sat.kmin, false);
+                    ripple_dec(p[r], wk);
+                    changed |= p[r][7] ^ old7;
+                }
+            }
+            if (ballot(changed != 0u)) { // the conjunction changed: re-evaluate this and the later examples
+                const uint64_t nb = eval64<WPL>(p, XT, a.qp, i0, lane, d.Wf);
+                const uint64_t keep = (1ull << l) - 1ull;
+                obits = (obits & keep) | (nb & ~keep);
+            }
+        }
+
+        // refresh of tally and previous-output bits (last lines of Algorithm 1)
+        uint32_t *op = a.ostar + (int64_t)g * a.Qw + (i0 >> 5);
+        const uint64_t ost = (uint64_t)op[0] | ((uint64_t)op[1] << 32);
+        const uint64_t diff = (obits ^ ost) & rmask;
+        if (diff) {
+            if ((diff >> lane) & 1ull) {
+                const int delta = ((obits >> lane) & 1ull) ? sign : -sign;
+                atomicAdd(&a.tally[(int64_t)c * a.qp + i], delta);
+            }
+            const uint64_t nw = ost ^ diff;
+            if (lane == 0) {
+                op[0] = (uint32_t)nw;
+                op[1] = (uint32_t)(nw >> 32);
+            }
+            n_changes += __builtin_popcountll(diff);
+        }
+    }
+
+#pragma unroll
+    for (int r = 0; r < WPL; ++r) {
+        const int lw = r * 64 + lane;
+        if (lw < d.W) {
+            uint4 *dst = reinterpret_cast<uint4 *>(a.planes + ((int64_t)g * d.W + lw) * 8);
+            dst[0] = make_uint4(p[r][0], p[r][1], p[r][2], p[r][3]);
+            dst[1] = make_uint4(p[r][4], p[r][5], p[r][6], p[r][7]);
+            a.inc[(int64_t)g * d.W + lw] = p[r][7];
+        }
+    }
+    if (lane == 0) {
+        atomicAdd(&a.counters[0], n_pairs);
+        atomicAdd(&a.counters[1], n_fired);
+        atomicAdd(&a.counters[2], n_type1);
+        atomicAdd(&a.counters[3], n_changes);
+    }
+}
+
+} // namespace tsetlin
+
+// ------------------------------------------------------------------------
+// host side: handle, validation, launches
+// ------------------------------------------------------------------------
+
+using namespace tsetlin;
+
+struct tm_handle {
+    tm_config cfg;
+    Dims d;
+    SatConst sat;
+    uint32_t *planes;
+    uint32_t *inc;
+    // bound training data
+    bool bound;
+    const uint32_t *X;
+    const int32_t *y;
+    int64_t q, qp, Qw;
+    int32_t *tally;
+    uint32_t *ostar;
+    uint32_t *XT;
+    int32_t *negcls;
+    unsigned long long *counters;
+    int32_t *flag;
+    uint32_t epoch;
+    int last_hip;
+};
+
+namespace {
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+int check_config(const tm_config *cfg)
+{
+    if (!cfg) return TM_EINVAL;
+    if (cfg->n_classes < 2 || cfg->clauses_per_class < 2 || (cfg->clauses_per_class & 1)) return TM_EINVAL;
+    if (cfg->n_features < 1) return TM_EINVAL;
+    if (cfg->states_per_action < 1 || cfg->states_per_action > 128) return TM_EINVAL;
+    if (cfg->T < 1 || cfg->T > (1 << 29)) return TM_EINVAL;
+    if (!(cfg->s >= 1.0) || !isfinite(cfg->s)) return TM_EINVAL;
+    if (cfg->device < 0) return TM_EINVAL;
+    if (cfg->n_features > TM_MAX_FEATURES) return TM_ELIMIT;
+    if ((int64_t)cfg->n_classes * cfg->clauses_per_class > (int64_t)1 << 30) return TM_ELIMIT;
+    return TM_OK;
+}
+
+Dims make_dims(const tm_config *cfg)
+{
+    Dims d;
+    d.m = cfg->n_classes;
+    d.n = cfg->clauses_per_class;
+    d.o = cfg->n_features;
+    d.N = cfg->states_per_action;
+    d.T = cfg->T;
+    d.C = d.m * d.n;
+    d.Wf = (d.o + 31) / 32;
+    d.W = 2 * d.Wf;
+    double t = floor(65536.0 / cfg->s + 0.5); // P(u < thr) = 1/s at 16-bit resolution
+    if (t < 0.0) t = 0.0;
+    if (t > 65536.0) t = 65536.0;
+    d.thr = (uint32_t)t;
+    d.tailmask = (d.o & 31) ? ((1u << (d.o & 31)) - 1u) : ~0u;
+    d.key.seed_lo = (uint32_t)(cfg->seed & 0xffffffffu);
+    d.key.seed_hi = (uint32_t)(cfg->seed >> 32);
+    return d;
+}
+
+struct WsLayout {
+    size_t tally, ostar, xt, negcls, counters, flag, total;
+};
+
+WsLayout ws_layout(const Dims &d, int64_t q)
+{
+    const int64_t qp = (q + 63) & ~(int64_t)63;
+    const int64_t Qw = qp / 32;
+    WsLayout L;
+    size_t off = 0;
+    L.tally = off; off += align256((size_t)d.m * qp * 4);
+    L.ostar = off; off += align256((size_t)d.C * Qw * 4);
+    L.xt = off; off += align256((size_t)d.Wf * qp * 4);
+    L.negcls = off; off += align256((size_t)qp * 4);
+    L.counters = off; off += 256;
+    L.flag = off; off += 256;
+    L.total = off;
+    return L;
+}
+
+inline int hip_fail(tm_handle *h, hipError_t e)
+{
+    if (h) h->last_hip = (int)e;
+    return TM_EHIP;
+}
+
+#define TM_HIP(h, expr)                                  \
+    do {                                                 \
+        hipError_t e_ = (expr);                          \
+        if (e_ != hipSuccess) return hip_fail((h), e_);  \
+    } while (0)
+
+inline unsigned blocks_for(int64_t n, int bs) { return (unsigned)((n + bs - 1) / bs); }
+
+int fill(tm_handle *h, void *p, size_t bytes, uint32_t v, hipStream_t st)
+{
+    const int64_t nw = (int64_t)(bytes / 4);
+    if (nw == 0) return TM_OK;
+    const unsigned nb = (unsigned)std::min<int64_t>(4096, (nw + 255) / 256);
+    hipLaunchKernelGGL(k_fill_u32, dim3(nb), dim3(256), 0, st, (uint32_t *)p, nw, v);
+    TM_HIP(h, hipGetLastError());
+    return TM_OK;
+}
+
+struct EvalPtrs {
+    const uint32_t *inc, *X;
+    uint32_t *bits;
+    int32_t *acc;
+};
+
+template <int CH>
+void launch_eval_t(const EvalPtrs &p, const EvalArgs &a, dim3 grid, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_eval<CH>, grid, dim3(64), 0, st, p.inc, p.X, p.bits, p.acc, a);
+}
+
+// Evaluation of all clauses on q examples; writes bits and/or accumulates sums.
+int launch_eval(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *bits, int64_t bits_stride, int32_t *acc,
+                int64_t acc_si, int64_t acc_sc, hipStream_t st)
+{
+    if (q == 0) return TM_OK;
+    const Dims &d = h->d;
+    EvalArgs a;
+    const EvalPtrs p{h->inc, X, bits, acc};
+    a.q = q; a.Wf = d.Wf; a.W = d.W; a.C = d.C; a.n = d.n; a.m = d.m;
+    a.bits_stride = bits_stride; a.acc_si = acc_si; a.acc_sc = acc_sc;
+    const int64_t tiles = (d.C + 63) / 64;
+    const int64_t max_ranges = (q + 255) / 256;
+    int64_t ranges = (8192 + tiles - 1) / tiles;
+    if (ranges > max_ranges) ranges = max_ranges;
+    if (ranges > 65535) ranges = 65535;
+    if (ranges < 1) ranges = 1;
+    int64_t epw = (q + ranges - 1) / ranges;
+    epw = (epw + 255) & ~(int64_t)255;
+    ranges = (q + epw - 1) / epw;
+    a.ex_per_wave = epw;
+    const dim3 grid((unsigned)tiles, (unsigned)ranges);
+    const int Wf = d.Wf;
+    if (Wf <= 1) launch_eval_t<1>(p, a, grid, st);
+    else if (Wf <= 2) launch_eval_t<2>(p, a, grid, st);
+    else if (Wf <= 4) launch_eval_t<4>(p, a, grid, st);
+    else if (Wf <= 8) launch_eval_t<8>(p, a, grid, st);
+    else if (Wf <= 12) launch_eval_t<12>(p, a, grid, st);
+    else if (Wf <= 16) launch_eval_t<16>(p, a, grid, st);
+    else if (Wf <= 20) launch_eval_t<20>(p, a, grid, st);
+    else if (Wf <= 25) launch_eval_t<25>(p, a, grid, st);
+    else launch_eval_t<32>(p, a, grid, st);
+    TM_HIP(h, hipGetLastError());
+    return TM_OK;
+}
+
+struct TrainPtrs {
+    const uint32_t *X, *XT;
+    const int32_t *y, *negcls;
+};
+
+template <int WPL>
+void launch_train_t(const TrainPtrs &p, const TrainArgs &a, bool full, hipStream_t st)
+{
+    if (full) hipLaunchKernelGGL((k_train<WPL, true>), dim3(a.d.C), dim3(64), 0, st, p.X, p.XT, p.y, p.negcls, a);
+    else hipLaunchKernelGGL((k_train<WPL, false>), dim3(a.d.C), dim3(64), 0, st, p.X, p.XT, p.y, p.negcls, a);
+}
+
+int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_end, hipStream_t st)
+{
+    const Dims &d = h->d;
+    TrainArgs a;
+    const TrainPtrs p{h->X, h->XT, h->y, h->negcls};
+    a.d = d; a.sat = h->sat; a.planes = h->planes; a.inc = h->inc; a.tally = h->tally; a.vhat = vhat; a.ostar = h->ostar; a.counters = h->counters;
+    a.q = h->q; a.qp = h->qp; a.Qw = h->Qw; a.i_begin = i_begin; a.i_end = i_end; a.epoch = h->epoch;
+    const bool full = (d.N == 128);
+    const int wpl = (d.W + 63) / 64;
+    if (wpl <= 1) launch_train_t<1>(p, a, full, st);
+    else if (wpl <= 2) launch_train_t<2>(p, a, full, st);
+    else if (wpl <= 3) launch_train_t<3>(p, a, full, st);
+    else if (wpl <= 4) launch_train_t<4>(p, a, full, st);
+    else if (wpl <= 6) launch_train_t<6>(p, a, full, st);
+    else if (wpl <= 8) launch_train_t<8>(p, a, full, st);
+    else if (wpl <= 10) launch_train_t<10>(p, a, full, st);
+    else if (wpl <= 12) launch_train_t<12>(p, a, full, st);
+    else if (wpl <= 16) launch_train_t<16>(p, a, full, st);
+    else if (wpl <= 20) launch_train_t<20>(p, a, full, st);
+    else return TM_ELIMIT;
+    TM_HIP(h, hipGetLastError());
+    return TM_OK;
+}
+
+int run_negcls(tm_handle *h, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_negcls, dim3(blocks_for(h->qp, 256)), dim3(256), 0, st, h->d, h->y, h->negcls, h->q,
+                       h->qp, h->epoch);
+    TM_HIP(h, hipGetLastError());
+    return TM_OK;
+}
+
+int sync_tallies(tm_handle *h, hipStream_t st)
+{
+    const Dims &d = h->d;
+    int rc = fill(h, h->tally, (size_t)d.m * h->qp * 4, 0u, st);
+    if (rc) return rc;
+    return launch_eval(h, h->X, h->q, h->ostar, h->Qw, h->tally, 1, h->qp, st);
+}
+
+} // namespace
+
+extern "C" {
+
+int tm_state_bytes(const tm_config *cfg, size_t *out)
+{
+    const int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!out) return TM_EINVAL;
+    const Dims d = make_dims(cfg);
+    *out = align256((size_t)d.C * d.W * 8 * 4) + align256((size_t)d.C * d.W * 4);
+    return TM_OK;
+}
+
+int tm_train_ws_bytes(const tm_config *cfg, int64_t q, size_t *out)
+{
+    const int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!out || q < 1) return TM_EINVAL;
+    *out = ws_layout(make_dims(cfg), q).total;
+    return TM_OK;
+}
+
+int tm_create(const tm_config *cfg, void *state_buf, void *stream, tm_handle **out)
+{
+    const int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!state_buf || !out || ((uintptr_t)state_buf & 255)) return TM_EINVAL;
+    tm_handle *h = new (std::nothrow) tm_handle;
+    if (!h) return TM_EINVAL;
+    memset(h, 0, sizeof(*h));
+    h->cfg = *cfg;
+    h->d = make_dims(cfg);
+    const uint32_t top = (uint32_t)(127 + h->d.N), bottom = (uint32_t)(128 - h->d.N);
+    for (int b = 0; b < 8; ++b) {
+        h->sat.kmax[b] = ((top >> b) & 1u) ? 0u : ~0u;
+        h->sat.kmin[b] = ((bottom >> b) & 1u) ? 0u : ~0u;
+    }
+    h->planes = (uint32_t *)state_buf;
+    h->inc = (uint32_t *)((char *)state_buf + align256((size_t)h->d.C * h->d.W * 8 * 4));
+    hipError_t e = hipSetDevice(cfg->device);
+    if (e != hipSuccess) {
+        delete h;
+        return TM_EHIP;
+    }
+    const int64_t nt = (int64_t)h->d.C * h->d.W;
+    hipLaunchKernelGGL(k_init_state, dim3(blocks_for(nt, 256)), dim3(256), 0, (hipStream_t)stream, h->d, h->planes,
+                       h->inc);
+    e = hipGetLastError();
+    if (e != hipSuccess) {
+        delete h;
+        return TM_EHIP;
+    }
+    *out = h;
+    return TM_OK;
+}
+
+int tm_destroy(tm_handle *h)
+{
+    if (!h) return TM_EINVAL;
+    delete h;
+    return TM_OK;
+}
+
+int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, void *ws, void *stream)
+{
+    if (!h || !X || !y || !ws || q < 1 || ((uintptr_t)ws & 255)) return TM_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    const Dims &d = h->d;
+    const WsLayout L = ws_layout(d, q);
+    char *base = (char *)ws;
+    h->bound = false;
+    h->X = X; h->y = y; h->q = q;
+    h->qp = (q + 63) & ~(int64_t)63;
+    h->Qw = h->qp / 32;
+    h->tally = (int32_t *)(base + L.tally);
+    h->ostar = (uint32_t *)(base + L.ostar);
+    h->XT = (uint32_t *)(base + L.xt);
+    h->negcls = (int32_t *)(base + L.negcls);
+    h->counters = (unsigned long long *)(base + L.counters);
+    h->flag = (int32_t *)(base + L.flag);
+
+    int rc = fill(h, h->flag, 256, 0u, st);
+    if (rc) return rc;
+    rc = fill(h, h->counters, 256, 0u, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_check_labels, dim3(blocks_for(q, 256)), dim3(256), 0, st, y, q, d.m, h->flag);
+    TM_HIP(h, hipGetLastError());
+    int32_t bad = 0;
+    TM_HIP(h, hipMemcpyAsync(&bad, h->flag, sizeof(bad), hipMemcpyDeviceToHost, st));
+    TM_HIP(h, hipStreamSynchronize(st));
+    if (bad) return TM_EINVAL;
+
+    rc = fill(h, h->ostar, (size_t)d.C * h->Qw * 4, 0u, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_transpose_x, dim3(blocks_for(h->qp * d.Wf, 256)), dim3(256), 0, st, X, h->XT, q, h->qp,
+                       d.Wf);
+    TM_HIP(h, hipGetLastError());
+    h->bound = true;
+    rc = run_negcls(h, st);
+    if (rc) return rc;
+    return sync_tallies(h, st);
+}
+
+int tm_fit_epoch(tm_handle *h, void *stream)
+{
+    if (!h) return TM_EINVAL;
+    if (!h->bound) return TM_ESTATE;
+    if (h->epoch >= (1u << 24)) return TM_ELIMIT;
+    hipStream_t st = (hipStream_t)stream;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    int rc = run_negcls(h, st);
+    if (rc) return rc;
+    rc = launch_train(h, nullptr, 0, h->q, st);
+    if (rc) return rc;
+    h->epoch += 1;
+    return TM_OK;
+}
+
+int tm_feedback_step(tm_handle *h, const int32_t *tally_snapshot, int64_t i0, int64_t cnt, void *stream)
+{
+    if (!h || !tally_snapshot || i0 < 0 || cnt < 0) return TM_EINVAL;
+    if (!h->bound) return TM_ESTATE;
+    if (i0 > h->q) return TM_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    const int64_t i_end = (cnt > h->q - i0) ? h->q : i0 + cnt;
+    int rc = run_negcls(h, st);
+    if (rc) return rc;
+    if (i_end <= i0) return TM_OK;
+    return launch_train(h, tally_snapshot, i0, i_end, st);
+}
+
+int tm_class_sums(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, void *stream)
+{
+    if (!h || q < 0) return TM_EINVAL;
+    if (q == 0) return TM_OK;
+    if (!X || !sums) return TM_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    const Dims &d = h->d;
+    int rc = fill(h, sums, (size_t)q * d.m * 4, 0u, st);
+    if (rc) return rc;
+    rc = launch_eval(h, X, q, nullptr, 0, sums, d.m, 1, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_clamp, dim3(blocks_for(q * d.m, 256)), dim3(256), 0, st, sums, q * d.m, d.T);
+    TM_HIP(h, hipGetLastError());
+    return TM_OK;
+}
+
+int tm_predict(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, int32_t *sums_scratch, void *stream)
+{
+    if (!h || q < 0) return TM_EINVAL;
+    if (q == 0) return TM_OK;
+    if (!pred || !sums_scratch) return TM_EINVAL;
+    const int rc = tm_class_sums(h, X, q, sums_scratch, stream);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_argmax, dim3(blocks_for(q, 256)), dim3(256), 0, (hipStream_t)stream, sums_scratch, pred, q,
+                       h->d.m);
+    TM_HIP(h, hipGetLastError());
+    return TM_OK;
+}
+
+int tm_get_ta_state(tm_handle *h, uint8_t *out, void *stream)
+{
+    if (!h || !out) return TM_EINVAL;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    const int64_t nt = (int64_t)h->d.C * h->d.W;
+    hipLaunchKernelGGL(k_get_state, dim3(blocks_for(nt, 256)), dim3(256), 0, (hipStream_t)stream, h->d, h->planes,
+                       out);
+    TM_HIP(h, hipGetLastError());
+    return TM_OK;
+}
+
+int tm_set_ta_state(tm_handle *h, const uint8_t *in, void *stream)
+{
+    if (!h || !in) return TM_EINVAL;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    const int64_t nt = (int64_t)h->d.C * h->d.W;
+    hipLaunchKernelGGL(k_set_state, dim3(blocks_for(nt, 256)), dim3(256), 0, (hipStream_t)stream, h->d, in,
+                       h->planes, h->inc);
+    TM_HIP(h, hipGetLastError());
+    return TM_OK;
+}
+
+int tm_clause_outputs(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *bits, void *stream)
+{
+    if (!h || q < 0) return TM_EINVAL;
+    if (q == 0) return TM_OK;
+    if (!X || !bits) return TM_EINVAL;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    return launch_eval(h, X, q, bits, (q + 31) / 32, nullptr, 0, 0, (hipStream_t)stream);
+}
+
+int tm_sync_tallies(tm_handle *h, void *stream)
+{
+    if (!h) return TM_EINVAL;
+    if (!h->bound) return TM_ESTATE;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    return sync_tallies(h, (hipStream_t)stream);
+}
+
+int tm_get_tallies(tm_handle *h, int32_t *out, void *stream)
+{
+    if (!h || !out) return TM_EINVAL;
+    if (!h->bound) return TM_ESTATE;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    hipLaunchKernelGGL(k_tally_out, dim3(blocks_for(h->q * h->d.m, 256)), dim3(256), 0, (hipStream_t)stream,
+                       h->tally, out, h->q, h->qp, h->d.m);
+    TM_HIP(h, hipGetLastError());
+    return TM_OK;
+}
+
+int tm_get_prev_outputs(tm_handle *h, uint32_t *bits, void *stream)
+{
+    if (!h || !bits) return TM_EINVAL;
+    if (!h->bound) return TM_ESTATE;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    const int64_t words = (h->q + 31) / 32;
+    hipLaunchKernelGGL(k_copy_rows, dim3(blocks_for((int64_t)h->d.C * words, 256)), dim3(256), 0,
+                       (hipStream_t)stream, h->ostar, h->Qw, bits, words, (int64_t)h->d.C, words);
+    TM_HIP(h, hipGetLastError());
+    return TM_OK;
+}
+
+int tm_set_epoch(tm_handle *h, uint32_t epoch)
+{
+    if (!h || epoch >= (1u << 24)) return TM_EINVAL;
+    h->epoch = epoch;
+    return TM_OK;
+}
+
+int tm_get_epoch(tm_handle *h, uint32_t *epoch)
+{
+    if (!h || !epoch) return TM_EINVAL;
+    *epoch = h->epoch;
+    return TM_OK;
+}
+
+int tm_read_counters(tm_handle *h, uint64_t *out, void *stream)
+{
+    if (!h || !out) return TM_EINVAL;
+    if (!h->bound) return TM_ESTATE;
+    hipStream_t st = (hipStream_t)stream;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    unsigned long long tmp[4];
+    TM_HIP(h, hipMemcpyAsync(tmp, h->counters, sizeof(tmp), hipMemcpyDeviceToHost, st));
+    TM_HIP(h, hipStreamSynchronize(st));
+    for (int k = 0; k < 4; ++k) out[k] = tmp[k];
+    return fill(h, h->counters, 256, 0u, st);
+}
+
+const char *tm_strerror(int code)
+{
+    switch (code) {
+    case TM_OK: return "ok";
+    case TM_EINVAL: return "invalid argument or configuration";
+    case TM_ESTATE: return "no training data bound (call tm_bind_train first)";
+    case TM_EHIP: return "HIP runtime error (see tm_last_hip_error)";
+    case TM_ELIMIT: return "size outside the supported range";
+    default: return "unknown error code";
+    }
+}
+
+int tm_last_hip_error(tm_handle *h) { return h ? h->last_hip : 0; }
+
+} // extern "C"

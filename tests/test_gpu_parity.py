@@ -1,0 +1,209 @@
+"""GPU parity: the HIP path against the CPU oracle, element by element, through
+the C boundary.  Everything here is integer / bit work, so the bar is exact
+equality."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tm_oracle as O
+from paper_2009_04861_amd import binding as B
+from paper_2009_04861_amd import synth
+from tests.helpers import (bits_to_u8, dev_bits, dev_i32, gpu_state_as_oracle, make_pair, push_state,
+                           sparse_random_state)
+
+pytestmark = pytest.mark.gpu
+
+# (m, n, o, N, T, s): shapes spanning one and several register slots per lane,
+# ragged feature tails, mixed classes inside a 64-clause tile, both saturation paths
+SHAPES = [
+    (2, 10, 12, 100, 15, 3.9),      # noisy-XOR machine: 2 literal words, classes share a tile
+    (3, 6, 37, 20, 4, 3.0),         # ragged tail, 3 classes in one tile
+    (10, 20, 784, 128, 16, 10.0),   # image-like feature count, 50 literal words
+    (2, 70, 100, 128, 9, 2.0),      # tiles straddle a class boundary; threshold 0x8000
+    (4, 4, 1100, 64, 7, 5.0),       # 70 literal words -> 2 register slots
+    (2, 4, 2500, 128, 3, 10.0),     # 158 literal words -> 3 slots, 3 mask chunks in evaluation
+]
+
+
+def rand_problem(rng, q, o, m, density=0.3):
+    X = (rng.random((q, o)) < density).astype(np.uint8)
+    y = rng.integers(0, m, size=q).astype(np.int32)
+    return X, y
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_initial_states_match(shape, device):
+    m, n, o, N, T, s = shape
+    print("init", shape, flush=True)
+    ora, gpu = make_pair(m, n, o, N, T, s, 1234)
+    assert np.array_equal(gpu_state_as_oracle(gpu), ora.state)
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_state_roundtrip(shape, device):
+    m, n, o, N, T, s = shape
+    print("roundtrip", shape, flush=True)
+    rng = np.random.default_rng(1)
+    ora, gpu = make_pair(m, n, o, N, T, s, 5)
+    st = rng.integers(1, 2 * N + 1, size=ora.state.shape).astype(np.int32)
+    push_state(gpu, st)
+    assert np.array_equal(gpu_state_as_oracle(gpu), st)
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("q", [1, 63, 300, 777])
+def test_inference_matches(shape, q, device):
+    m, n, o, N, T, s = shape
+    print("inference", shape, q, flush=True)
+    rng = np.random.default_rng(q + o)
+    ora, gpu = make_pair(m, n, o, N, T, s, 7)
+    ora.state[:] = sparse_random_state(rng, ora.C, ora.L, N, 1.5 / o)
+    push_state(gpu, ora.state)
+    X, _ = rand_problem(rng, q, o, m)
+    Xd = dev_bits(gpu, X)
+    assert np.array_equal(bits_to_u8(gpu.clause_outputs(Xd), q), ora.clause_outputs(X).T)
+    want = ora.class_sums(X)
+    assert np.abs(want).max() > 0
+    assert np.array_equal(gpu.class_sums(Xd).cpu().numpy(), want)
+    assert np.array_equal(gpu.predict(Xd).cpu().numpy(), ora.predict(X))
+
+
+def test_class_sums_are_clamped(device):
+    ora, gpu = make_pair(2, 64, 20, 128, 5, 3.0, 3)
+    ora.state[:] = 1
+    push_state(gpu, ora.state)          # every clause empty -> raw sums 0; silence negatives of class 1
+    ora.state[64 + np.arange(0, 64, 2), :] = 256
+    push_state(gpu, ora.state)
+    X = np.zeros((5, 20), dtype=np.uint8)
+    got = gpu.class_sums(dev_bits(gpu, X)).cpu().numpy()
+    assert np.array_equal(got, ora.class_sums(X))
+    assert got[0].tolist() == [0, 5]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_sync_pass_matches(shape, device):
+    m, n, o, N, T, s = shape
+    print("sync", shape, flush=True)
+    rng = np.random.default_rng(11)
+    q = 333
+    ora, gpu = make_pair(m, n, o, N, T, s, 7)
+    ora.state[:] = sparse_random_state(rng, ora.C, ora.L, N, 1.5 / o)
+    push_state(gpu, ora.state)
+    X, y = rand_problem(rng, q, o, m)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    assert np.array_equal(gpu.tallies().cpu().numpy(), tally)
+    assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar)
+
+
+def run_frozen(ora, gpu, X, y, epoch, i0, cnt, tally, ostar):
+    """One frozen-snapshot step on both sides from the same starting point."""
+    snap = tally.copy()
+    gpu.feedback_step(dev_i32(gpu, snap), i0, cnt)
+    fired = ora.feedback_step(X, y, snap, tally, ostar, epoch, i0, cnt)
+    return fired
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_feedback_step_matches_bit_exactly(shape, device):
+    m, n, o, N, T, s = shape
+    print("feedback", shape, flush=True)
+    rng = np.random.default_rng(21)
+    q = 200
+    ora, gpu = make_pair(m, n, o, N, T, s, 99)
+    X, y = rand_problem(rng, q, o, m)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    total_fired = 0
+    # ranges that start and end inside 64-example blocks, then whole passes
+    for step, (i0, cnt) in enumerate([(0, 1), (1, 70), (71, 57), (128, 72), (0, q), (0, q), (0, q)]):
+        B.tm_set_epoch(gpu.h, step)
+        total_fired += run_frozen(ora, gpu, X, y, step, i0, cnt, tally, ostar)
+        assert np.array_equal(gpu_state_as_oracle(gpu), ora.state), ("state", step)
+        assert np.array_equal(gpu.tallies().cpu().numpy(), tally), ("tally", step)
+        assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar), ("ostar", step)
+    assert total_fired > 0
+    c = gpu.counters()
+    assert c["fired"] == total_fired
+
+
+@pytest.mark.parametrize("s", [1.0, 2.0, 4.0, 3.9, 25.0])
+@pytest.mark.parametrize("N", [3, 100, 128])
+def test_feedback_saturation_and_threshold_paths(s, N, device):
+    # small N drives automata into both ends of their range quickly
+    print("saturation", s, N, flush=True)
+    m, n, o, T = 2, 8, 45, 6
+    rng = np.random.default_rng(5)
+    q = 150
+    ora, gpu = make_pair(m, n, o, N, T, s, 17)
+    X, y = rand_problem(rng, q, o, m, density=0.5)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    for ep in range(12):
+        B.tm_set_epoch(gpu.h, ep)
+        run_frozen(ora, gpu, X, y, ep, 0, q, tally, ostar)
+    assert np.array_equal(gpu_state_as_oracle(gpu), ora.state)
+    assert np.array_equal(gpu.tallies().cpu().numpy(), tally)
+    if N == 3:
+        assert ora.state.min() == 1 and ora.state.max() == 2 * N      # both ends were reached
+
+
+def test_noisy_xor_frozen_epochs_match(device):
+    # the small benchmark configuration, whole epochs, snapshot = tallies at epoch start
+    Xtr, ytr, Xte, yte = synth.noisy_xor(1000, 500)
+    ora, gpu = make_pair(2, 10, 12, 100, 15, 3.9, 1)
+    gpu.bind_train(dev_bits(gpu, Xtr), dev_i32(gpu, ytr))
+    tally, ostar = ora.sync_tallies(Xtr)
+    for ep in range(10):
+        B.tm_set_epoch(gpu.h, ep)
+        run_frozen(ora, gpu, Xtr, ytr, ep, 0, len(ytr), tally, ostar)
+    assert np.array_equal(gpu_state_as_oracle(gpu), ora.state)
+    assert np.array_equal(gpu.predict(dev_bits(gpu, Xte)).cpu().numpy(), ora.predict(Xte))
+
+
+@pytest.mark.parametrize("shape", SHAPES[:4])
+def test_async_epoch_invariants(shape, device):
+    m, n, o, N, T, s = shape
+    print("async", shape, flush=True)
+    rng = np.random.default_rng(31)
+    q = 500
+    ora, gpu = make_pair(m, n, o, N, T, s, 3)
+    X, y = rand_problem(rng, q, o, m)
+    Xd = dev_bits(gpu, X)
+    gpu.bind_train(Xd, dev_i32(gpu, y))
+    sign = np.where(np.arange(ora.C) % n % 2 == 1, 1, -1)
+    for ep in range(4):
+        gpu.fit_epoch()
+        st = gpu.get_ta_state().cpu().numpy()
+        assert st.max() <= 2 * N - 1                               # states stay in [1, 2N]
+        # atomics lose nothing: the tally is the signed sum of the stored previous outputs
+        ostar = bits_to_u8(gpu.prev_outputs(), q).astype(np.int64)
+        want = np.stack([(ostar[c * n:(c + 1) * n] * sign[c * n:(c + 1) * n, None]).sum(0) for c in range(m)], 1)
+        assert np.array_equal(gpu.tallies().cpu().numpy(), want)
+    assert B.tm_get_epoch(gpu.h) == 4
+    # eventual consistency: after a pass of pure refreshes the tallies are the exact vote sums
+    gpu.sync_tallies()
+    ora.state[:] = gpu_state_as_oracle(gpu)
+    assert np.array_equal(gpu.tallies().cpu().numpy(), ora.class_sums(X, clamp=False))
+    c = gpu.counters()
+    assert c["pairs"] == 4 * q * ora.C and 0 < c["fired"] < c["pairs"]
+
+
+def test_error_codes(device):
+    gpu = B.TsetlinMachine(3, 4, 20, 10, 5, 3.0, 1)
+    with pytest.raises(B.TMError) as e:
+        gpu.fit_epoch()
+    assert e.value.code == B.TM_ESTATE
+    X = dev_bits(gpu, np.zeros((10, 20), dtype=np.uint8))
+    with pytest.raises(B.TMError) as e:
+        gpu.bind_train(X, dev_i32(gpu, np.array([0, 1, 2, 3, 0, 0, 0, 0, 0, 0])))   # label 3 of 3 classes
+    assert e.value.code == B.TM_EINVAL
+    with pytest.raises(B.TMError) as e:
+        gpu.fit_epoch()
+    assert e.value.code == B.TM_ESTATE
+    gpu.bind_train(X, dev_i32(gpu, np.zeros(10)))
+    gpu.fit_epoch()
+    # empty inference batch is a no-op
+    empty = torch.empty((0, 1), dtype=torch.int32, device=gpu.dev)
+    assert gpu.class_sums(empty).shape == (0, 3)
+    torch.cuda.synchronize()

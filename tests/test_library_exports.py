@@ -1,0 +1,55 @@
+"""CPU checks of the boundary: the built library loads and exports every
+function the header declares; host-only entry points validate configurations."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2009_04861_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "tm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tm_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"tm_create", "tm_fit_epoch", "tm_predict", "tm_class_sums"} <= set(names)
+    L = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(B.EXPORTS) == set(names)
+
+
+def test_binding_has_same_names():
+    for n in declared_functions():
+        if n in ("tm_strerror", "tm_last_hip_error"):
+            continue
+        assert callable(getattr(B, n)), n
+
+
+def test_sizes_and_validation_are_host_only():
+    cfg = B.make_config(10, 2000, 784, 128, 50, 10.0, 1)
+    C, W = 20000, 50
+    assert B.tm_state_bytes(cfg) == C * W * 32 + C * W * 4
+    ws = B.tm_train_ws_bytes(cfg, 60000)
+    qp = 60032
+    # tallies + one bit per example per clause + transposed X + negative class + counters/flag
+    assert ws >= 10 * qp * 4 + C * qp // 8 + 25 * qp * 4 + qp * 4
+    assert ws < 1.01 * (10 * qp * 4 + C * qp // 8 + 25 * qp * 4 + qp * 4) + 4096
+    bad = [dict(m=1), dict(n=3), dict(n=0), dict(o=0), dict(N=0), dict(N=129), dict(T=0), dict(s=0.5)]
+    for kw in bad:
+        a = dict(m=2, n=4, o=8, N=10, T=5, s=3.0)
+        a.update(kw)
+        with pytest.raises(B.TMError) as e:
+            B.tm_state_bytes(B.make_config(a["m"], a["n"], a["o"], a["N"], a["T"], a["s"], 1))
+        assert e.value.code == B.TM_EINVAL
+    with pytest.raises(B.TMError) as e:
+        B.tm_state_bytes(B.make_config(2, 4, 20481, 10, 5, 3.0, 1))
+    assert e.value.code == B.TM_ELIMIT
+    assert B.strerror(B.TM_ESTATE).startswith("no training data")
