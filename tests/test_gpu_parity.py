@@ -144,8 +144,33 @@ def test_feedback_saturation_and_threshold_paths(s, N, device):
         run_frozen(ora, gpu, X, y, ep, 0, q, tally, ostar)
     assert np.array_equal(gpu_state_as_oracle(gpu), ora.state)
     assert np.array_equal(gpu.tallies().cpu().numpy(), tally)
-    if N == 3:
-        assert ora.state.min() == 1 and ora.state.max() == 2 * N      # both ends were reached
+
+
+@pytest.mark.parametrize("s", [2.0, 3.9])
+@pytest.mark.parametrize("N", [3, 100, 128])
+def test_feedback_reaches_both_ends_of_the_state_range(s, N, device):
+    # plain literals start one below the top, negated ones one above the bottom, and
+    # half the examples are all-ones: strong Type I pushes into 2N, weak into 1
+    print("ends", s, N, flush=True)
+    m, n, o, T = 2, 8, 45, 6
+    rng = np.random.default_rng(5)
+    q = 150
+    ora, gpu = make_pair(m, n, o, N, T, s, 17)
+    X, y = rand_problem(rng, q, o, m, density=0.5)
+    X[::2] = 1
+    ora.state[:, :o] = 2 * N - 1
+    ora.state[:, o:] = 2
+    push_state(gpu, ora.state)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    for ep in range(6):
+        B.tm_set_epoch(gpu.h, ep)
+        run_frozen(ora, gpu, X, y, ep, 0, q, tally, ostar)
+    assert ora.state.min() == 1 and ora.state.max() == 2 * N
+    assert (ora.state == 2 * N).sum() > 5 and (ora.state == 1).sum() > 2
+    assert np.array_equal(gpu_state_as_oracle(gpu), ora.state)
+    assert np.array_equal(gpu.tallies().cpu().numpy(), tally)
+    assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar)
 
 
 def test_noisy_xor_frozen_epochs_match(device):
