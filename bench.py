@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the Tsetlin machine hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over the image-like workload
+(60,000 training examples x 784 Boolean features, 10 classes x 2,000 clauses,
+2N = 256 states, T = 50, s = 10):
+    tm_fit_epoch      gate, clause evaluation, Type I / II feedback, tally refresh
+    tm_sync_tallies   tally pre-calculation over all (clause, example) pairs
+    tm_predict        class sums + argmax over the 10,000 test examples
+`value` is training examples per second of whole steps with all inputs resident
+in HBM.  The roofline object is for the dominant kernel (the training kernel)
+and is measured inside this program with events on the launch stream; the CPU
+oracle is timed on a bounded sample of the same workload in the same run.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# integer-ALU roofline of MI355X: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one
+# 32-bit integer lane-operation per lane per clock
+ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+HBM_PEAK_GBS = 8000.0
+
+# Algorithmic 32-bit lane-operations of the training kernel, per unit of work.
+PHILOX_OPS = 100          # 10 rounds x (4 multiplies + 4 xors + 2 key updates)
+TYPE1_OPS_PER_WORD = 4 * PHILOX_OPS + 16 + 16 + 48 + 4   # draws, comparator, 2 saturation tests, 2 ripples, masks
+TYPE2_OPS_PER_WORD = 2 + 24
+GATE_OPS = PHILOX_OPS + 8
+
+
+def train_kernel_ops(counters, W):
+    """Algorithmic lane-ops of a run of the training kernel from its event counters."""
+    return (counters["pairs"] * (W + 2)                    # one AND-OR per literal word + refresh
+            + counters["candidates"] * GATE_OPS
+            + counters["type1"] * W * TYPE1_OPS_PER_WORD
+            + counters["type2_active"] * W * TYPE2_OPS_PER_WORD)
+
+
+def make_workload(name, small=False):
+    from paper_2009_04861_amd import synth
+    if name == "image_like":
+        hp = dict(synth.WORKLOADS["image_like"])
+        if small:
+            hp["n"] = 200
+            Xtr, ytr, Xte, yte = synth.image_like(6000, 1000)
+        else:
+            Xtr, ytr, Xte, yte = synth.image_like()
+        desc = "image_like (configs[1]): 60000x784 train, 10000 test, 10 classes x 2000 clauses, T=50, s=10, 2N=256"
+    elif name == "noisy_xor":
+        hp = dict(synth.WORKLOADS["noisy_xor"])
+        Xtr, ytr, Xte, yte = synth.noisy_xor()
+        desc = "noisy_xor (configs[0]): 5000x12 train, 5000 test, 2 classes x 10 clauses, T=15, s=3.9, N=100"
+    else:
+        raise SystemExit("unknown workload %s" % name)
+    return hp, (Xtr, ytr, Xte, yte), desc
+
+
+def cpu_baseline(hp, Xtr, ytr, Xte, seed, budget_s=15.0):
+    """The oracle as it stands, one core, on a bounded sample: Algorithm 1 over the
+    first S training examples for all clauses (same work per example as
+    tm_fit_epoch), plus tally pre-calculation and prediction on S examples."""
+    import numpy as np
+    from oracle import tm_oracle as O
+    ora = O.Oracle(hp["m"], hp["n"], hp["o"], hp["N"], hp["T"], hp["s"], seed)
+
+    def run(S):
+        X = np.ascontiguousarray(Xtr[:S]); y = np.ascontiguousarray(ytr[:S])
+        t0 = time.perf_counter()
+        tally, ostar = ora.sync_tallies(X)
+        ora.feedback_step(X, y, tally.copy(), tally, ostar, 0, 0, S)
+        ora.predict(np.ascontiguousarray(Xte[:max(1, S // 6)]))
+        return time.perf_counter() - t0
+
+    S = 8
+    t = run(S)
+    while t < 1.0 and S < len(ytr):
+        S = min(len(ytr), S * 4)
+        t = run(S)
+    S2 = int(min(len(ytr), max(S, S * budget_s / max(t, 1e-9))))
+    if S2 > S:
+        S, t = S2, run(S2)
+    return {"value": S / t, "unit": "examples/s", "cores": 1, "kind": "oracle",
+            "sample": "sequential C oracle, 1 thread: tally pre-calculation + one Algorithm-1 pass over the first %d "
+                      "training examples (all %d clauses) + prediction of %d test examples; %.1f s"
+                      % (S, hp["m"] * hp["n"], max(1, S // 6), t)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="image_like")
+    ap.add_argument("--small", action="store_true", help="reduced sizes (debugging only, not a valid result)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=1)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on one GPU only (the path shards by clause across GPUs by "
+                         "design, but no multi-GPU code exists); run with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2009_04861_amd import binding as B
+    from paper_2009_04861_amd import synth
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    B.lib()  # fail loudly if the HIP library is missing
+
+    hp, (Xtr, ytr, Xte, yte), desc = make_workload(args.workload, args.small)
+    q, qt = len(ytr), len(yte)
+    tm = B.TsetlinMachine(seed=args.seed, **hp)
+    C, W = tm.C, 2 * tm.Wf
+    Xd = tm.to_device_bits(synth.pack_features(Xtr))
+    yd = torch.from_numpy(ytr).to(tm.dev)
+    Xte_d = tm.to_device_bits(synth.pack_features(Xte))
+    pred = torch.empty(qt, dtype=torch.int32, device=tm.dev)
+    scratch = torch.empty((qt, tm.m), dtype=torch.int32, device=tm.dev)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    e0, e1 = ev(), ev()
+    e0.record()
+    tm.bind_train(Xd, yd)
+    e1.record()
+    torch.cuda.synchronize()
+    bind_ms = e0.elapsed_time(e1)
+
+    def step(evs=None):
+        if evs:
+            evs[0].record()
+        B.tm_fit_epoch(tm.h)
+        if evs:
+            evs[1].record()
+        B.tm_sync_tallies(tm.h)
+        if evs:
+            evs[2].record()
+        B.tm_predict(tm.h, Xte_d, pred, scratch)
+        if evs:
+            evs[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    tm.counters()  # reset the device counters
+
+    evs = [[ev() for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(evs[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall = t1 - t0
+    cnt = tm.counters()
+    acc = float((pred.cpu().numpy() == yte).mean())
+
+    fit_ms = [e[0].elapsed_time(e[1]) for e in evs]
+    sync_ms = [e[1].elapsed_time(e[2]) for e in evs]
+    pred_ms = [e[2].elapsed_time(e[3]) for e in evs]
+    fit_avg = float(np.mean(fit_ms))
+    ops = train_kernel_ops(cnt, W) / args.steps
+    achieved = ops / (fit_avg * 1e-3) / 1e12
+    # algorithmic HBM bytes of one training launch: TA planes in + out, include masks out,
+    # X and its transposed copy once, previous-output bits in + out, tallies, labels
+    hbm_bytes = (2 * C * W * 32 + C * W * 4 + 2 * q * tm.Wf * 4 + 2 * C * ((q + 63) // 64) * 8
+                 + tm.m * q * 4 * 2 + q * 8)
+
+    out = {
+        "metric": "training examples/sec per epoch (one step = fit epoch + tally pre-calculation + test-set prediction)",
+        "value": args.steps * q / wall,
+        "unit": "examples/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": 1e3 * wall / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32 bit words, u8 bit-sliced automata, int32 tallies",
+        "data": "synthetic",
+        "config": {
+            "workload": desc if not args.small else desc + " [REDUCED SIZES, NOT A VALID RESULT]",
+            "m": tm.m, "n": tm.n, "o": tm.o, "N": tm.N, "T": tm.T, "s": tm.s, "q_train": q, "q_test": qt,
+            "clauses_total": C, "pairs_per_epoch": q * C,
+            "fit_epoch_ms": fit_avg, "sync_tallies_ms": float(np.mean(sync_ms)), "predict_ms": float(np.mean(pred_ms)),
+            "bind_train_ms": bind_ms,
+            "train_pairs_per_s": q * C / (fit_avg * 1e-3),
+            "inference_clause_evals_per_s": qt * C / (float(np.mean(pred_ms)) * 1e-3),
+            "sync_clause_evals_per_s": q * C / (float(np.mean(sync_ms)) * 1e-3),
+            "gate_rate_of_candidates": cnt["fired"] / max(1, cnt["candidates"]),
+            "type1_per_epoch": cnt["type1"] / args.steps,
+            "tally_changes_per_epoch": cnt["tally_changes"] / args.steps,
+            "test_accuracy_after_run": acc,
+        },
+        "roofline": {
+            "kernel": "k_train (Algorithm 1, one wavefront per clause)",
+            "bound": "alu",
+            "achieved": achieved,
+            "peak": ALU_PEAK_TOPS,
+            "unit": "Tlane-op/s (32-bit integer)",
+            "frac": achieved / ALU_PEAK_TOPS,
+            "traffic": None,
+            "avg_launch_ms": fit_avg,
+            "algorithmic_lane_ops_per_launch": ops,
+            "hbm_algorithmic_bytes_per_launch": hbm_bytes,
+            "hbm_achieved_GBs": hbm_bytes / (fit_avg * 1e-3) / 1e9,
+            "hbm_frac": hbm_bytes / (fit_avg * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(hp, Xtr, ytr, Xte, args.seed)
+    print(json.dumps(out))
+    tm.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -411,7 +411,7 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
     const int first_blk = min(tz >> 2, 4);
     const uint32_t ge_init = d.thr >= 65536u ? 0u : ~0u;
 
-    unsigned long long n_pairs = 0, n_fired = 0, n_type1 = 0, n_changes = 0;
+    unsigned long long n_pairs = 0, n_fired = 0, n_type1 = 0, n_changes = 0, n_draws = 0, n_type2 = 0;
 
     for (int64_t i0 = a.i_begin & ~(int64_t)63; i0 < a.i_end; i0 += 64) {
         const int64_t i = i0 + lane;
@@ -437,6 +437,7 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
         }
         uint64_t fmask = ballot(fire);
         const uint64_t tmask = ballot(target);
+        n_draws += __builtin_popcountll(ballot(cand));
         const uint64_t rmask = ballot(inr);
         n_pairs += __builtin_popcountll(rmask);
         n_fired += __builtin_popcountll(fmask);
@@ -454,6 +455,7 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
             if (tgt != pos) {
                 // Type II feedback (Table 2): where the clause is 1 and the literal 0, push Exclude towards Include
                 if (Cout) {
+                    ++n_type2;
 #pragma unroll
                     for (int r = 0; r < WPL; ++r) {
                         const int lw = r * 64 + lane;
@@ -547,6 +549,8 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
         atomicAdd(&a.counters[1], n_fired);
         atomicAdd(&a.counters[2], n_type1);
         atomicAdd(&a.counters[3], n_changes);
+        atomicAdd(&a.counters[4], n_draws);
+        atomicAdd(&a.counters[5], n_type2);
     }
 }
 
@@ -1007,10 +1011,10 @@ int tm_read_counters(tm_handle *h, uint64_t *out, void *stream)
     if (!h->bound) return TM_ESTATE;
     hipStream_t st = (hipStream_t)stream;
     TM_HIP(h, hipSetDevice(h->cfg.device));
-    unsigned long long tmp[4];
+    unsigned long long tmp[6];
     TM_HIP(h, hipMemcpyAsync(tmp, h->counters, sizeof(tmp), hipMemcpyDeviceToHost, st));
     TM_HIP(h, hipStreamSynchronize(st));
-    for (int k = 0; k < 4; ++k) out[k] = tmp[k];
+    for (int k = 0; k < 6; ++k) out[k] = tmp[k];
     return fill(h, h->counters, 256, 0u, st);
 }
 
