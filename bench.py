@@ -102,6 +102,9 @@ def main():
     ap.add_argument("--small", action="store_true", help="reduced sizes (debugging only, not a valid result)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy (reference dispatch for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on one GPU only (the path shards by clause across GPUs by "
@@ -146,6 +149,13 @@ def main():
         B.tm_predict(tm.h, Xte_d, pred, scratch)
         if evs:
             evs[3].record()
+
+    if args.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device=tm.dev)   # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

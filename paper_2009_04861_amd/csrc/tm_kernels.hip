@@ -334,45 +334,74 @@ struct TrainArgs {
     unsigned long long *counters;
     int64_t q, qp, Qw, i_begin, i_end;
     uint32_t epoch;
+    int lds_mask_words; // W rounded up to a multiple of 4
+    int lds_off_words;  // Wf + 8 rounded up to a multiple of 4
 };
 
-// Clause outputs for the 64 examples i0 .. i0+63, lane = example: bit l of the
-// result is C(X_{i0+l}) for the include masks currently held in plane 7 of the
-// calling wavefront (lane = literal word).  Only non-zero mask words are
-// visited; the loop stops as soon as all 64 examples are violated.
+// The clause as the evaluation loop wants it: one entry per feature word whose
+// plain or negated mask word is non-zero, compacted in LDS: eoff[k] = byte
+// offset of that word's row in XT, emask[k] = {mask of plain literals, mask of
+// negated literals}; padded with eight empty entries.  Rebuilt whenever plane 7
+// changes.
 template <int WPL>
-__device__ __forceinline__ uint64_t eval64(const uint32_t (&p)[WPL][8], const uint32_t *__restrict__ XT,
-                                           int64_t qp, int64_t i0, int lane, int Wf)
+__device__ __forceinline__ int build_entries(const uint32_t (&p)[WPL][8], uint32_t *lmask, uint32_t *eoff,
+                                             uint2 *emask, int lane, int Wf, int W, uint32_t row_bytes)
 {
-    uint32_t viol = 0;
-    bool dead = false;
-    const uint32_t *col = XT + i0 + lane;
 #pragma unroll
     for (int r = 0; r < WPL; ++r) {
-        uint64_t nz = ballot(p[r][7] != 0u);
-        while (nz != 0 && !dead) {
-            int l[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) { // a repeated word is harmless (OR is idempotent)
-                l[k] = __builtin_ctzll(nz);
-                const uint64_t rest = nz & (nz - 1);
-                nz = rest ? rest : nz;
-                if (k == 3) nz = rest;
-            }
-            uint32_t x[4], M[4], flip[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int lw = r * 64 + l[k];
-                const bool neg = lw >= Wf;
-                const int fw = neg ? lw - Wf : lw;
-                M[k] = readlane(p[r][7], l[k]);
-                flip[k] = neg ? 0u : ~0u; // plain literal violated where x = 0, negated where x = 1
-                x[k] = col[(int64_t)fw * qp];
-            }
-#pragma unroll
-            for (int k = 0; k < 4; ++k) viol |= M[k] & (x[k] ^ flip[k]);
-            dead = (ballot(viol == 0u) == 0);
+        const int lw = r * 64 + lane;
+        if (lw < W) lmask[lw] = p[r][7];
+    }
+    __syncthreads(); // one wavefront per workgroup: orders the LDS traffic, costs nothing
+    int n = 0;
+    for (int f0 = 0; f0 < Wf; f0 += 64) {
+        const int fw = f0 + lane;
+        const bool ok = fw < Wf;
+        const uint32_t mp = ok ? lmask[fw] : 0u;
+        const uint32_t mn = ok ? lmask[Wf + fw] : 0u;
+        const bool nzf = (mp | mn) != 0u;
+        const uint64_t b = ballot(nzf);
+        const int pre = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, 0u));
+        if (nzf) {
+            eoff[n + pre] = (uint32_t)fw * row_bytes;
+            emask[n + pre] = make_uint2(mp, mn);
         }
+        n += __builtin_popcountll(b);
+    }
+    if (lane < 8) {
+        eoff[n + lane] = 0u;
+        emask[n + lane] = make_uint2(0u, 0u);
+    }
+    __syncthreads();
+    return n;
+}
+
+// Clause outputs for 64 examples, lane = example: bit l of the result is
+// C(X_{i0+l}).  xt_block points at XT[0][i0].  Entries are taken eight at a
+// time: their eight coalesced 256-byte loads are in flight together, the masks
+// arrive as LDS broadcasts, and each entry costs two bit operations.  Stops as
+// soon as all 64 examples are violated.
+__device__ __forceinline__ uint64_t eval64(const uint32_t *eoff, const uint2 *emask, int nent,
+                                           const uint32_t *__restrict__ xt_block, int lane)
+{
+    uint32_t viol = 0;
+    const char *base = reinterpret_cast<const char *>(xt_block);
+    const uint32_t lane4 = (uint32_t)lane * 4u;
+    for (int k = 0; k < nent; k += 8) {
+        const uint4 oa = *reinterpret_cast<const uint4 *>(eoff + k);
+        const uint4 ob = *reinterpret_cast<const uint4 *>(eoff + k + 4);
+        const uint32_t off[8] = {oa.x, oa.y, oa.z, oa.w, ob.x, ob.y, ob.z, ob.w};
+        uint32_t x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = *reinterpret_cast<const uint32_t *>(base + (off[j] + lane4));
+        const uint4 *mq = reinterpret_cast<const uint4 *>(emask + k);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint4 m = mq[j]; // {plain, negated} masks of entries 2j and 2j+1
+            // a plain literal is violated where x = 0, a negated one where x = 1
+            viol |= ((x[2 * j] & m.y) | (~x[2 * j] & m.x)) | ((x[2 * j + 1] & m.w) | (~x[2 * j + 1] & m.z));
+        }
+        if (ballot(viol == 0u) == 0) break;
     }
     return ballot(viol == 0u);
 }
@@ -382,6 +411,11 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
                                               const int32_t *__restrict__ y, const int32_t *__restrict__ negcls,
                                               const TrainArgs a)
 {
+    extern __shared__ uint32_t lds[];
+    uint32_t *lmask = lds;                                  // [W] include masks, literal-word order
+    uint32_t *eoff = lds + a.lds_mask_words;                // [Wf + 8] (rounded to 4 words)
+    uint2 *emask = reinterpret_cast<uint2 *>(eoff + a.lds_off_words);
+
     const Dims &d = a.d;
     const int lane = threadIdx.x;
     const int g = blockIdx.x;
@@ -389,6 +423,7 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
     const bool pos = ((g - c * d.n) & 1) != 0; // odd index within the class: positive polarity
     const int sign = pos ? 1 : -1;
     const int T = d.T;
+    const uint32_t row_bytes = (uint32_t)a.qp * 4u;
 
     uint32_t p[WPL][8];
 #pragma unroll
@@ -404,6 +439,7 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
             for (int b = 0; b < 8; ++b) p[r][b] = 0u;
         }
     }
+    int nent = build_entries<WPL>(p, lmask, eoff, emask, lane, d.Wf, d.W, row_bytes);
 
     // lowest Philox block of the Type I comparator that can matter: bits of the
     // uniform below the lowest set bit of thr never decide u < thr
@@ -411,24 +447,47 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
     const int first_blk = min(tz >> 2, 4);
     const uint32_t ge_init = d.thr >= 65536u ? 0u : ~0u;
 
-    unsigned long long n_pairs = 0, n_fired = 0, n_type1 = 0, n_changes = 0, n_draws = 0, n_type2 = 0;
+    unsigned long long n_pairs = 0, n_fired = 0, n_type1 = 0, n_changes = 0, n_cand = 0, n_type2 = 0;
 
-    for (int64_t i0 = a.i_begin & ~(int64_t)63; i0 < a.i_end; i0 += 64) {
+    // Per-block inputs (label, negative class, tally, previous-output words) are
+    // fetched one block ahead so that their latency hides behind the current block.
+    // Reading the tally 64 examples early is within the method's premise of
+    // outdated tallies.
+    struct BlockIn {
+        int yi, ng, v;
+        uint32_t o0, o1;
+    };
+    auto fetch = [&](int64_t i0) {
+        BlockIn f;
         const int64_t i = i0 + lane;
         const bool inr = i >= a.i_begin && i < a.i_end;
-        int yi = -1, ng = -1;
+        f.yi = -1; f.ng = -1; f.v = 0;
         if (inr) {
-            yi = y[i];
-            ng = negcls[i];
+            f.yi = y[i];
+            f.ng = negcls[i];
+            f.v = a.vhat ? a.vhat[i * d.m + c]
+                         : __hip_atomic_load(&a.tally[(int64_t)c * a.qp + i], __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
         }
+        const uint32_t *op = a.ostar + (int64_t)g * a.Qw + (i0 >> 5);
+        f.o0 = op[0];
+        f.o1 = op[1];
+        return f;
+    };
+    const int64_t i_first = a.i_begin & ~(int64_t)63;
+    BlockIn nxt = fetch(i_first);
+
+    for (int64_t i0 = i_first; i0 < a.i_end; i0 += 64) {
+        const int64_t i = i0 + lane;
+        const bool inr = i >= a.i_begin && i < a.i_end;
+        const BlockIn cur = nxt;
+        if (i0 + 64 < a.i_end) nxt = fetch(i0 + 64);
+        const int yi = cur.yi, ng = cur.ng;
         const bool target = (yi == c);
         const bool cand = inr && (target || ng == c);
         bool fire = false;
         if (cand) {
-            const int v = a.vhat ? a.vhat[i * d.m + c]
-                                 : __hip_atomic_load(&a.tally[(int64_t)c * a.qp + i], __ATOMIC_RELAXED,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
-            const int vc = min(max(v, -T), T);
+            const int vc = min(max(cur.v, -T), T);
             const int e = target ? T - vc : T + vc; // Algorithm 1: error of the recorded vote sum
             if (e > 0) {
                 const U4 r = draw(d.key, STREAM_GATE, 0, (uint32_t)g, (uint64_t)i, a.epoch);
@@ -437,12 +496,13 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
         }
         uint64_t fmask = ballot(fire);
         const uint64_t tmask = ballot(target);
-        n_draws += __builtin_popcountll(ballot(cand));
         const uint64_t rmask = ballot(inr);
         n_pairs += __builtin_popcountll(rmask);
         n_fired += __builtin_popcountll(fmask);
+        n_cand += __builtin_popcountll(ballot(cand));
 
-        uint64_t obits = eval64<WPL>(p, XT, a.qp, i0, lane, d.Wf);
+        const uint32_t *xt_block = XT + i0;
+        uint64_t obits = eval64(eoff, emask, nent, xt_block, lane);
 
         while (fmask) {
             const int l = __builtin_ctzll(fmask);
@@ -482,7 +542,8 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
                     const uint32_t valid = act ? (fw == d.Wf - 1 ? d.tailmask : ~0u) : 0u;
                     const uint32_t lit = (xrow[fw] ^ (neg ? ~0u : 0u)) & valid;
                     // bit-sliced comparison of 32 16-bit uniforms with thr, least significant bit first:
-                    // ge = [u >= thr]; bit b of literal j's uniform is bit j of random word b
+                    // ge = [u >= thr]; bit b of literal j's uniform is bit j of random word b;
+                    // thr bit 1: ge &= w, thr bit 0: ge |= w, i.e. majority(w, ge, ~thr bit)
                     uint32_t ge = ge_init;
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
@@ -493,8 +554,7 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
 #pragma unroll
                             for (int k = 0; k < 4; ++k) {
                                 const uint32_t K = ((d.thr >> (4 * t + k)) & 1u) ? 0u : ~0u;
-                                const uint32_t df = w[k] ^ ge; // majority(w, ge, K): thr bit 1 -> w & ge, 0 -> w | ge
-                                ge = (df & K) | (~df & w[k]);
+                                ge = majority3(w[k], ge, K);
                             }
                         }
                     }
@@ -510,7 +570,8 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
                 }
             }
             if (ballot(changed != 0u)) { // the conjunction changed: re-evaluate this and the later examples
-                const uint64_t nb = eval64<WPL>(p, XT, a.qp, i0, lane, d.Wf);
+                nent = build_entries<WPL>(p, lmask, eoff, emask, lane, d.Wf, d.W, row_bytes);
+                const uint64_t nb = eval64(eoff, emask, nent, xt_block, lane);
                 const uint64_t keep = (1ull << l) - 1ull;
                 obits = (obits & keep) | (nb & ~keep);
             }
@@ -518,7 +579,8 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
 
         // refresh of tally and previous-output bits (last lines of Algorithm 1)
         uint32_t *op = a.ostar + (int64_t)g * a.Qw + (i0 >> 5);
-        const uint64_t ost = (uint64_t)op[0] | ((uint64_t)op[1] << 32);
+        const uint64_t ost = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)cur.o0) |
+                             ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)cur.o1) << 32);
         const uint64_t diff = (obits ^ ost) & rmask;
         if (diff) {
             if ((diff >> lane) & 1ull) {
@@ -549,7 +611,7 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
         atomicAdd(&a.counters[1], n_fired);
         atomicAdd(&a.counters[2], n_type1);
         atomicAdd(&a.counters[3], n_changes);
-        atomicAdd(&a.counters[4], n_draws);
+        atomicAdd(&a.counters[4], n_cand);
         atomicAdd(&a.counters[5], n_type2);
     }
 }
@@ -721,8 +783,20 @@ struct TrainPtrs {
 template <int WPL>
 void launch_train_t(const TrainPtrs &p, const TrainArgs &a, bool full, hipStream_t st)
 {
-    if (full) hipLaunchKernelGGL((k_train<WPL, true>), dim3(a.d.C), dim3(64), 0, st, p.X, p.XT, p.y, p.negcls, a);
-    else hipLaunchKernelGGL((k_train<WPL, false>), dim3(a.d.C), dim3(64), 0, st, p.X, p.XT, p.y, p.negcls, a);
+    const size_t lds = (size_t)(a.lds_mask_words + a.lds_off_words + 2 * (a.d.Wf + 8)) * 4;
+    if (full) hipLaunchKernelGGL((k_train<WPL, true>), dim3(a.d.C), dim3(64), lds, st, p.X, p.XT, p.y, p.negcls, a);
+    else hipLaunchKernelGGL((k_train<WPL, false>), dim3(a.d.C), dim3(64), lds, st, p.X, p.XT, p.y, p.negcls, a);
+}
+
+// Examples per launch of the training kernel.  An epoch is cut into ranges
+// whose slice of XT (Wf rows of `chunk` words) stays resident in one XCD's
+// 4 MiB L2 while all clauses stream over it; without the cut, wavefronts
+// drift apart over the whole of XT and re-fetch it from HBM many times.
+int64_t train_chunk(const Dims &d)
+{
+    int64_t chunk = ((int64_t)(1 << 20) / (4 * (int64_t)d.Wf)) & ~(int64_t)63;
+    if (chunk < 512) chunk = 512;
+    return chunk;
 }
 
 int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_end, hipStream_t st)
@@ -730,22 +804,30 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     const Dims &d = h->d;
     TrainArgs a;
     const TrainPtrs p{h->X, h->XT, h->y, h->negcls};
-    a.d = d; a.sat = h->sat; a.planes = h->planes; a.inc = h->inc; a.tally = h->tally; a.vhat = vhat; a.ostar = h->ostar; a.counters = h->counters;
-    a.q = h->q; a.qp = h->qp; a.Qw = h->Qw; a.i_begin = i_begin; a.i_end = i_end; a.epoch = h->epoch;
+    a.d = d; a.sat = h->sat; a.planes = h->planes; a.inc = h->inc; a.tally = h->tally;
+    a.vhat = vhat; a.ostar = h->ostar; a.counters = h->counters;
+    a.q = h->q; a.qp = h->qp; a.Qw = h->Qw; a.epoch = h->epoch;
+    a.lds_mask_words = (d.W + 3) & ~3;
+    a.lds_off_words = (d.Wf + 8 + 3) & ~3;
     const bool full = (d.N == 128);
     const int wpl = (d.W + 63) / 64;
-    if (wpl <= 1) launch_train_t<1>(p, a, full, st);
-    else if (wpl <= 2) launch_train_t<2>(p, a, full, st);
-    else if (wpl <= 3) launch_train_t<3>(p, a, full, st);
-    else if (wpl <= 4) launch_train_t<4>(p, a, full, st);
-    else if (wpl <= 6) launch_train_t<6>(p, a, full, st);
-    else if (wpl <= 8) launch_train_t<8>(p, a, full, st);
-    else if (wpl <= 10) launch_train_t<10>(p, a, full, st);
-    else if (wpl <= 12) launch_train_t<12>(p, a, full, st);
-    else if (wpl <= 16) launch_train_t<16>(p, a, full, st);
-    else if (wpl <= 20) launch_train_t<20>(p, a, full, st);
-    else return TM_ELIMIT;
-    TM_HIP(h, hipGetLastError());
+    const int64_t chunk = train_chunk(d);
+    for (int64_t b = (i_begin / chunk) * chunk; b < i_end; b += chunk) {
+        a.i_begin = std::max(b, i_begin);
+        a.i_end = std::min(b + chunk, i_end);
+        if (wpl <= 1) launch_train_t<1>(p, a, full, st);
+        else if (wpl <= 2) launch_train_t<2>(p, a, full, st);
+        else if (wpl <= 3) launch_train_t<3>(p, a, full, st);
+        else if (wpl <= 4) launch_train_t<4>(p, a, full, st);
+        else if (wpl <= 6) launch_train_t<6>(p, a, full, st);
+        else if (wpl <= 8) launch_train_t<8>(p, a, full, st);
+        else if (wpl <= 10) launch_train_t<10>(p, a, full, st);
+        else if (wpl <= 12) launch_train_t<12>(p, a, full, st);
+        else if (wpl <= 16) launch_train_t<16>(p, a, full, st);
+        else if (wpl <= 20) launch_train_t<20>(p, a, full, st);
+        else return TM_ELIMIT;
+        TM_HIP(h, hipGetLastError());
+    }
     return TM_OK;
 }
 
@@ -835,6 +917,8 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
     hipStream_t st = (hipStream_t)stream;
     TM_HIP(h, hipSetDevice(h->cfg.device));
     const Dims &d = h->d;
+    // the evaluation loop addresses XT rows with 32-bit byte offsets
+    if ((int64_t)d.Wf * ((q + 63) & ~(int64_t)63) * 4 >= ((int64_t)1 << 32)) return TM_ELIMIT;
     const WsLayout L = ws_layout(d, q);
     char *base = (char *)ws;
     h->bound = false;
