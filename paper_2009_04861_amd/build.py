@@ -10,6 +10,9 @@ HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950",
     # packed fp32 instructions are not wanted on this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the per-slot loops of the training kernel must unroll completely even for
+    # 20 register slots, or the automata fall out of registers into scratch
+    "-mllvm", "-pragma-unroll-threshold=1000000",
     "-shared", "-fPIC",
 ]
 

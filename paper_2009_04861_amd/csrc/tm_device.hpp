@@ -78,6 +78,23 @@ __device__ __forceinline__ int lane_id() { return (int)__builtin_amdgcn_mbcnt_hi
 // reinforcing Exclude subtracts 1 (Section 2.2 of the paper: the state is a
 // counter), both saturating at the ends of the range.
 
+// The planes of one register slot travel as one 8-wide vector value, so that a
+// clause with many slots is a short array of vectors the compiler keeps in VGPRs.
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ void get_slot(const u32x8 &v, uint32_t (&s)[8])
+{
+#pragma unroll
+    for (int b = 0; b < 8; ++b) s[b] = v[b];
+}
+__device__ __forceinline__ void put_slot(u32x8 &v, const uint32_t (&s)[8])
+{
+    u32x8 t;
+#pragma unroll
+    for (int b = 0; b < 8; ++b) t[b] = s[b];
+    v = t;
+}
+
 struct SatConst {
     uint32_t kmax[8]; // per plane: 0 if that bit of the top value is 1, else ~0
     uint32_t kmin[8]; // same for the bottom value

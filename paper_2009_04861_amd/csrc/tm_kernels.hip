@@ -344,7 +344,7 @@ struct TrainArgs {
 // negated literals}; padded with eight empty entries.  Rebuilt whenever plane 7
 // changes.
 template <int WPL>
-__device__ __forceinline__ int build_entries(const uint32_t (&p)[WPL][8], uint32_t *lmask, uint32_t *eoff,
+__device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lmask, uint32_t *eoff,
                                              uint2 *emask, int lane, int Wf, int W, uint32_t row_bytes)
 {
 #pragma unroll
@@ -425,19 +425,18 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
     const int T = d.T;
     const uint32_t row_bytes = (uint32_t)a.qp * 4u;
 
-    uint32_t p[WPL][8];
+    u32x8 p[WPL];
 #pragma unroll
     for (int r = 0; r < WPL; ++r) {
         const int lw = r * 64 + lane;
+        u32x8 t = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
         if (lw < d.W) {
             const uint4 *src = reinterpret_cast<const uint4 *>(a.planes + ((int64_t)g * d.W + lw) * 8);
             const uint4 v0 = src[0], v1 = src[1];
-            p[r][0] = v0.x; p[r][1] = v0.y; p[r][2] = v0.z; p[r][3] = v0.w;
-            p[r][4] = v1.x; p[r][5] = v1.y; p[r][6] = v1.z; p[r][7] = v1.w;
-        } else {
-#pragma unroll
-            for (int b = 0; b < 8; ++b) p[r][b] = 0u;
+            t[0] = v0.x; t[1] = v0.y; t[2] = v0.z; t[3] = v0.w;
+            t[4] = v1.x; t[5] = v1.y; t[6] = v1.z; t[7] = v1.w;
         }
+        p[r] = t;
     }
     int nent = build_entries<WPL>(p, lmask, eoff, emask, lane, d.Wf, d.W, row_bytes);
 
@@ -512,22 +511,42 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
             const bool Cout = (obits >> l) & 1; // clause output on the state before the update
             const uint32_t *xrow = X + ii * d.Wf;
             uint32_t changed = 0;
+            // words of this example in lane = literal-word layout.  Slot geometry (which half, which
+            // bits exist) is recomputed from a laundered index wherever it is needed: it is
+            // example-independent, and the compiler would otherwise keep it in VGPRs for every slot.
+            uint32_t xw[WPL];
+#pragma unroll
+            for (int r = 0; r < WPL; ++r) {
+                uint32_t lw = (uint32_t)(r * 64 + lane);
+                asm volatile("" : "+v"(lw));
+                const bool act = lw < (uint32_t)d.W;
+                const uint32_t fw = act ? (lw >= (uint32_t)d.Wf ? lw - (uint32_t)d.Wf : lw) : 0u;
+                xw[r] = xrow[fw];
+            }
+            auto literal = [&](uint32_t lw, uint32_t x, uint32_t &valid) {
+                const bool act = lw < (uint32_t)d.W;
+                const bool neg = lw >= (uint32_t)d.Wf;
+                const uint32_t fw = neg ? lw - (uint32_t)d.Wf : lw;
+                valid = act ? (fw == (uint32_t)d.Wf - 1u ? d.tailmask : ~0u) : 0u;
+                return (x ^ (neg ? ~0u : 0u)) & valid; // 0 on padding bits and idle lanes
+            };
             if (tgt != pos) {
                 // Type II feedback (Table 2): where the clause is 1 and the literal 0, push Exclude towards Include
                 if (Cout) {
                     ++n_type2;
 #pragma unroll
                     for (int r = 0; r < WPL; ++r) {
-                        const int lw = r * 64 + lane;
-                        const bool act = lw < d.W;
-                        const bool neg = lw >= d.Wf;
-                        const int fw = act ? (neg ? lw - d.Wf : lw) : 0;
-                        const uint32_t valid = act ? (fw == d.Wf - 1 ? d.tailmask : ~0u) : 0u;
-                        const uint32_t lit = (xrow[fw] ^ (neg ? ~0u : 0u)) & valid;
-                        const uint32_t m = ~lit & ~p[r][7] & valid; // excluded automata (below the top bit) cannot overflow
-                        const uint32_t old7 = p[r][7];
-                        ripple_inc(p[r], m);
-                        changed |= p[r][7] ^ old7;
+                        uint32_t lw = (uint32_t)(r * 64 + lane);
+                        asm volatile("" : "+v"(lw));
+                        uint32_t valid;
+                        const uint32_t lit = literal(lw, xw[r], valid);
+                        uint32_t sp[8];
+                        get_slot(p[r], sp);
+                        const uint32_t old7 = sp[7];
+                        const uint32_t m = ~lit & ~old7 & valid; // excluded automata (below the top bit) cannot overflow
+                        ripple_inc(sp, m);
+                        changed |= sp[7] ^ old7;
+                        put_slot(p[r], sp);
                     }
                 }
             } else {
@@ -535,12 +554,11 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
                 ++n_type1;
 #pragma unroll
                 for (int r = 0; r < WPL; ++r) {
-                    const int lw = r * 64 + lane;
-                    const bool act = lw < d.W;
-                    const bool neg = lw >= d.Wf;
-                    const int fw = act ? (neg ? lw - d.Wf : lw) : 0;
-                    const uint32_t valid = act ? (fw == d.Wf - 1 ? d.tailmask : ~0u) : 0u;
-                    const uint32_t lit = (xrow[fw] ^ (neg ? ~0u : 0u)) & valid;
+                    // The literal-word index is laundered through an empty asm so that the
+                    // compiler does not hoist the example-independent first Philox round of
+                    // every slot and block out of the example loop (dozens of live VGPRs per slot).
+                    uint32_t lw = (uint32_t)(r * 64 + lane);
+                    asm volatile("" : "+v"(lw));
                     // bit-sliced comparison of 32 16-bit uniforms with thr, least significant bit first:
                     // ge = [u >= thr]; bit b of literal j's uniform is bit j of random word b;
                     // thr bit 1: ge &= w, thr bit 0: ge |= w, i.e. majority(w, ge, ~thr bit)
@@ -548,7 +566,7 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
                         if (t >= first_blk) {
-                            const U4 R = draw(d.key, STREAM_TYPE1, 4u * (uint32_t)lw + (uint32_t)t, (uint32_t)g,
+                            const U4 R = draw(d.key, STREAM_TYPE1, 4u * lw + (uint32_t)t, (uint32_t)g,
                                               (uint64_t)ii, a.epoch);
                             const uint32_t w[4] = {R.x, R.y, R.z, R.w};
 #pragma unroll
@@ -558,15 +576,23 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
                             }
                         }
                     }
-                    const uint32_t old7 = p[r][7];
+                    uint32_t valid;
+                    const uint32_t lit = literal(lw, xw[r], valid);
+                    uint32_t sp[8];
+                    get_slot(p[r], sp);
+                    const uint32_t old7 = sp[7];
                     if (Cout) { // strong: literals that are 1 move towards Include with probability (s-1)/s
-                        const uint32_t m = lit & ge & ~at_value<FULL>(p[r], a.sat.kmax, true);
-                        ripple_inc(p[r], m);
+                        const uint32_t m = lit & ge & ~at_value<FULL>(sp, a.sat.kmax, true);
+                        ripple_inc(sp, m);
                     }
                     // weak: everything else moves towards Exclude with probability 1/s
-                    const uint32_t wk = (Cout ? ~lit : ~0u) & ~ge & valid & ~at_value<FULL>(p[r], a.sat.kmin, false);
-                    ripple_dec(p[r], wk);
-                    changed |= p[r][7] ^ old7;
+                    const uint32_t wk = (Cout ? ~lit : ~0u) & ~ge & valid & ~at_value<FULL>(sp, a.sat.kmin, false);
+                    ripple_dec(sp, wk);
+                    changed |= sp[7] ^ old7;
+                    put_slot(p[r], sp);
+                    // keep the slots apart in the instruction schedule: interleaving them
+                    // multiplies the live registers by the number of slots
+                    if (WPL > 2) __builtin_amdgcn_sched_barrier(0);
                 }
             }
             if (ballot(changed != 0u)) { // the conjunction changed: re-evaluate this and the later examples
@@ -601,9 +627,10 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
         const int lw = r * 64 + lane;
         if (lw < d.W) {
             uint4 *dst = reinterpret_cast<uint4 *>(a.planes + ((int64_t)g * d.W + lw) * 8);
-            dst[0] = make_uint4(p[r][0], p[r][1], p[r][2], p[r][3]);
-            dst[1] = make_uint4(p[r][4], p[r][5], p[r][6], p[r][7]);
-            a.inc[(int64_t)g * d.W + lw] = p[r][7];
+            const u32x8 t = p[r];
+            dst[0] = make_uint4(t[0], t[1], t[2], t[3]);
+            dst[1] = make_uint4(t[4], t[5], t[6], t[7]);
+            a.inc[(int64_t)g * d.W + lw] = t[7];
         }
     }
     if (lane == 0) {
