@@ -365,6 +365,48 @@ void otm_feedback_step(const otm_config *cfg, int32_t *state, const uint8_t *X,
     free(lit);
 }
 
+/* The same frozen-snapshot pass for a chosen subset of clauses only (each
+ * clause's trajectory is independent of the others under a frozen snapshot, so
+ * a few clauses of a machine too large to run in full can be followed alone).
+ * state is the full [C][2o] array; ostar_sub is [n_ids][q], row r belonging to
+ * clause ids[r]; the live tally is not kept. */
+void otm_feedback_step_subset(const otm_config *cfg, int32_t *state, const uint8_t *X,
+                              const int32_t *y, int64_t q, const int32_t *vhat,
+                              uint8_t *ostar_sub, uint32_t epoch, int64_t i0, int64_t cnt,
+                              const int32_t *ids, int32_t n_ids, int64_t *fired_count)
+{
+    int L = 2 * cfg->o;
+    uint8_t *lit = (uint8_t *)malloc((size_t)L);
+    int64_t fired = 0;
+    for (int r = 0; r < n_ids; ++r) {
+        int g = ids[r];
+        int c = g / cfg->n;
+        for (int64_t i = i0; i < i0 + cnt && i < q; ++i) {
+            int32_t scratch_tally = 0;
+            literals(cfg, X + i * cfg->o, lit);
+            int role = role_of(cfg, c, y[i], epoch, i);
+            fired += visit(cfg, state, g, lit, i, epoch, role, vhat[i * cfg->m + c],
+                           &scratch_tally, &ostar_sub[(size_t)r * q + i]);
+        }
+    }
+    if (fired_count) *fired_count = fired;
+    free(lit);
+}
+
+/* out[r][i] = C_{ids[r]}(X_i) for a subset of clauses */
+void otm_clause_outputs_subset(const otm_config *cfg, const int32_t *state, const uint8_t *X,
+                               int64_t q, const int32_t *ids, int32_t n_ids, uint8_t *out)
+{
+    int L = 2 * cfg->o;
+    uint8_t *lit = (uint8_t *)malloc((size_t)L);
+    for (int64_t i = 0; i < q; ++i) {
+        literals(cfg, X + i * cfg->o, lit);
+        for (int r = 0; r < n_ids; ++r)
+            out[(size_t)r * q + i] = (uint8_t)clause_output(cfg, state + (size_t)ids[r] * L, lit);
+    }
+    free(lit);
+}
+
 /* Sequential execution of Algorithm 1 with live tallies (one legal schedule of
  * the asynchronous method): examples outermost if example_major, else clauses
  * outermost. */

@@ -136,6 +136,26 @@ class Oracle:
                                 ctypes.c_int64(cnt), ctypes.byref(fired))
         return fired.value
 
+    def clause_outputs_subset(self, X, ids):
+        q = X.shape[0]
+        _chk(X, np.uint8, (q, self.o))
+        ids = np.ascontiguousarray(ids, dtype=np.int32)
+        out = np.zeros((len(ids), q), dtype=np.uint8)
+        lib().otm_clause_outputs_subset(ctypes.byref(self.cfg), _p(self.state), _p(X), ctypes.c_int64(q), _p(ids),
+                                        ctypes.c_int32(len(ids)), _p(out))
+        return out
+
+    def feedback_step_subset(self, X, y, vhat, ostar_sub, epoch, i0, cnt, ids):
+        q = X.shape[0]
+        ids = np.ascontiguousarray(ids, dtype=np.int32)
+        _chk(X, np.uint8, (q, self.o)); _chk(y, np.int32, (q,))
+        _chk(vhat, np.int32, (q, self.m)); _chk(ostar_sub, np.uint8, (len(ids), q))
+        fired = ctypes.c_int64(0)
+        lib().otm_feedback_step_subset(ctypes.byref(self.cfg), _p(self.state), _p(X), _p(y), ctypes.c_int64(q),
+                                       _p(vhat), _p(ostar_sub), ctypes.c_uint32(epoch), ctypes.c_int64(i0),
+                                       ctypes.c_int64(cnt), _p(ids), ctypes.c_int32(len(ids)), ctypes.byref(fired))
+        return fired.value
+
     def async_epoch(self, X, y, tally, ostar, epoch, example_major=True):
         q = X.shape[0]
         _chk(X, np.uint8, (q, self.o)); _chk(y, np.int32, (q,))

@@ -1,0 +1,99 @@
+"""Parity at the benchmark's full size (image-like workload: 60,000 x 784, 10 classes x
+2,000 clauses), in the launch configuration bench.py times.  The oracle cannot run the
+whole machine in reasonable time, so it follows sampled clauses (whose trajectories are
+independent under a frozen tally snapshot) and sampled examples; properties that hold at
+any size cover the rest.  No expected value comes from the HIP path: the frozen snapshot
+is synthetic."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tm_oracle as O
+from paper_2009_04861_amd import binding as B
+from paper_2009_04861_amd import synth
+from tests.helpers import bits_to_u8, dev_bits, dev_i32, push_state, sparse_random_state
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def workload():
+    return synth.image_like()
+
+
+def test_full_size_training_pass_sampled_clauses(workload, device):
+    Xtr, ytr, Xte, yte = workload
+    hp = synth.WORKLOADS["image_like"]
+    m, n, o = hp["m"], hp["n"], hp["o"]
+    q = len(ytr)
+    print("full size: oracle init", flush=True)
+    ora = O.Oracle(seed=3, **hp)
+    gpu = B.TsetlinMachine(seed=3, **hp)
+    rng = np.random.default_rng(0)
+    # sampled clauses: both polarities, first / last class, first / last clause
+    ids = np.array([0, 1, n - 1, 3 * n + 500, 3 * n + 501, 7 * n + 1234, m * n - 2, m * n - 1], dtype=np.int32)
+    st0 = gpu.get_ta_state().cpu().numpy().astype(np.int32) + 1
+    assert np.array_equal(st0[ids], ora.state[ids])
+    del st0
+
+    print("full size: bind", flush=True)
+    gpu.bind_train(dev_bits(gpu, Xtr), dev_i32(gpu, ytr))
+    # tally pre-calculation on sampled examples (exact vote sums of all 20,000 clauses)
+    ex = np.concatenate([[0, 1, 63, 64, q - 1], rng.integers(0, q, size=27)])
+    want = ora.class_sums(np.ascontiguousarray(Xtr[ex]), clamp=False)
+    got = gpu.tallies().cpu().numpy()
+    assert np.array_equal(got[ex], want)
+    ostar_sub = ora.clause_outputs_subset(Xtr, ids)
+    prev = gpu.prev_outputs()
+    assert np.array_equal(bits_to_u8(prev[torch.from_numpy(ids).long().to(prev.device)], q), ostar_sub)
+
+    print("full size: frozen pass", flush=True)
+    vhat = rng.integers(-hp["T"], hp["T"] + 1, size=(q, m)).astype(np.int32)   # synthetic snapshot
+    B.tm_set_epoch(gpu.h, 5)
+    gpu.feedback_step(dev_i32(gpu, vhat), 0, q)
+    fired = ora.feedback_step_subset(Xtr, ytr, vhat, ostar_sub, 5, 0, q, ids)
+    assert fired > 1000
+    st1 = gpu.get_ta_state()[torch.from_numpy(ids).long().to(gpu.dev)].cpu().numpy().astype(np.int32) + 1
+    assert np.array_equal(st1, ora.state[ids])
+    prev = gpu.prev_outputs()
+    assert np.array_equal(bits_to_u8(prev[torch.from_numpy(ids).long().to(prev.device)], q), ostar_sub)
+
+    print("full size: tally == signed sum of stored outputs", flush=True)
+    tally = gpu.tallies().cpu().numpy()
+    sign = np.where(np.arange(n) % 2 == 1, 1, -1).astype(np.int32)
+    for c in range(m):
+        bits = bits_to_u8(prev[c * n:(c + 1) * n], q)          # [n][q]
+        assert np.array_equal(tally[:, c], sign @ bits.astype(np.int32))
+
+    print("full size: asynchronous epoch + refresh pass", flush=True)
+    gpu.fit_epoch()
+    st = gpu.get_ta_state()
+    assert int(st.max()) <= 255
+    gpu.sync_tallies()
+    ora.state[:] = st.cpu().numpy().astype(np.int32) + 1
+    got = gpu.tallies().cpu().numpy()
+    assert np.array_equal(got[ex], ora.class_sums(np.ascontiguousarray(Xtr[ex]), clamp=False))
+    gpu.close()
+
+
+def test_full_size_inference_sampled_examples(workload, device):
+    Xtr, ytr, Xte, yte = workload
+    hp = synth.WORKLOADS["image_like"]
+    rng = np.random.default_rng(1)
+    ora = O.Oracle(seed=4, init=False, **hp)
+    ora.state[:] = sparse_random_state(rng, ora.C, ora.L, hp["N"], 3.0 / hp["o"])
+    gpu = B.TsetlinMachine(seed=4, **hp)
+    push_state(gpu, ora.state)
+    Xd = dev_bits(gpu, Xte)
+    sums = gpu.class_sums(Xd).cpu().numpy()
+    pred = gpu.predict(Xd).cpu().numpy()
+    ex = np.concatenate([[0, 255, 256, len(yte) - 1], rng.integers(0, len(yte), size=44)])
+    Xs = np.ascontiguousarray(Xte[ex])
+    want = ora.class_sums(Xs)
+    assert np.abs(want).max() > 0
+    assert np.array_equal(sums[ex], want)
+    assert np.array_equal(pred[ex], ora.predict(Xs))
+    # properties at any size: clamped range, argmax consistent with the sums
+    assert sums.min() >= -hp["T"] and sums.max() <= hp["T"]
+    assert np.array_equal(pred, sums.argmax(axis=1))
+    gpu.close()

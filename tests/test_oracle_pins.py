@@ -510,3 +510,21 @@ def test_sequential_algorithm1_is_schedule_independent_between_loop_orders():
         a.async_epoch(Xtr, ytr, ta, oa, ep, True)
         b.async_epoch(Xtr, ytr, tb, ob, ep, False)
     assert np.array_equal(a.state, b.state) and np.array_equal(ta, tb) and np.array_equal(oa, ob)
+
+
+def test_subset_step_equals_full_step_on_those_clauses():
+    # the subset routines are the full ones restricted to some clauses
+    rng = np.random.default_rng(9)
+    X = rng.integers(0, 2, size=(120, 20), dtype=np.uint8)
+    y = rng.integers(0, 3, size=120).astype(np.int32)
+    a = O.Oracle(3, 6, 20, 10, 5, 3.0, 4)
+    b = O.Oracle(3, 6, 20, 10, 5, 3.0, 4)
+    vhat = rng.integers(-5, 6, size=(120, 3)).astype(np.int32)
+    tally, ostar = a.sync_tallies(X)
+    ids = np.array([0, 5, 7, 17], dtype=np.int32)
+    sub = b.clause_outputs_subset(X, ids)
+    assert np.array_equal(sub, ostar[ids])
+    a.feedback_step(X, y, vhat, tally, ostar, 2, 0, 120)
+    b.feedback_step_subset(X, y, vhat, sub, 2, 0, 120, ids)
+    assert np.array_equal(a.state[ids], b.state[ids])
+    assert np.array_equal(sub, ostar[ids])
