@@ -209,6 +209,7 @@ def main():
             "gate_rate_of_candidates": cnt["fired"] / max(1, cnt["candidates"]),
             "type1_per_epoch": cnt["type1"] / args.steps,
             "tally_changes_per_epoch": cnt["tally_changes"] / args.steps,
+            "blocks_evaluated_fraction": cnt["blocks_evaluated"] / max(1, args.steps * C * ((q + 63) // 64)),
             "test_accuracy_after_run": acc,
         },
         "roofline": {

@@ -163,10 +163,10 @@ def tm_get_epoch(h):
 
 
 def tm_read_counters(h):
-    out = (ctypes.c_uint64 * 6)()
+    out = (ctypes.c_uint64 * 7)()
     _check(lib().tm_read_counters(h, out, _stream()), "tm_read_counters")
     return {"pairs": out[0], "fired": out[1], "type1": out[2], "tally_changes": out[3],
-            "candidates": out[4], "type2_active": out[5]}
+            "candidates": out[4], "type2_active": out[5], "blocks_evaluated": out[6]}
 
 
 class TsetlinMachine:

@@ -191,6 +191,13 @@ __global__ void k_copy_rows(const uint32_t *src, int64_t src_stride, uint32_t *d
     dst[r * dst_stride + w] = src[r * src_stride + w];
 }
 
+// fresh[g] = {plo, phi, slo, 0}: nothing outdated (0, 0, qp) or everything outdated (0, qp, qp)
+__global__ void k_fresh_set(int32_t *fresh, int C, int qp, int all_stale)
+{
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g < C) *reinterpret_cast<int4 *>(fresh + (int64_t)g * 4) = make_int4(0, all_stale ? qp : 0, qp, 0);
+}
+
 // ------------------------------------------------------------------------
 // k_eval: clause evaluation, lane = clause   (Eq. 1, Eq. 3, Section 3.1)
 // ------------------------------------------------------------------------
@@ -331,6 +338,7 @@ struct TrainArgs {
     int32_t *tally;
     const int32_t *vhat; // [q][m] snapshot the gate reads instead of the live tally, or null
     uint32_t *ostar;
+    int32_t *fresh; // [C][4] per clause: examples whose stored output may be outdated lie in [plo,phi) or [slo,qp)
     unsigned long long *counters;
     int64_t q, qp, Qw, i_begin, i_end;
     uint32_t epoch;
@@ -446,7 +454,20 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
     const int first_blk = min(tz >> 2, 4);
     const uint32_t ge_init = d.thr >= 65536u ? 0u : ~0u;
 
-    unsigned long long n_pairs = 0, n_fired = 0, n_type1 = 0, n_changes = 0, n_cand = 0, n_type2 = 0;
+    unsigned long long n_pairs = 0, n_fired = 0, n_type1 = 0, n_changes = 0, n_cand = 0, n_type2 = 0, n_eval = 0;
+
+    // Which stored previous outputs o* can differ from the clause's current output: only
+    // those not re-evaluated since the include mask last changed.  Kept per clause as two
+    // example ranges, a prefix part [plo, phi) and a suffix [slo, qp); a block outside both
+    // needs no evaluation and no refresh unless one of its gates fires (the result is the
+    // same as refreshing every visited pair, the comparison o != o* would be false).
+    int plo, phi, slo;
+    {
+        const int4 f = *reinterpret_cast<const int4 *>(a.fresh + (int64_t)g * 4);
+        plo = __builtin_amdgcn_readfirstlane(f.x);
+        phi = __builtin_amdgcn_readfirstlane(f.y);
+        slo = __builtin_amdgcn_readfirstlane(f.z);
+    }
 
     // Per-block inputs (label, negative class, tally, previous-output words) are
     // fetched one block ahead so that their latency hides behind the current block.
@@ -499,6 +520,13 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
         n_pairs += __builtin_popcountll(rmask);
         n_fired += __builtin_popcountll(fmask);
         n_cand += __builtin_popcountll(ballot(cand));
+
+        const int b0 = (int)i0, b1 = (int)i0 + 64;
+        const bool stale = (b0 < phi && b1 > plo) || (b1 > slo);
+        if (!stale && fmask == 0) continue;
+        ++n_eval;
+        const bool whole = i0 >= a.i_begin && (i0 + 64 <= a.i_end || a.i_end == a.q);
+        bool mask_changed = false;
 
         const uint32_t *xt_block = XT + i0;
         uint64_t obits = eval64(eoff, emask, nent, xt_block, lane);
@@ -596,6 +624,7 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
                 }
             }
             if (ballot(changed != 0u)) { // the conjunction changed: re-evaluate this and the later examples
+                mask_changed = true;
                 nent = build_entries<WPL>(p, lmask, eoff, emask, lane, d.Wf, d.W, row_bytes);
                 const uint64_t nb = eval64(eoff, emask, nent, xt_block, lane);
                 const uint64_t keep = (1ull << l) - 1ull;
@@ -620,7 +649,18 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
             }
             n_changes += __builtin_popcountll(diff);
         }
+        if (whole) { // this block is up to date again
+            if (b0 <= plo) plo = max(plo, b1);
+            if (b0 <= slo) slo = max(slo, b1);
+        }
+        if (mask_changed) { // everything not visited after the change is outdated now
+            plo = 0;
+            phi = b1;
+            slo = b1;
+        }
     }
+    if (plo >= phi) plo = phi = 0;
+    if (lane == 0) *reinterpret_cast<int4 *>(a.fresh + (int64_t)g * 4) = make_int4(plo, phi, slo, 0);
 
 #pragma unroll
     for (int r = 0; r < WPL; ++r) {
@@ -640,6 +680,7 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
         atomicAdd(&a.counters[3], n_changes);
         atomicAdd(&a.counters[4], n_cand);
         atomicAdd(&a.counters[5], n_type2);
+        atomicAdd(&a.counters[6], n_eval);
     }
 }
 
@@ -666,6 +707,7 @@ struct tm_handle {
     uint32_t *ostar;
     uint32_t *XT;
     int32_t *negcls;
+    int32_t *fresh;
     unsigned long long *counters;
     int32_t *flag;
     uint32_t epoch;
@@ -712,7 +754,7 @@ Dims make_dims(const tm_config *cfg)
 }
 
 struct WsLayout {
-    size_t tally, ostar, xt, negcls, counters, flag, total;
+    size_t tally, ostar, xt, negcls, fresh, counters, flag, total;
 };
 
 WsLayout ws_layout(const Dims &d, int64_t q)
@@ -725,6 +767,7 @@ WsLayout ws_layout(const Dims &d, int64_t q)
     L.ostar = off; off += align256((size_t)d.C * Qw * 4);
     L.xt = off; off += align256((size_t)d.Wf * qp * 4);
     L.negcls = off; off += align256((size_t)qp * 4);
+    L.fresh = off; off += align256((size_t)d.C * 16);
     L.counters = off; off += 256;
     L.flag = off; off += 256;
     L.total = off;
@@ -832,7 +875,7 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     TrainArgs a;
     const TrainPtrs p{h->X, h->XT, h->y, h->negcls};
     a.d = d; a.sat = h->sat; a.planes = h->planes; a.inc = h->inc; a.tally = h->tally;
-    a.vhat = vhat; a.ostar = h->ostar; a.counters = h->counters;
+    a.vhat = vhat; a.ostar = h->ostar; a.fresh = h->fresh; a.counters = h->counters;
     a.q = h->q; a.qp = h->qp; a.Qw = h->Qw; a.epoch = h->epoch;
     a.lds_mask_words = (d.W + 3) & ~3;
     a.lds_off_words = (d.Wf + 8 + 3) & ~3;
@@ -866,12 +909,22 @@ int run_negcls(tm_handle *h, hipStream_t st)
     return TM_OK;
 }
 
+int fresh_set(tm_handle *h, bool all_stale, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_fresh_set, dim3(blocks_for(h->d.C, 256)), dim3(256), 0, st, h->fresh, h->d.C, (int)h->qp,
+                       all_stale ? 1 : 0);
+    TM_HIP(h, hipGetLastError());
+    return TM_OK;
+}
+
 int sync_tallies(tm_handle *h, hipStream_t st)
 {
     const Dims &d = h->d;
     int rc = fill(h, h->tally, (size_t)d.m * h->qp * 4, 0u, st);
     if (rc) return rc;
-    return launch_eval(h, h->X, h->q, h->ostar, h->Qw, h->tally, 1, h->qp, st);
+    rc = launch_eval(h, h->X, h->q, h->ostar, h->Qw, h->tally, 1, h->qp, st);
+    if (rc) return rc;
+    return fresh_set(h, false, st); // every stored output is current
 }
 
 } // namespace
@@ -956,6 +1009,7 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
     h->ostar = (uint32_t *)(base + L.ostar);
     h->XT = (uint32_t *)(base + L.xt);
     h->negcls = (int32_t *)(base + L.negcls);
+    h->fresh = (int32_t *)(base + L.fresh);
     h->counters = (unsigned long long *)(base + L.counters);
     h->flag = (int32_t *)(base + L.flag);
 
@@ -1059,6 +1113,7 @@ int tm_set_ta_state(tm_handle *h, const uint8_t *in, void *stream)
     hipLaunchKernelGGL(k_set_state, dim3(blocks_for(nt, 256)), dim3(256), 0, (hipStream_t)stream, h->d, in,
                        h->planes, h->inc);
     TM_HIP(h, hipGetLastError());
+    if (h->bound) return fresh_set(h, true, (hipStream_t)stream); // stored outputs no longer match the clauses
     return TM_OK;
 }
 
@@ -1122,10 +1177,10 @@ int tm_read_counters(tm_handle *h, uint64_t *out, void *stream)
     if (!h->bound) return TM_ESTATE;
     hipStream_t st = (hipStream_t)stream;
     TM_HIP(h, hipSetDevice(h->cfg.device));
-    unsigned long long tmp[6];
+    unsigned long long tmp[7];
     TM_HIP(h, hipMemcpyAsync(tmp, h->counters, sizeof(tmp), hipMemcpyDeviceToHost, st));
     TM_HIP(h, hipStreamSynchronize(st));
-    for (int k = 0; k < 6; ++k) out[k] = tmp[k];
+    for (int k = 0; k < 7; ++k) out[k] = tmp[k];
     return fill(h, h->counters, 256, 0u, st);
 }
 

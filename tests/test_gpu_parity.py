@@ -175,6 +175,47 @@ def test_feedback_reaches_both_ends_of_the_state_range(s, N, device):
     assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar)
 
 
+def test_set_state_after_bind_then_step_refreshes_everything(device):
+    # the stored previous outputs come from the old clauses; a pass must repair all of them
+    m, n, o, N, T, s = 3, 6, 37, 20, 4, 3.0
+    rng = np.random.default_rng(77)
+    q = 300
+    ora, gpu = make_pair(m, n, o, N, T, s, 5)
+    X, y = rand_problem(rng, q, o, m)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)                       # tallies / outputs of the initial clauses
+    ora.state[:] = sparse_random_state(rng, ora.C, ora.L, N, 2.0 / o)
+    push_state(gpu, ora.state)                               # new clauses, no re-synchronisation
+    for ep, (i0, cnt) in enumerate([(100, 100), (0, q), (0, q)]):
+        B.tm_set_epoch(gpu.h, ep)
+        run_frozen(ora, gpu, X, y, ep, i0, cnt, tally, ostar)
+        assert np.array_equal(gpu_state_as_oracle(gpu), ora.state)
+        assert np.array_equal(gpu.tallies().cpu().numpy(), tally)
+        assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar)
+
+
+def test_quiet_epochs_skip_evaluation_but_change_nothing(device):
+    # T = 1 closes almost every gate once the sums reach the margin: most blocks are skipped
+    m, n, o, N, T, s = 2, 20, 30, 50, 1, 3.0
+    rng = np.random.default_rng(78)
+    q = 1000
+    ora, gpu = make_pair(m, n, o, N, T, s, 6)
+    X, y = rand_problem(rng, q, o, m)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    gpu.counters()
+    for ep in range(8):
+        B.tm_set_epoch(gpu.h, ep)
+        run_frozen(ora, gpu, X, y, ep, 0, q, tally, ostar)
+    assert np.array_equal(gpu_state_as_oracle(gpu), ora.state)
+    assert np.array_equal(gpu.tallies().cpu().numpy(), tally)
+    assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar)
+    c = gpu.counters()
+    blocks = 8 * ora.C * ((q + 63) // 64)
+    assert 0 < c["blocks_evaluated"] <= blocks
+    print("blocks evaluated: %d of %d" % (c["blocks_evaluated"], blocks), flush=True)
+
+
 def test_noisy_xor_frozen_epochs_match(device):
     # the small benchmark configuration, whole epochs, snapshot = tallies at epoch start
     Xtr, ytr, Xte, yte = synth.noisy_xor(1000, 500)
