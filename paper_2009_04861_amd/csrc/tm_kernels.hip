@@ -344,6 +344,7 @@ struct TrainArgs {
     uint32_t epoch;
     int lds_mask_words; // W rounded up to a multiple of 4
     int lds_off_words;  // Wf + 8 rounded up to a multiple of 4
+    int lds_wave_words; // LDS words per wavefront
 };
 
 // The clause as the evaluation loop wants it: one entry per feature word whose
@@ -360,7 +361,7 @@ __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lm
         const int lw = r * 64 + lane;
         if (lw < W) lmask[lw] = p[r][7];
     }
-    __syncthreads(); // one wavefront per workgroup: orders the LDS traffic, costs nothing
+    wave_lds_sync();
     int n = 0;
     for (int f0 = 0; f0 < Wf; f0 += 64) {
         const int fw = f0 + lane;
@@ -380,7 +381,7 @@ __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lm
         eoff[n + lane] = 0u;
         emask[n + lane] = make_uint2(0u, 0u);
     }
-    __syncthreads();
+    wave_lds_sync();
     return n;
 }
 
@@ -414,19 +415,24 @@ __device__ __forceinline__ uint64_t eval64(const uint32_t *eoff, const uint2 *em
     return ballot(viol == 0u);
 }
 
+constexpr int COUNTER_SETS = 64; // interleaved copies of the 8 event counters
+constexpr int TRAIN_WAVES = 4; // clauses (wavefronts) per workgroup of the training kernel
+
 template <int WPL, bool FULL>
-__global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
+__global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
                                               const int32_t *__restrict__ y, const int32_t *__restrict__ negcls,
                                               const TrainArgs a)
 {
     extern __shared__ uint32_t lds[];
-    uint32_t *lmask = lds;                                  // [W] include masks, literal-word order
-    uint32_t *eoff = lds + a.lds_mask_words;                // [Wf + 8] (rounded to 4 words)
+    const Dims &d = a.d;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int g = blockIdx.x * TRAIN_WAVES + wave;
+    if (g >= d.C) return; // whole wavefront; the kernel has no workgroup-wide barrier
+    uint32_t *lmask = lds + wave * a.lds_wave_words;        // [W] include masks, literal-word order
+    uint32_t *eoff = lmask + a.lds_mask_words;              // [Wf + 8] (rounded to 4 words)
     uint2 *emask = reinterpret_cast<uint2 *>(eoff + a.lds_off_words);
 
-    const Dims &d = a.d;
-    const int lane = threadIdx.x;
-    const int g = blockIdx.x;
     const int c = g / d.n;
     const bool pos = ((g - c * d.n) & 1) != 0; // odd index within the class: positive polarity
     const int sign = pos ? 1 : -1;
@@ -673,14 +679,12 @@ __global__ __launch_bounds__(64) void k_train(const uint32_t *__restrict__ X, co
             a.inc[(int64_t)g * d.W + lw] = t[7];
         }
     }
-    if (lane == 0) {
-        atomicAdd(&a.counters[0], n_pairs);
-        atomicAdd(&a.counters[1], n_fired);
-        atomicAdd(&a.counters[2], n_type1);
-        atomicAdd(&a.counters[3], n_changes);
-        atomicAdd(&a.counters[4], n_cand);
-        atomicAdd(&a.counters[5], n_type2);
-        atomicAdd(&a.counters[6], n_eval);
+    // event counters: 64 interleaved sets, because thousands of wavefronts ending at the
+    // same time on one address serialise in the L2 atomic unit (measured: ~1.7 ms per launch)
+    if (lane < 7) {
+        const unsigned long long v = lane == 0 ? n_pairs : lane == 1 ? n_fired : lane == 2 ? n_type1
+                                   : lane == 3 ? n_changes : lane == 4 ? n_cand : lane == 5 ? n_type2 : n_eval;
+        if (v) atomicAdd(&a.counters[(g & (COUNTER_SETS - 1)) * 8 + lane], v);
     }
 }
 
@@ -768,7 +772,7 @@ WsLayout ws_layout(const Dims &d, int64_t q)
     L.xt = off; off += align256((size_t)d.Wf * qp * 4);
     L.negcls = off; off += align256((size_t)qp * 4);
     L.fresh = off; off += align256((size_t)d.C * 16);
-    L.counters = off; off += 256;
+    L.counters = off; off += align256((size_t)COUNTER_SETS * 8 * 8);
     L.flag = off; off += 256;
     L.total = off;
     return L;
@@ -853,9 +857,10 @@ struct TrainPtrs {
 template <int WPL>
 void launch_train_t(const TrainPtrs &p, const TrainArgs &a, bool full, hipStream_t st)
 {
-    const size_t lds = (size_t)(a.lds_mask_words + a.lds_off_words + 2 * (a.d.Wf + 8)) * 4;
-    if (full) hipLaunchKernelGGL((k_train<WPL, true>), dim3(a.d.C), dim3(64), lds, st, p.X, p.XT, p.y, p.negcls, a);
-    else hipLaunchKernelGGL((k_train<WPL, false>), dim3(a.d.C), dim3(64), lds, st, p.X, p.XT, p.y, p.negcls, a);
+    const size_t lds = (size_t)a.lds_wave_words * TRAIN_WAVES * 4;
+    const dim3 grid((unsigned)((a.d.C + TRAIN_WAVES - 1) / TRAIN_WAVES)), block(64 * TRAIN_WAVES);
+    if (full) hipLaunchKernelGGL((k_train<WPL, true>), grid, block, lds, st, p.X, p.XT, p.y, p.negcls, a);
+    else hipLaunchKernelGGL((k_train<WPL, false>), grid, block, lds, st, p.X, p.XT, p.y, p.negcls, a);
 }
 
 // Examples per launch of the training kernel.  An epoch is cut into ranges
@@ -879,6 +884,7 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     a.q = h->q; a.qp = h->qp; a.Qw = h->Qw; a.epoch = h->epoch;
     a.lds_mask_words = (d.W + 3) & ~3;
     a.lds_off_words = (d.Wf + 8 + 3) & ~3;
+    a.lds_wave_words = a.lds_mask_words + a.lds_off_words + 2 * ((d.Wf + 8 + 1) & ~1);
     const bool full = (d.N == 128);
     const int wpl = (d.W + 63) / 64;
     const int64_t chunk = train_chunk(d);
@@ -1015,7 +1021,7 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
 
     int rc = fill(h, h->flag, 256, 0u, st);
     if (rc) return rc;
-    rc = fill(h, h->counters, 256, 0u, st);
+    rc = fill(h, h->counters, (size_t)COUNTER_SETS * 64, 0u, st);
     if (rc) return rc;
     hipLaunchKernelGGL(k_check_labels, dim3(blocks_for(q, 256)), dim3(256), 0, st, y, q, d.m, h->flag);
     TM_HIP(h, hipGetLastError());
@@ -1177,11 +1183,14 @@ int tm_read_counters(tm_handle *h, uint64_t *out, void *stream)
     if (!h->bound) return TM_ESTATE;
     hipStream_t st = (hipStream_t)stream;
     TM_HIP(h, hipSetDevice(h->cfg.device));
-    unsigned long long tmp[7];
+    unsigned long long tmp[COUNTER_SETS * 8];
     TM_HIP(h, hipMemcpyAsync(tmp, h->counters, sizeof(tmp), hipMemcpyDeviceToHost, st));
     TM_HIP(h, hipStreamSynchronize(st));
-    for (int k = 0; k < 7; ++k) out[k] = tmp[k];
-    return fill(h, h->counters, 256, 0u, st);
+    for (int k = 0; k < 7; ++k) {
+        out[k] = 0;
+        for (int c = 0; c < COUNTER_SETS; ++c) out[k] += tmp[c * 8 + k];
+    }
+    return fill(h, h->counters, (size_t)COUNTER_SETS * 64, 0u, st);
 }
 
 const char *tm_strerror(int code)
