@@ -29,11 +29,15 @@ if ROOT not in sys.path:
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 HBM_PEAK_GBS = 8000.0
 
-# Algorithmic 32-bit lane-operations of the training kernel, per unit of work.
-PHILOX_OPS = 100          # 10 rounds x (4 multiplies + 4 xors + 2 key updates)
-TYPE1_OPS_PER_WORD = 4 * PHILOX_OPS + 16 + 16 + 48 + 4   # draws, comparator, 2 saturation tests, 2 ripples, masks
-TYPE2_OPS_PER_WORD = 2 + 24
-GATE_OPS = PHILOX_OPS + 8
+# Algorithmic 32-bit lane-operations of the training kernel, per unit of work.  An operation is
+# one 32-bit integer instruction on one lane as gfx950 has them: a 32x32->64 multiply and a
+# three-input bitwise function each count as one.  Wave-uniform work (key schedule, loop
+# control) is not counted.
+PHILOX_OPS = 40           # 10 rounds x (2 multiplies + 2 three-input xors)
+TYPE1_OPS_PER_WORD = 4 * PHILOX_OPS + 16 + 8 + 32 + 6    # 4 blocks, 16-bit comparator, 2 saturation tests,
+                                                         # 2 ripples (2 ops per plane), event masks
+TYPE2_OPS_PER_WORD = 2 + 16                              # mask + one ripple
+GATE_OPS = PHILOX_OPS + 8                                # one block + clip, error, 64-bit compare
 
 
 def train_kernel_ops(counters, W):

@@ -30,6 +30,13 @@ __device__ __forceinline__ uint32_t majority3(uint32_t a, uint32_t b, uint32_t c
     return (uint32_t)__builtin_amdgcn_bitop3_b32(a, b, c, 0xE8);
 }
 
+// bit-select: where a bit of sel is 1 take it from b, else from c (operand truth
+// tables 0xF0 / 0xCC / 0xAA, so sel ? b : c is 0xCA)
+__device__ __forceinline__ uint32_t bitselect(uint32_t sel, uint32_t b, uint32_t c)
+{
+    return (uint32_t)__builtin_amdgcn_bitop3_b32(sel, b, c, 0xCA);
+}
+
 // One round costs two 32x32->64 multiplies (v_mad_u64_u32) and two 3-input xors.
 __device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                             uint32_t k0, uint32_t k1)

@@ -12,8 +12,8 @@
 //   literal word lw < Wf holds x_(32 lw + j), literal word Wf + fw holds NOT x_(32 fw + j).
 //
 // Two evaluation layouts are used:
-//   k_eval   lane = clause : include masks in VGPRs, example words arrive through
-//            scalar loads, one v_bfi per feature word and pair; clause votes are
+//   k_eval_* lane = clause : include masks in VGPRs, example words arrive through
+//            scalar loads, one bit-select per feature word and pair; clause votes are
 //            summed with wave ballot + popcount (inference, tally pre-calculation).
 //   k_train  one wavefront = one clause (Algorithm 1: "every clause runs in its own
 //            thread"); lane = literal word for feedback, lane = example for the
@@ -215,18 +215,123 @@ struct EvalArgs {
 };
 
 // A wavefront owns 64 consecutive clauses (a "tile") and a range of examples.
-// CH feature words of the include masks (plain and negated half) sit in
-// 2*CH VGPRs per lane; the words of one example are wave-uniform and come in
-// through scalar loads, so the violation test of a feature word,
+// The words of one example are wave-uniform and come in through scalar loads,
+// so the violation test of a feature word for 64 clauses,
 //   (inc_neg & x) | (inc_pos & ~x),
-// is a single v_bfi_b32 with x as the scalar selector.  A lane keeps one
-// "violated" flag bit per example for a batch of 256 examples; this is what
-// lets masks wider than the register budget be streamed in chunks.
-template <int CH>
-__global__ __launch_bounds__(64) void k_eval(const uint32_t *__restrict__ inc, const uint32_t *__restrict__ X,
-                                             uint32_t *__restrict__ bits, int32_t *__restrict__ acc,
-                                             const EvalArgs a)
+// is a single bit-select with the scalar x as selector.  Votes are summed with
+// ballot + popcount against the polarity masks (odd clause index = positive).
+
+// Vote of the clauses of class `cc` in this tile for one example.
+__device__ __forceinline__ int tile_vote(uint64_t satisfied, uint64_t cmpos, uint64_t cmneg)
 {
+    return __builtin_popcountll(satisfied & cmpos) - __builtin_popcountll(satisfied & cmneg);
+}
+
+// Resident variant, Wf <= CH <= 32: both mask halves of the tile stay in 2*CH
+// VGPRs for the whole range of examples.  Rows of X are read CH words wide; a
+// row shorter than CH is over-read into the next row (the surplus masks are 0),
+// except for the last row of X, which takes a guarded path.
+template <int CH, bool BITS, bool ACC>
+__global__ __launch_bounds__(64) void k_eval_resident(const uint32_t *__restrict__ inc,
+                                                      const uint32_t *__restrict__ X, uint32_t *__restrict__ bits,
+                                                      int32_t *__restrict__ acc, const EvalArgs a)
+{
+    const int lane = threadIdx.x;
+    const int tile = blockIdx.x;
+    const int g = tile * 64 + lane;
+    const bool gv = g < a.C;
+    const int64_t e_begin = (int64_t)blockIdx.y * a.ex_per_wave;
+    const int64_t e_end = min(a.q, e_begin + a.ex_per_wave);
+    if (e_begin >= e_end) return;
+
+    const uint32_t *mrow = inc + (int64_t)(gv ? g : 0) * a.W;
+    uint32_t mp[CH], mn[CH];
+#pragma unroll
+    for (int w = 0; w < CH; ++w) {
+        const bool ok = gv && (w < a.Wf);
+        const int wi = w < a.Wf ? w : 0;
+        const uint32_t vp = mrow[wi], vn = mrow[a.Wf + wi];
+        mp[w] = ok ? vp : 0u;
+        mn[w] = ok ? vn : 0u;
+    }
+
+    const int c_first = (tile * 64) / a.n;
+    const int c_last = (min(a.C, tile * 64 + 64) - 1) / a.n;
+    const bool one_class = (c_first == c_last);
+    const int my_class = gv ? g / a.n : -1;
+    const uint64_t cm0 = ballot(my_class == c_first);
+    const uint64_t cmpos0 = cm0 & 0xAAAAAAAAAAAAAAAAull, cmneg0 = cm0 & 0x5555555555555555ull;
+    const int64_t safe_end = (a.Wf == CH) ? e_end : min(e_end, a.q - 1);
+
+    for (int64_t b0 = e_begin; b0 < e_end; b0 += 64) {
+        const int nb = (int)min((int64_t)64, e_end - b0);
+        uint32_t sat[2] = {0u, 0u}; // bit e: this lane's clause is satisfied by example b0 + 32*h + e
+        int accv = 0;               // lane e: vote of class c_first in this tile for example b0 + e
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int ne = min(32, nb - 32 * h);
+            for (int e = 0; e < ne; ++e) {
+                const int64_t i = b0 + 32 * h + e;
+                const uint32_t *xr = X + i * a.Wf; // wave-uniform
+                uint32_t viol = 0;
+                if (i < safe_end) {
+#pragma unroll
+                    for (int w = 0; w < CH; ++w) {
+                        const uint32_t x = xr[w];
+                        viol |= bitselect(x, mn[w], mp[w]); // negated literal violated where x = 1, plain where x = 0
+                    }
+                } else {
+#pragma unroll
+                    for (int w = 0; w < CH; ++w) {
+                        if (w < a.Wf) {
+                            const uint32_t x = xr[w];
+                            viol |= bitselect(x, mn[w], mp[w]); // negated literal violated where x = 1, plain where x = 0
+                        }
+                    }
+                }
+                const bool ok = (viol == 0u);
+                if (BITS || !one_class) sat[h] |= ok ? (1u << e) : 0u;
+                if (ACC) {
+                    const int s = tile_vote(ballot(ok), cmpos0, cmneg0);
+                    accv = (lane == 32 * h + e) ? s : accv;
+                }
+            }
+        }
+        if (BITS && gv) {
+            bits[(int64_t)g * a.bits_stride + (b0 >> 5)] = sat[0];
+            if (nb > 32) bits[(int64_t)g * a.bits_stride + (b0 >> 5) + 1] = sat[1];
+        }
+        if (ACC) {
+            const int64_t i = b0 + lane;
+            if (lane < nb && accv != 0) atomicAdd(acc + i * a.acc_si + (int64_t)c_first * a.acc_sc, accv);
+            if (!one_class) { // tiles that straddle class boundaries: remaining classes from the stored bits
+                for (int cc = c_first + 1; cc <= c_last; ++cc) {
+                    const uint64_t cm = ballot(my_class == cc);
+                    const uint64_t cmpos = cm & 0xAAAAAAAAAAAAAAAAull, cmneg = cm & 0x5555555555555555ull;
+                    int av = 0;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int ne = min(32, nb - 32 * h);
+                        for (int e = 0; e < ne; ++e) {
+                            const int s = tile_vote(ballot(((sat[h] >> e) & 1u) != 0u), cmpos, cmneg);
+                            av = (lane == 32 * h + e) ? s : av;
+                        }
+                    }
+                    if (lane < nb && av != 0) atomicAdd(acc + i * a.acc_si + (int64_t)cc * a.acc_sc, av);
+                }
+            }
+        }
+    }
+}
+
+// Streaming variant for masks wider than the register budget (Wf > 32): the
+// masks are streamed in chunks of 32 feature words per batch of 256 examples;
+// a lane keeps one "violated" flag bit per example of the batch.
+__global__ __launch_bounds__(64) void k_eval_stream(const uint32_t *__restrict__ inc, const uint32_t *__restrict__ X,
+                                                    uint32_t *__restrict__ bits, int32_t *__restrict__ acc,
+                                                    const EvalArgs a)
+{
+    constexpr int CH = 32;
     const int lane = threadIdx.x;
     const int tile = blockIdx.x;
     const int g = tile * 64 + lane;
@@ -237,21 +342,8 @@ __global__ __launch_bounds__(64) void k_eval(const uint32_t *__restrict__ inc, c
 
     const int nch = (a.Wf + CH - 1) / CH;
     const uint32_t *mrow = inc + (int64_t)(gv ? g : 0) * a.W;
-    uint32_t mp[CH], mn[CH];
-
-    auto load_masks = [&](int w0) {
-#pragma unroll
-        for (int w = 0; w < CH; ++w) {
-            const bool ok = gv && (w0 + w < a.Wf);
-            mp[w] = ok ? mrow[w0 + w] : 0u;
-            mn[w] = ok ? mrow[a.Wf + w0 + w] : 0u;
-        }
-    };
-    if (nch == 1) load_masks(0);
-
-    const int g_first = tile * 64;
-    const int g_last = min(a.C, g_first + 64) - 1;
-    const int c_first = g_first / a.n, c_last = g_last / a.n;
+    const int c_first = (tile * 64) / a.n;
+    const int c_last = (min(a.C, tile * 64 + 64) - 1) / a.n;
     const int my_class = gv ? g / a.n : -1;
 
     for (int64_t b0 = e_begin; b0 < e_end; b0 += 256) {
@@ -262,7 +354,15 @@ __global__ __launch_bounds__(64) void k_eval(const uint32_t *__restrict__ inc, c
 
         for (int ch = 0; ch < nch; ++ch) {
             const int w0 = ch * CH;
-            if (nch > 1) load_masks(w0);
+            uint32_t mp[CH], mn[CH];
+#pragma unroll
+            for (int w = 0; w < CH; ++w) {
+                const bool ok = gv && (w0 + w < a.Wf);
+                const int wi = (w0 + w < a.Wf) ? w0 + w : 0;
+                const uint32_t vp = mrow[wi], vn = mrow[a.Wf + wi];
+                mp[w] = ok ? vp : 0u;
+                mn[w] = ok ? vn : 0u;
+            }
             const bool full = (w0 + CH <= a.Wf);
 #pragma unroll
             for (int fb = 0; fb < 8; ++fb) {
@@ -274,18 +374,18 @@ __global__ __launch_bounds__(64) void k_eval(const uint32_t *__restrict__ inc, c
 #pragma unroll
                         for (int w = 0; w < CH; ++w) {
                             const uint32_t x = xr[w];
-                            viol |= (x & mn[w]) | (~x & mp[w]);
+                            viol |= bitselect(x, mn[w], mp[w]); // negated literal violated where x = 1, plain where x = 0
                         }
                     } else {
 #pragma unroll
                         for (int w = 0; w < CH; ++w) {
                             if (w0 + w < a.Wf) {
                                 const uint32_t x = xr[w];
-                                viol |= (x & mn[w]) | (~x & mp[w]);
+                                viol |= bitselect(x, mn[w], mp[w]); // negated literal violated where x = 1, plain where x = 0
                             }
                         }
                     }
-                    flags[fb] |= (viol != 0) ? (1u << e) : 0u;
+                    flags[fb] |= (viol != 0u) ? (1u << e) : 0u;
                 }
             }
         }
@@ -311,8 +411,7 @@ __global__ __launch_bounds__(64) void k_eval(const uint32_t *__restrict__ inc, c
                 for (int fb = 0; fb < 8; ++fb) {
                     const int ne = min(32, nb - fb * 32);
                     for (int e = 0; e < ne; ++e) {
-                        const uint64_t sat = ballot(((flags[fb] >> e) & 1u) == 0u);
-                        const int s = __builtin_popcountll(sat & cmpos) - __builtin_popcountll(sat & cmneg);
+                        const int s = tile_vote(ballot(((flags[fb] >> e) & 1u) == 0u), cmpos, cmneg);
                         accv[fb >> 1] = (lane == (fb & 1) * 32 + e) ? s : accv[fb >> 1];
                     }
                 }
@@ -809,24 +908,31 @@ struct EvalPtrs {
 };
 
 template <int CH>
-void launch_eval_t(const EvalPtrs &p, const EvalArgs &a, dim3 grid, hipStream_t st)
+void launch_eval_resident(const EvalPtrs &p, const EvalArgs &a, dim3 grid, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_eval<CH>, grid, dim3(64), 0, st, p.inc, p.X, p.bits, p.acc, a);
+    if (p.bits && p.acc)
+        hipLaunchKernelGGL((k_eval_resident<CH, true, true>), grid, dim3(64), 0, st, p.inc, p.X, p.bits, p.acc, a);
+    else if (p.bits)
+        hipLaunchKernelGGL((k_eval_resident<CH, true, false>), grid, dim3(64), 0, st, p.inc, p.X, p.bits, p.acc, a);
+    else
+        hipLaunchKernelGGL((k_eval_resident<CH, false, true>), grid, dim3(64), 0, st, p.inc, p.X, p.bits, p.acc, a);
 }
 
 // Evaluation of all clauses on q examples; writes bits and/or accumulates sums.
 int launch_eval(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *bits, int64_t bits_stride, int32_t *acc,
                 int64_t acc_si, int64_t acc_sc, hipStream_t st)
 {
-    if (q == 0) return TM_OK;
+    if (q == 0 || (!bits && !acc)) return TM_OK;
     const Dims &d = h->d;
     EvalArgs a;
     const EvalPtrs p{h->inc, X, bits, acc};
     a.q = q; a.Wf = d.Wf; a.W = d.W; a.C = d.C; a.n = d.n; a.m = d.m;
     a.bits_stride = bits_stride; a.acc_si = acc_si; a.acc_sc = acc_sc;
+    // a wavefront takes one tile of 64 clauses and a range of examples (a multiple of 256);
+    // ranges are sized so that the launch has a few thousand wavefronts per XCD
     const int64_t tiles = (d.C + 63) / 64;
     const int64_t max_ranges = (q + 255) / 256;
-    int64_t ranges = (8192 + tiles - 1) / tiles;
+    int64_t ranges = (16384 + tiles - 1) / tiles;
     if (ranges > max_ranges) ranges = max_ranges;
     if (ranges > 65535) ranges = 65535;
     if (ranges < 1) ranges = 1;
@@ -836,15 +942,17 @@ int launch_eval(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *bits, int6
     a.ex_per_wave = epw;
     const dim3 grid((unsigned)tiles, (unsigned)ranges);
     const int Wf = d.Wf;
-    if (Wf <= 1) launch_eval_t<1>(p, a, grid, st);
-    else if (Wf <= 2) launch_eval_t<2>(p, a, grid, st);
-    else if (Wf <= 4) launch_eval_t<4>(p, a, grid, st);
-    else if (Wf <= 8) launch_eval_t<8>(p, a, grid, st);
-    else if (Wf <= 12) launch_eval_t<12>(p, a, grid, st);
-    else if (Wf <= 16) launch_eval_t<16>(p, a, grid, st);
-    else if (Wf <= 20) launch_eval_t<20>(p, a, grid, st);
-    else if (Wf <= 25) launch_eval_t<25>(p, a, grid, st);
-    else launch_eval_t<32>(p, a, grid, st);
+    if (Wf <= 1) launch_eval_resident<1>(p, a, grid, st);
+    else if (Wf <= 2) launch_eval_resident<2>(p, a, grid, st);
+    else if (Wf <= 4) launch_eval_resident<4>(p, a, grid, st);
+    else if (Wf <= 8) launch_eval_resident<8>(p, a, grid, st);
+    else if (Wf <= 12) launch_eval_resident<12>(p, a, grid, st);
+    else if (Wf <= 16) launch_eval_resident<16>(p, a, grid, st);
+    else if (Wf <= 20) launch_eval_resident<20>(p, a, grid, st);
+    else if (Wf <= 25) launch_eval_resident<25>(p, a, grid, st);
+    else if (Wf <= 28) launch_eval_resident<28>(p, a, grid, st);
+    else if (Wf <= 32) launch_eval_resident<32>(p, a, grid, st);
+    else hipLaunchKernelGGL(k_eval_stream, grid, dim3(64), 0, st, p.inc, p.X, p.bits, p.acc, a);
     TM_HIP(h, hipGetLastError());
     return TM_OK;
 }
