@@ -269,32 +269,49 @@ __global__ __launch_bounds__(64) void k_eval_resident(const uint32_t *__restrict
         int accv = 0;               // lane e: vote of class c_first in this tile for example b0 + e
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
+            const int64_t base = b0 + 32 * h;
             const int ne = min(32, nb - 32 * h);
-            for (int e = 0; e < ne; ++e) {
-                const int64_t i = b0 + 32 * h + e;
-                const uint32_t *xr = X + i * a.Wf; // wave-uniform
-                uint32_t viol = 0;
-                if (i < safe_end) {
-#pragma unroll
-                    for (int w = 0; w < CH; ++w) {
-                        const uint32_t x = xr[w];
-                        viol |= bitselect(x, mn[w], mp[w]); // negated literal violated where x = 1, plain where x = 0
-                    }
-                } else {
-#pragma unroll
-                    for (int w = 0; w < CH; ++w) {
-                        if (w < a.Wf) {
-                            const uint32_t x = xr[w];
-                            viol |= bitselect(x, mn[w], mp[w]); // negated literal violated where x = 1, plain where x = 0
-                        }
-                    }
-                }
+            const int nf = (int)min((int64_t)ne, safe_end - base); // examples whose rows may be read CH words wide
+            auto post = [&](int e, uint32_t viol) {
                 const bool ok = (viol == 0u);
                 if (BITS || !one_class) sat[h] |= ok ? (1u << e) : 0u;
                 if (ACC) {
                     const int s = tile_vote(ballot(ok), cmpos0, cmneg0);
                     accv = (lane == 32 * h + e) ? s : accv;
                 }
+            };
+            if (nf > 0) {
+                // the row of the next example is requested before the current one is consumed,
+                // so that the scalar-load latency hides behind the bit operations
+                uint32_t xa[CH];
+                {
+                    const uint32_t *xr = X + base * a.Wf;
+#pragma unroll
+                    for (int w = 0; w < CH; ++w) xa[w] = xr[w];
+                }
+#pragma unroll 2
+                for (int e = 0; e < nf; ++e) {
+                    uint32_t xb[CH];
+                    const int64_t inext = min(base + e + 1, safe_end - 1);
+                    const uint32_t *xr = X + inext * a.Wf; // wave-uniform
+#pragma unroll
+                    for (int w = 0; w < CH; ++w) xb[w] = xr[w];
+                    uint32_t viol = 0;
+#pragma unroll
+                    for (int w = 0; w < CH; ++w) viol |= bitselect(xa[w], mn[w], mp[w]); // negated literal violated where x = 1, plain where x = 0
+                    post(e, viol);
+#pragma unroll
+                    for (int w = 0; w < CH; ++w) xa[w] = xb[w];
+                }
+            }
+            for (int e = max(nf, 0); e < ne; ++e) { // the last row of X when it is shorter than CH words
+                const uint32_t *xr = X + (base + e) * a.Wf;
+                uint32_t viol = 0;
+#pragma unroll
+                for (int w = 0; w < CH; ++w) {
+                    if (w < a.Wf) viol |= bitselect(xr[w], mn[w], mp[w]);
+                }
+                post(e, viol);
             }
         }
         if (BITS && gv) {
