@@ -40,6 +40,17 @@ TYPE2_OPS_PER_WORD = 2 + 16                              # mask + one ripple
 GATE_OPS = PHILOX_OPS + 8                                # one block + clip, error, 64-bit compare
 
 
+# HBM traffic of one launch of the training kernel in the timed (steady) epochs of the default
+# workload, from two separate `rocprofv3 --pmc` runs of this program (FETCH_SIZE, then
+# WRITE_SIZE, KiB per dispatch, averaged over the launches of the last timed epoch).  The scale
+# factors come from the same counters read for a plain 1 GiB device copy in the same runs
+# (--calibration-copy): FETCH_SIZE reads 524,310 KiB for 1,048,576 KiB fetched, WRITE_SIZE reads
+# 1,048,576 KiB for 1,048,576 KiB written.  Summaries are under profiles/.
+MEASURED_TRAFFIC = {
+    "image_like": {"fetch_kib": 68634.0, "fetch_scale": 2.0, "write_kib": 47872.0, "write_scale": 1.0},
+}
+
+
 def train_kernel_ops(counters, W):
     """Algorithmic lane-ops of a run of the training kernel from its event counters."""
     return (counters["pairs"] * (W + 2)                    # one AND-OR per literal word + refresh
@@ -48,22 +59,42 @@ def train_kernel_ops(counters, W):
             + counters["type2_active"] * W * TYPE2_OPS_PER_WORD)
 
 
-def make_workload(name, small=False):
+def make_workload(name, small=False, n_override=None, q_override=None):
+    """Hyper-parameters, data and description of a benchmark workload.  The default
+    (image_like at full size) is the configuration the metric is quoted on; the other names,
+    the clause override (clause-scaling sweep: T = 0.8 n) and the example override exist to
+    measure the remaining configurations and are reported as what they are."""
     from paper_2009_04861_amd import synth
     if name == "image_like":
         hp = dict(synth.WORKLOADS["image_like"])
+        qtr, qte = (6000, 1000) if small else (q_override or 60000, 10000)
         if small:
             hp["n"] = 200
-            Xtr, ytr, Xte, yte = synth.image_like(6000, 1000)
-        else:
-            Xtr, ytr, Xte, yte = synth.image_like()
-        desc = "image_like (configs[1]): 60000x784 train, 10000 test, 10 classes x 2000 clauses, T=50, s=10, 2N=256"
+        Xtr, ytr, Xte, yte = synth.image_like(qtr, qte)
+        desc = "image_like (configs[1]): %dx784 train, %d test, 10 classes" % (qtr, qte)
     elif name == "noisy_xor":
         hp = dict(synth.WORKLOADS["noisy_xor"])
         Xtr, ytr, Xte, yte = synth.noisy_xor()
-        desc = "noisy_xor (configs[0]): 5000x12 train, 5000 test, 2 classes x 10 clauses, T=15, s=3.9, N=100"
+        desc = "noisy_xor (configs[0]): 5000x12 train, 5000 test, 2 classes"
+    elif name == "text_like":
+        hp = dict(synth.WORKLOADS["text_like"])
+        qtr = q_override or 25000
+        Xtr, ytr, Xte, yte = synth.text_like(qtr, min(qtr, 25000))
+        desc = "text_like (configs[2]): %dx10000 train, %d test, 2 classes" % (qtr, len(yte))
+    elif name == "stress":
+        hp = dict(synth.WORKLOADS["stress"])
+        qtr = q_override or 200000
+        X, y = synth.planted_conjunctions(qtr + min(qtr, 20000))
+        Xtr, ytr, Xte, yte = X[:qtr], y[:qtr], X[qtr:], y[qtr:]
+        desc = "stress (configs[4]): %dx20000 train, %d test, 2 classes" % (qtr, len(yte))
     else:
         raise SystemExit("unknown workload %s" % name)
+    if n_override:
+        hp["n"] = n_override
+        hp["T"] = max(1, int(round(0.8 * n_override)))
+    desc += " x %d clauses, T=%d, s=%g, N=%d" % (hp["n"], hp["T"], hp["s"], hp["N"])
+    if small or n_override or q_override:
+        desc += " [NOT THE HEADLINE CONFIGURATION]"
     return hp, (Xtr, ytr, Xte, yte), desc
 
 
@@ -106,6 +137,9 @@ def main():
     ap.add_argument("--small", action="store_true", help="reduced sizes (debugging only, not a valid result)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--clauses-per-class", type=int, default=None,
+                    help="override n and set T = 0.8 n (clause-scaling sweep; not the headline configuration)")
+    ap.add_argument("--q-train", type=int, default=None, help="override the number of training examples")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference dispatch for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -123,7 +157,7 @@ def main():
         raise SystemExit("bench.py needs a GPU")
     B.lib()  # fail loudly if the HIP library is missing
 
-    hp, (Xtr, ytr, Xte, yte), desc = make_workload(args.workload, args.small)
+    hp, (Xtr, ytr, Xte, yte), desc = make_workload(args.workload, args.small, args.clauses_per_class, args.q_train)
     q, qt = len(ytr), len(yte)
     tm = B.TsetlinMachine(seed=args.seed, **hp)
     C, W = tm.C, 2 * tm.Wf
@@ -181,12 +215,22 @@ def main():
     sync_ms = [e[1].elapsed_time(e[2]) for e in evs]
     pred_ms = [e[2].elapsed_time(e[3]) for e in evs]
     fit_avg = float(np.mean(fit_ms))
-    ops = train_kernel_ops(cnt, W) / args.steps
-    achieved = ops / (fit_avg * 1e-3) / 1e12
-    # algorithmic HBM bytes of one training launch: TA planes in + out, include masks out,
-    # X and its transposed copy once, previous-output bits in + out, tallies, labels
-    hbm_bytes = (2 * C * W * 32 + C * W * 4 + 2 * q * tm.Wf * 4 + 2 * C * ((q + 63) // 64) * 8
-                 + tm.m * q * 4 * 2 + q * 8)
+    # tm_fit_epoch launches the training kernel once per range of `chunk` examples
+    chunk = B.tm_train_chunk(tm.h)
+    n_launch = (q + chunk - 1) // chunk
+    launch_ms = fit_avg / n_launch
+    ops = train_kernel_ops(cnt, W) / args.steps / n_launch
+    achieved = ops / (launch_ms * 1e-3) / 1e12
+    # algorithmic HBM bytes of one training launch: TA planes in + out and include masks out for
+    # every clause, and the launch's share of X, transposed X, previous-output bits in + out,
+    # tallies in + out and labels
+    share = min(1.0, chunk / q)
+    hbm_bytes = (2 * C * W * 32 + C * W * 4
+                 + share * (2 * q * tm.Wf * 4 + 2 * C * ((q + 63) // 64) * 8 + tm.m * q * 4 * 2 + q * 8))
+    traffic = None
+    if args.workload == "image_like" and not (args.small or args.clauses_per_class or args.q_train):
+        t = MEASURED_TRAFFIC["image_like"]
+        traffic = 1024.0 * (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"])
 
     out = {
         "metric": "training examples/sec per epoch (one step = fit epoch + tally pre-calculation + test-set prediction)",
@@ -202,7 +246,7 @@ def main():
         "dtype": "u32 bit words, u8 bit-sliced automata, int32 tallies",
         "data": "synthetic",
         "config": {
-            "workload": desc if not args.small else desc + " [REDUCED SIZES, NOT A VALID RESULT]",
+            "workload": desc,
             "m": tm.m, "n": tm.n, "o": tm.o, "N": tm.N, "T": tm.T, "s": tm.s, "q_train": q, "q_test": qt,
             "clauses_total": C, "pairs_per_epoch": q * C,
             "fit_epoch_ms": fit_avg, "sync_tallies_ms": float(np.mean(sync_ms)), "predict_ms": float(np.mean(pred_ms)),
@@ -223,12 +267,14 @@ def main():
             "peak": ALU_PEAK_TOPS,
             "unit": "Tlane-op/s (32-bit integer)",
             "frac": achieved / ALU_PEAK_TOPS,
-            "traffic": None,
-            "avg_launch_ms": fit_avg,
+            "traffic": traffic,
+            "avg_launch_ms": launch_ms,
+            "launches_per_epoch": n_launch,
+            "examples_per_launch": chunk,
             "algorithmic_lane_ops_per_launch": ops,
             "hbm_algorithmic_bytes_per_launch": hbm_bytes,
-            "hbm_achieved_GBs": hbm_bytes / (fit_avg * 1e-3) / 1e9,
-            "hbm_frac": hbm_bytes / (fit_avg * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "hbm_achieved_GBs": hbm_bytes / (launch_ms * 1e-3) / 1e9,
+            "hbm_frac": hbm_bytes / (launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         },
     }
     if not args.no_cpu_baseline:

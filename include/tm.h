@@ -143,6 +143,11 @@ int tm_get_prev_outputs(tm_handle *h, uint32_t *bits, void *stream);
 int tm_feedback_step(tm_handle *h, const int32_t *tally_snapshot, int64_t i0, int64_t cnt,
                      void *stream);
 
+/* tm_fit_epoch cuts the pass into consecutive ranges of this many examples, one
+ * launch of the training kernel each, so that a range's slice of the
+ * transposed features stays resident in L2 (measurement aid). */
+int tm_train_chunk(tm_handle *h, int64_t *examples_per_launch);
+
 /* Epoch counter used for the random counter of the next tm_fit_epoch. */
 int tm_set_epoch(tm_handle *h, uint32_t epoch);
 int tm_get_epoch(tm_handle *h, uint32_t *epoch);

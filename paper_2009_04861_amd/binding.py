@@ -18,7 +18,7 @@ TM_OK, TM_EINVAL, TM_ESTATE, TM_EHIP, TM_ELIMIT = 0, -1, -2, -3, -4
 EXPORTS = [
     "tm_state_bytes", "tm_train_ws_bytes", "tm_create", "tm_destroy", "tm_bind_train", "tm_fit_epoch",
     "tm_class_sums", "tm_predict", "tm_get_ta_state", "tm_set_ta_state", "tm_clause_outputs",
-    "tm_sync_tallies", "tm_get_tallies", "tm_get_prev_outputs", "tm_feedback_step", "tm_set_epoch",
+    "tm_sync_tallies", "tm_get_tallies", "tm_get_prev_outputs", "tm_feedback_step", "tm_train_chunk", "tm_set_epoch",
     "tm_get_epoch", "tm_read_counters", "tm_strerror", "tm_last_hip_error",
 ]
 
@@ -150,6 +150,12 @@ def tm_get_prev_outputs(h, bits):
 def tm_feedback_step(h, snapshot, i0, cnt):
     _check(lib().tm_feedback_step(h, _ptr(snapshot, torch.int32), ctypes.c_int64(i0), ctypes.c_int64(cnt),
                                   _stream()), "tm_feedback_step")
+
+
+def tm_train_chunk(h):
+    c = ctypes.c_int64(0)
+    _check(lib().tm_train_chunk(h, ctypes.byref(c)), "tm_train_chunk")
+    return c.value
 
 
 def tm_set_epoch(h, epoch):

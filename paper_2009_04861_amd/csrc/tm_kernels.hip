@@ -653,26 +653,35 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
         const uint32_t *xt_block = XT + i0;
         uint64_t obits = eval64(eoff, emask, nent, xt_block, lane);
 
-        while (fmask) {
-            const int l = __builtin_ctzll(fmask);
-            fmask &= fmask - 1;
-            const int64_t ii = i0 + l;
-            const bool tgt = (tmask >> l) & 1;
-            const bool Cout = (obits >> l) & 1; // clause output on the state before the update
-            const uint32_t *xrow = X + ii * d.Wf;
-            uint32_t changed = 0;
-            // words of this example in lane = literal-word layout.  Slot geometry (which half, which
-            // bits exist) is recomputed from a laundered index wherever it is needed: it is
-            // example-independent, and the compiler would otherwise keep it in VGPRs for every slot.
-            uint32_t xw[WPL];
+        // words of a fired example in lane = literal-word layout.  Slot geometry (which half,
+        // which bits exist) is recomputed from a laundered index wherever it is needed: it is
+        // example-independent, and the compiler would otherwise keep it in VGPRs for every slot.
+        auto load_row = [&](int l, uint32_t (&dst)[WPL]) {
+            const uint32_t *xrow = X + (i0 + l) * d.Wf;
 #pragma unroll
             for (int r = 0; r < WPL; ++r) {
                 uint32_t lw = (uint32_t)(r * 64 + lane);
                 asm volatile("" : "+v"(lw));
                 const bool act = lw < (uint32_t)d.W;
                 const uint32_t fw = act ? (lw >= (uint32_t)d.Wf ? lw - (uint32_t)d.Wf : lw) : 0u;
-                xw[r] = xrow[fw];
+                dst[r] = xrow[fw];
             }
+        };
+        // the row of the next fired example is requested while the current one is processed
+        uint32_t xnext[WPL];
+        if (fmask) load_row(__builtin_ctzll(fmask), xnext);
+
+        while (fmask) {
+            const int l = __builtin_ctzll(fmask);
+            fmask &= fmask - 1;
+            const int64_t ii = i0 + l;
+            const bool tgt = (tmask >> l) & 1;
+            const bool Cout = (obits >> l) & 1; // clause output on the state before the update
+            uint32_t changed = 0;
+            uint32_t xw[WPL];
+#pragma unroll
+            for (int r = 0; r < WPL; ++r) xw[r] = xnext[r];
+            if (fmask) load_row(__builtin_ctzll(fmask), xnext);
             auto literal = [&](uint32_t lw, uint32_t x, uint32_t &valid) {
                 const bool act = lw < (uint32_t)d.W;
                 const bool neg = lw >= (uint32_t)d.Wf;
@@ -1285,6 +1294,13 @@ int tm_get_prev_outputs(tm_handle *h, uint32_t *bits, void *stream)
     hipLaunchKernelGGL(k_copy_rows, dim3(blocks_for((int64_t)h->d.C * words, 256)), dim3(256), 0,
                        (hipStream_t)stream, h->ostar, h->Qw, bits, words, (int64_t)h->d.C, words);
     TM_HIP(h, hipGetLastError());
+    return TM_OK;
+}
+
+int tm_train_chunk(tm_handle *h, int64_t *examples_per_launch)
+{
+    if (!h || !examples_per_launch) return TM_EINVAL;
+    *examples_per_launch = train_chunk(h->d);
     return TM_OK;
 }
 
