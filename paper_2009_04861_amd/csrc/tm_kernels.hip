@@ -281,28 +281,31 @@ __global__ __launch_bounds__(64) void k_eval_resident(const uint32_t *__restrict
                 }
             };
             if (nf > 0) {
-                // the row of the next example is requested before the current one is consumed,
-                // so that the scalar-load latency hides behind the bit operations
-                uint32_t xa[CH];
-                {
-                    const uint32_t *xr = X + base * a.Wf;
+                // two row buffers in turn: the row of the next example is requested before the
+                // current one is consumed, so that the scalar-load latency hides behind the
+                // bit operations (no register copies between the buffers)
+                auto load = [&](uint32_t (&x)[CH], int e) {
+                    const int64_t ir = min(base + e, safe_end - 1); // clamped: a surplus request re-reads a valid row
+                    const uint32_t *xr = X + ir * a.Wf;             // wave-uniform
 #pragma unroll
-                    for (int w = 0; w < CH; ++w) xa[w] = xr[w];
-                }
-#pragma unroll 2
-                for (int e = 0; e < nf; ++e) {
-                    uint32_t xb[CH];
-                    const int64_t inext = min(base + e + 1, safe_end - 1);
-                    const uint32_t *xr = X + inext * a.Wf; // wave-uniform
-#pragma unroll
-                    for (int w = 0; w < CH; ++w) xb[w] = xr[w];
+                    for (int w = 0; w < CH; ++w) x[w] = xr[w];
+                };
+                auto consume = [&](const uint32_t (&x)[CH], int e) {
                     uint32_t viol = 0;
 #pragma unroll
-                    for (int w = 0; w < CH; ++w) viol |= bitselect(xa[w], mn[w], mp[w]); // negated literal violated where x = 1, plain where x = 0
+                    for (int w = 0; w < CH; ++w) viol |= bitselect(x[w], mn[w], mp[w]); // negated literal violated where x = 1, plain where x = 0
                     post(e, viol);
-#pragma unroll
-                    for (int w = 0; w < CH; ++w) xa[w] = xb[w];
+                };
+                uint32_t xa[CH], xb[CH];
+                load(xa, 0);
+                int e = 0;
+                for (; e + 1 < nf; e += 2) {
+                    load(xb, e + 1);
+                    consume(xa, e);
+                    load(xa, e + 2);
+                    consume(xb, e + 1);
                 }
+                if (e < nf) consume(xa, e);
             }
             for (int e = max(nf, 0); e < ne; ++e) { // the last row of X when it is shorter than CH words
                 const uint32_t *xr = X + (base + e) * a.Wf;
