@@ -8,6 +8,7 @@
 //                  ostar  uint32 [C][Qw]    previous clause outputs, 1 bit per (clause, example), Qw = qp/32
 //                  XT     uint32 [Wf][qp]   transposed features (word-major) for lane = example evaluation
 //                  negcls int32  [qp]       class trained towards 0 for each example, this epoch
+//                  cand   int32  [m][qp]    per class: ascending list of (example << 1 | target) that may get feedback
 //                  counters uint64 [8], flag int32
 //   literal word lw < Wf holds x_(32 lw + j), literal word Wf + fw holds NOT x_(32 fw + j).
 //
@@ -145,6 +146,47 @@ __global__ void k_negcls(Dims d, const int32_t *y, int32_t *negcls, int64_t q, i
         r = dd + (dd >= y[i] ? 1 : 0);
     }
     negcls[i] = r;
+}
+
+// Candidate list of class c = blockIdx.x: the examples, in ascending order, for which
+// the clauses of c may receive feedback this epoch, packed as (example << 1 | target):
+// target 1 where y_i = c, target 0 where c is the drawn negative class.  One workgroup
+// per class scans the examples 1024 at a time and compacts the matches with ballot
+// prefixes.  ncand[c] receives the length.
+__global__ __launch_bounds__(1024) void k_cand_lists(const int32_t *__restrict__ y, const int32_t *__restrict__ negcls,
+                                                     int32_t *__restrict__ cand, int32_t *__restrict__ ncand, int64_t q,
+                                                     int64_t qp)
+{
+    __shared__ int wave_cnt[16];
+    __shared__ int base_sh;
+    const int c = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int32_t *list = cand + (int64_t)c * qp;
+    if (tid == 0) base_sh = 0;
+    __syncthreads();
+    for (int64_t i0 = 0; i0 < q; i0 += 1024) {
+        const int64_t i = i0 + tid;
+        bool match = false;
+        int target = 0;
+        if (i < q) {
+            target = (y[i] == c) ? 1 : 0;
+            match = target || negcls[i] == c;
+        }
+        const uint64_t b = ballot(match);
+        const int pre = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, 0u));
+        if (lane == 0) wave_cnt[wave] = __builtin_popcountll(b);
+        __syncthreads();
+        int off = base_sh, total = 0;
+        for (int w = 0; w < 16; ++w) {
+            if (w < wave) off += wave_cnt[w];
+            total += wave_cnt[w];
+        }
+        if (match) list[off + pre] = (int32_t)((i << 1) | target);
+        __syncthreads();
+        if (tid == 0) base_sh += total;
+        __syncthreads();
+    }
+    if (tid == 0) ncand[c] = base_sh;
 }
 
 // sums[i][c] = clamp(sums[i][c], -T, T)
@@ -537,10 +579,39 @@ __device__ __forceinline__ uint64_t eval64(const uint32_t *eoff, const uint2 *em
 constexpr int COUNTER_SETS = 64; // interleaved copies of the 8 event counters
 constexpr int TRAIN_WAVES = 4; // clauses (wavefronts) per workgroup of the training kernel
 
+// First position k in the ascending list[0..n) with list[k] >= key, found by the
+// whole wavefront: 64 probes per round, three rounds for a quarter million entries.
+__device__ __forceinline__ int wave_lower_bound(const int32_t *__restrict__ list, int n, int key, int lane)
+{
+    int lo = 0, hi = n; // answer in [lo, hi]
+    while (hi > lo) {
+        const int span = hi - lo;
+        const int step = (span + 63) >> 6;
+        const int idx = lo + lane * step;
+        const bool ge = idx < hi ? (list[idx] >= key) : true;
+        const uint64_t b = ballot(ge);
+        const int first = __builtin_ctzll(b | (1ull << 63)); // b is monotone; lane 63 counts as true if none is
+        // entries before probe `first` that are known to be < key: up to probe first-1
+        const int nlo = first == 0 ? lo : lo + (first - 1) * step + 1;
+        int nhi = lo + first * step;
+        if (nhi > hi || b == 0) nhi = hi;
+        if (step == 1) return b == 0 ? hi : min(hi, lo + first);
+        lo = min(nlo, hi);
+        hi = nhi;
+    }
+    return lo;
+}
+
+// One wavefront = one clause of class c.  The examples whose gate can open for this
+// clause are those of the candidate list of c (label c: trained towards 1; drawn
+// negative class c: trained towards 0); their gates are drawn 64 at a time, lane =
+// candidate.  Blocks of 64 consecutive examples are evaluated (lane = example) only
+// when a gate in them fired or their stored outputs may be outdated; all other blocks
+// of the pass are never touched.
 template <int WPL, bool FULL>
 __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
-                                              const int32_t *__restrict__ y, const int32_t *__restrict__ negcls,
-                                              const TrainArgs a)
+                                                            const int32_t *__restrict__ cand,
+                                                            const int32_t *__restrict__ ncand, const TrainArgs a)
 {
     extern __shared__ uint32_t lds[];
     const Dims &d = a.d;
@@ -557,6 +628,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     const int sign = pos ? 1 : -1;
     const int T = d.T;
     const uint32_t row_bytes = (uint32_t)a.qp * 4u;
+    const int i_begin = (int)a.i_begin, i_end = (int)a.i_end, q = (int)a.q;
 
     u32x8 p[WPL];
 #pragma unroll
@@ -579,13 +651,13 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     const int first_blk = min(tz >> 2, 4);
     const uint32_t ge_init = d.thr >= 65536u ? 0u : ~0u;
 
-    unsigned long long n_pairs = 0, n_fired = 0, n_type1 = 0, n_changes = 0, n_cand = 0, n_type2 = 0, n_eval = 0;
+    unsigned long long n_fired = 0, n_type1 = 0, n_changes = 0, n_cand = 0, n_type2 = 0, n_eval = 0;
 
     // Which stored previous outputs o* can differ from the clause's current output: only
     // those not re-evaluated since the include mask last changed.  Kept per clause as two
-    // example ranges, a prefix part [plo, phi) and a suffix [slo, qp); a block outside both
-    // needs no evaluation and no refresh unless one of its gates fires (the result is the
-    // same as refreshing every visited pair, the comparison o != o* would be false).
+    // example ranges (multiples of 64), a prefix part [plo, phi) and a suffix [slo, qp); a
+    // block outside both needs no evaluation and no refresh unless one of its gates fires
+    // (the result is the same as refreshing every visited pair: o != o* would be false).
     int plo, phi, slo;
     {
         const int4 f = *reinterpret_cast<const int4 *>(a.fresh + (int64_t)g * 4);
@@ -593,74 +665,74 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
         phi = __builtin_amdgcn_readfirstlane(f.y);
         slo = __builtin_amdgcn_readfirstlane(f.z);
     }
-
-    // Per-block inputs (label, negative class, tally, previous-output words) are
-    // fetched one block ahead so that their latency hides behind the current block.
-    // Reading the tally 64 examples early is within the method's premise of
-    // outdated tallies.
-    struct BlockIn {
-        int yi, ng, v;
-        uint32_t o0, o1;
+    auto next_stale = [&](int b) { // first block index >= b that may hold outdated outputs
+        int r = max(b, slo >> 6);
+        if (plo < phi && b < ((phi + 63) >> 6)) r = min(r, max(b, plo >> 6));
+        return r;
     };
-    auto fetch = [&](int64_t i0) {
-        BlockIn f;
-        const int64_t i = i0 + lane;
-        const bool inr = i >= a.i_begin && i < a.i_end;
-        f.yi = -1; f.ng = -1; f.v = 0;
-        if (inr) {
-            f.yi = y[i];
-            f.ng = negcls[i];
-            f.v = a.vhat ? a.vhat[i * d.m + c]
-                         : __hip_atomic_load(&a.tally[(int64_t)c * a.qp + i], __ATOMIC_RELAXED,
-                                             __HIP_MEMORY_SCOPE_AGENT);
-        }
-        const uint32_t *op = a.ostar + (int64_t)g * a.Qw + (i0 >> 5);
-        f.o0 = op[0];
-        f.o1 = op[1];
-        return f;
-    };
-    const int64_t i_first = a.i_begin & ~(int64_t)63;
-    BlockIn nxt = fetch(i_first);
 
-    for (int64_t i0 = i_first; i0 < a.i_end; i0 += 64) {
-        const int64_t i = i0 + lane;
-        const bool inr = i >= a.i_begin && i < a.i_end;
-        const BlockIn cur = nxt;
-        if (i0 + 64 < a.i_end) nxt = fetch(i0 + 64);
-        const int yi = cur.yi, ng = cur.ng;
-        const bool target = (yi == c);
-        const bool cand = inr && (target || ng == c);
-        bool fire = false;
-        if (cand) {
-            const int vc = min(max(cur.v, -T), T);
-            const int e = target ? T - vc : T + vc; // Algorithm 1: error of the recorded vote sum
-            if (e > 0) {
-                const U4 r = draw(d.key, STREAM_GATE, 0, (uint32_t)g, (uint64_t)i, a.epoch);
-                fire = (uint64_t)r.x * (uint64_t)(2 * (int64_t)T) < ((uint64_t)e << 32);
+    // the candidate list of this class, restricted to the examples of this launch
+    const int32_t *list = cand + (int64_t)c * a.qp;
+    const int n_list = ncand[c];
+    const int k_lo = wave_lower_bound(list, n_list, i_begin * 2, lane);
+    const int k_hi = wave_lower_bound(list, n_list, i_end * 2, lane);
+    const int32_t *tally_c = a.tally + (int64_t)c * a.qp;
+
+    // state of the block of 64 examples that is currently open (cb < 0: none)
+    const int end_block = (i_end + 63) >> 6;
+    int cb = -1, next_block = i_begin >> 6;
+    uint64_t obits = 0, ost = 0, rmask = 0;
+    bool mask_changed = false;
+
+    // Candidate data are fetched ahead: entry words two candidate blocks ahead, tallies (which
+    // need the entry's example index) one block ahead.  Reading a tally early is within the
+    // method's premise of outdated tallies.
+    auto load_ent = [&](int k0) { // packed (example << 1 | target), or -1 beyond the range
+        const int k = k0 + lane;
+        return k < k_hi ? list[k] : -1;
+    };
+    auto load_v = [&](int ent) {
+        if (ent < 0) return 0;
+        const int i = ent >> 1;
+        return a.vhat ? a.vhat[(int64_t)i * d.m + c]
+                      : __hip_atomic_load(&tally_c[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    int ent_cur = load_ent(k_lo);
+    int v_cur = load_v(ent_cur);
+    int ent_nxt = load_ent(k_lo + 64);
+
+    for (int k0 = k_lo;; k0 += 64) {
+        const bool last = k0 >= k_hi; // all candidates done: one more round sweeps the remaining blocks
+        uint64_t fmask = 0, tmask = 0;
+        int iv = 0;
+        if (!last) {
+            const int ent = ent_cur, v = v_cur;
+            ent_cur = ent_nxt;
+            v_cur = load_v(ent_cur);
+            ent_nxt = load_ent(k0 + 128);
+            const bool valid = ent >= 0;
+            iv = ent >> 1;
+            const bool target = (ent & 1) != 0;
+            bool fire = false;
+            if (valid) {
+                const int vc = min(max(v, -T), T);
+                const int e = target ? T - vc : T + vc; // Algorithm 1: error of the recorded vote sum
+                if (e > 0) {
+                    const U4 r = draw(d.key, STREAM_GATE, 0, (uint32_t)g, (uint64_t)(uint32_t)iv, a.epoch);
+                    fire = (uint64_t)r.x * (uint64_t)(2 * (int64_t)T) < ((uint64_t)e << 32);
+                }
             }
+            fmask = ballot(fire);
+            tmask = ballot(target);
+            n_cand += __builtin_popcountll(ballot(valid));
+            n_fired += __builtin_popcountll(fmask);
         }
-        uint64_t fmask = ballot(fire);
-        const uint64_t tmask = ballot(target);
-        const uint64_t rmask = ballot(inr);
-        n_pairs += __builtin_popcountll(rmask);
-        n_fired += __builtin_popcountll(fmask);
-        n_cand += __builtin_popcountll(ballot(cand));
-
-        const int b0 = (int)i0, b1 = (int)i0 + 64;
-        const bool stale = (b0 < phi && b1 > plo) || (b1 > slo);
-        if (!stale && fmask == 0) continue;
-        ++n_eval;
-        const bool whole = i0 >= a.i_begin && (i0 + 64 <= a.i_end || a.i_end == a.q);
-        bool mask_changed = false;
-
-        const uint32_t *xt_block = XT + i0;
-        uint64_t obits = eval64(eoff, emask, nent, xt_block, lane);
 
         // words of a fired example in lane = literal-word layout.  Slot geometry (which half,
         // which bits exist) is recomputed from a laundered index wherever it is needed: it is
         // example-independent, and the compiler would otherwise keep it in VGPRs for every slot.
-        auto load_row = [&](int l, uint32_t (&dst)[WPL]) {
-            const uint32_t *xrow = X + (i0 + l) * d.Wf;
+        auto load_row = [&](int ii, uint32_t (&dst)[WPL]) {
+            const uint32_t *xrow = X + (int64_t)ii * d.Wf;
 #pragma unroll
             for (int r = 0; r < WPL; ++r) {
                 uint32_t lw = (uint32_t)(r * 64 + lane);
@@ -672,19 +744,79 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
         };
         // the row of the next fired example is requested while the current one is processed
         uint32_t xnext[WPL];
-        if (fmask) load_row(__builtin_ctzll(fmask), xnext);
+        if (fmask) load_row(__builtin_amdgcn_readlane(iv, __builtin_ctzll(fmask)), xnext);
 
-        while (fmask) {
-            const int l = __builtin_ctzll(fmask);
-            fmask &= fmask - 1;
-            const int64_t ii = i0 + l;
+        for (;;) {
+            // next event: a fired candidate, or (after the last candidate) the end of the range
+            const bool have = fmask != 0;
+            int l = 0, ii = 0, B;
+            if (have) {
+                l = __builtin_ctzll(fmask);
+                fmask &= fmask - 1;
+                ii = __builtin_amdgcn_readlane(iv, l);
+                B = ii >> 6;
+            } else if (last) {
+                B = end_block;
+            } else {
+                break;
+            }
+
+            // bring block B up: close the open block, refresh the outdated blocks in between
+            while (cb != B) {
+                if (cb >= 0) {
+                    // refresh of tally and previous-output bits (last lines of Algorithm 1), 64 examples at once
+                    const int b0 = cb << 6, b1 = b0 + 64;
+                    const uint64_t diff = (obits ^ ost) & rmask;
+                    if (diff) {
+                        if ((diff >> lane) & 1ull) {
+                            const int delta = ((obits >> lane) & 1ull) ? sign : -sign;
+                            atomicAdd(&a.tally[(int64_t)c * a.qp + b0 + lane], delta);
+                        }
+                        const uint64_t nw = ost ^ diff;
+                        if (lane == 0) {
+                            uint32_t *op = a.ostar + (int64_t)g * a.Qw + (b0 >> 5);
+                            op[0] = (uint32_t)nw;
+                            op[1] = (uint32_t)(nw >> 32);
+                        }
+                        n_changes += __builtin_popcountll(diff);
+                    }
+                    const bool whole = b0 >= i_begin && (b1 <= i_end || i_end == q);
+                    if (whole) { // this block is up to date again
+                        if (b0 <= plo) plo = max(plo, b1);
+                        if (b0 <= slo) slo = max(slo, b1);
+                    }
+                    if (mask_changed) { // everything not visited after the change is outdated now
+                        plo = 0;
+                        phi = b1;
+                        slo = b1;
+                    }
+                    next_block = cb + 1;
+                    cb = -1;
+                }
+                const int nb = min(next_stale(next_block), B);
+                if (nb >= end_block) break; // only when B is the end of the range
+                // open block nb: previous outputs, range mask, evaluation with the current masks
+                cb = nb;
+                const int b0 = nb << 6;
+                const uint32_t *op = a.ostar + (int64_t)g * a.Qw + (b0 >> 5);
+                const uint32_t o0 = op[0], o1 = op[1];
+                rmask = ballot(b0 + lane >= i_begin && b0 + lane < i_end);
+                obits = eval64(eoff, emask, nent, XT + b0, lane);
+                ost = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)o0) |
+                      ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)o1) << 32);
+                mask_changed = false;
+                ++n_eval;
+            }
+            if (!have) break; // the range is finished
+
+            const int bl = ii & 63;                  // position of the example in the open block
             const bool tgt = (tmask >> l) & 1;
-            const bool Cout = (obits >> l) & 1; // clause output on the state before the update
+            const bool Cout = (obits >> bl) & 1;     // clause output on the state before the update
             uint32_t changed = 0;
             uint32_t xw[WPL];
 #pragma unroll
             for (int r = 0; r < WPL; ++r) xw[r] = xnext[r];
-            if (fmask) load_row(__builtin_ctzll(fmask), xnext);
+            if (fmask) load_row(__builtin_amdgcn_readlane(iv, __builtin_ctzll(fmask)), xnext);
             auto literal = [&](uint32_t lw, uint32_t x, uint32_t &valid) {
                 const bool act = lw < (uint32_t)d.W;
                 const bool neg = lw >= (uint32_t)d.Wf;
@@ -729,7 +861,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
                     for (int t = 0; t < 4; ++t) {
                         if (t >= first_blk) {
                             const U4 R = draw(d.key, STREAM_TYPE1, 4u * lw + (uint32_t)t, (uint32_t)g,
-                                              (uint64_t)ii, a.epoch);
+                                              (uint64_t)(uint32_t)ii, a.epoch);
                             const uint32_t w[4] = {R.x, R.y, R.z, R.w};
 #pragma unroll
                             for (int k = 0; k < 4; ++k) {
@@ -757,41 +889,15 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
                     if (WPL > 2) __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            if (ballot(changed != 0u)) { // the conjunction changed: re-evaluate this and the later examples
+            if (ballot(changed != 0u)) { // the conjunction changed: re-evaluate this and the later examples of the block
                 mask_changed = true;
                 nent = build_entries<WPL>(p, lmask, eoff, emask, lane, d.Wf, d.W, row_bytes);
-                const uint64_t nb = eval64(eoff, emask, nent, xt_block, lane);
-                const uint64_t keep = (1ull << l) - 1ull;
+                const uint64_t nb = eval64(eoff, emask, nent, XT + (cb << 6), lane);
+                const uint64_t keep = (1ull << bl) - 1ull;
                 obits = (obits & keep) | (nb & ~keep);
             }
         }
-
-        // refresh of tally and previous-output bits (last lines of Algorithm 1)
-        uint32_t *op = a.ostar + (int64_t)g * a.Qw + (i0 >> 5);
-        const uint64_t ost = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)cur.o0) |
-                             ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)cur.o1) << 32);
-        const uint64_t diff = (obits ^ ost) & rmask;
-        if (diff) {
-            if ((diff >> lane) & 1ull) {
-                const int delta = ((obits >> lane) & 1ull) ? sign : -sign;
-                atomicAdd(&a.tally[(int64_t)c * a.qp + i], delta);
-            }
-            const uint64_t nw = ost ^ diff;
-            if (lane == 0) {
-                op[0] = (uint32_t)nw;
-                op[1] = (uint32_t)(nw >> 32);
-            }
-            n_changes += __builtin_popcountll(diff);
-        }
-        if (whole) { // this block is up to date again
-            if (b0 <= plo) plo = max(plo, b1);
-            if (b0 <= slo) slo = max(slo, b1);
-        }
-        if (mask_changed) { // everything not visited after the change is outdated now
-            plo = 0;
-            phi = b1;
-            slo = b1;
-        }
+        if (last) break;
     }
     if (plo >= phi) plo = phi = 0;
     if (lane == 0) *reinterpret_cast<int4 *>(a.fresh + (int64_t)g * 4) = make_int4(plo, phi, slo, 0);
@@ -809,9 +915,9 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     }
     // event counters: 64 interleaved sets, because thousands of wavefronts ending at the
     // same time on one address serialise in the L2 atomic unit (measured: ~1.7 ms per launch)
-    if (lane < 7) {
-        const unsigned long long v = lane == 0 ? n_pairs : lane == 1 ? n_fired : lane == 2 ? n_type1
-                                   : lane == 3 ? n_changes : lane == 4 ? n_cand : lane == 5 ? n_type2 : n_eval;
+    if (lane >= 1 && lane < 7) {
+        const unsigned long long v = lane == 1 ? n_fired : lane == 2 ? n_type1 : lane == 3 ? n_changes
+                                   : lane == 4 ? n_cand : lane == 5 ? n_type2 : n_eval;
         if (v) atomicAdd(&a.counters[(g & (COUNTER_SETS - 1)) * 8 + lane], v);
     }
 }
@@ -839,10 +945,13 @@ struct tm_handle {
     uint32_t *ostar;
     uint32_t *XT;
     int32_t *negcls;
+    int32_t *cand;  // [m][qp] candidate lists of the current epoch
+    int32_t *ncand; // [m]
     int32_t *fresh;
     unsigned long long *counters;
     int32_t *flag;
     uint32_t epoch;
+    uint64_t pairs_visited; // (clause, example) visits enqueued since the counters were last read
     int last_hip;
 };
 
@@ -886,7 +995,7 @@ Dims make_dims(const tm_config *cfg)
 }
 
 struct WsLayout {
-    size_t tally, ostar, xt, negcls, fresh, counters, flag, total;
+    size_t tally, ostar, xt, negcls, cand, ncand, fresh, counters, flag, total;
 };
 
 WsLayout ws_layout(const Dims &d, int64_t q)
@@ -899,6 +1008,8 @@ WsLayout ws_layout(const Dims &d, int64_t q)
     L.ostar = off; off += align256((size_t)d.C * Qw * 4);
     L.xt = off; off += align256((size_t)d.Wf * qp * 4);
     L.negcls = off; off += align256((size_t)qp * 4);
+    L.cand = off; off += align256((size_t)d.m * qp * 4);
+    L.ncand = off; off += align256((size_t)d.m * 4);
     L.fresh = off; off += align256((size_t)d.C * 16);
     L.counters = off; off += align256((size_t)COUNTER_SETS * 8 * 8);
     L.flag = off; off += 256;
@@ -988,7 +1099,7 @@ int launch_eval(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *bits, int6
 
 struct TrainPtrs {
     const uint32_t *X, *XT;
-    const int32_t *y, *negcls;
+    const int32_t *cand, *ncand;
 };
 
 template <int WPL>
@@ -996,8 +1107,8 @@ void launch_train_t(const TrainPtrs &p, const TrainArgs &a, bool full, hipStream
 {
     const size_t lds = (size_t)a.lds_wave_words * TRAIN_WAVES * 4;
     const dim3 grid((unsigned)((a.d.C + TRAIN_WAVES - 1) / TRAIN_WAVES)), block(64 * TRAIN_WAVES);
-    if (full) hipLaunchKernelGGL((k_train<WPL, true>), grid, block, lds, st, p.X, p.XT, p.y, p.negcls, a);
-    else hipLaunchKernelGGL((k_train<WPL, false>), grid, block, lds, st, p.X, p.XT, p.y, p.negcls, a);
+    if (full) hipLaunchKernelGGL((k_train<WPL, true>), grid, block, lds, st, p.X, p.XT, p.cand, p.ncand, a);
+    else hipLaunchKernelGGL((k_train<WPL, false>), grid, block, lds, st, p.X, p.XT, p.cand, p.ncand, a);
 }
 
 // Examples per launch of the training kernel.  An epoch is cut into ranges
@@ -1015,7 +1126,7 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
 {
     const Dims &d = h->d;
     TrainArgs a;
-    const TrainPtrs p{h->X, h->XT, h->y, h->negcls};
+    const TrainPtrs p{h->X, h->XT, h->cand, h->ncand};
     a.d = d; a.sat = h->sat; a.planes = h->planes; a.inc = h->inc; a.tally = h->tally;
     a.vhat = vhat; a.ostar = h->ostar; a.fresh = h->fresh; a.counters = h->counters;
     a.q = h->q; a.qp = h->qp; a.Qw = h->Qw; a.epoch = h->epoch;
@@ -1025,6 +1136,7 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     const bool full = (d.N == 128);
     const int wpl = (d.W + 63) / 64;
     const int64_t chunk = train_chunk(d);
+    h->pairs_visited += (uint64_t)d.C * (uint64_t)(i_end - i_begin);
     for (int64_t b = (i_begin / chunk) * chunk; b < i_end; b += chunk) {
         a.i_begin = std::max(b, i_begin);
         a.i_end = std::min(b + chunk, i_end);
@@ -1048,6 +1160,9 @@ int run_negcls(tm_handle *h, hipStream_t st)
 {
     hipLaunchKernelGGL(k_negcls, dim3(blocks_for(h->qp, 256)), dim3(256), 0, st, h->d, h->y, h->negcls, h->q,
                        h->qp, h->epoch);
+    TM_HIP(h, hipGetLastError());
+    hipLaunchKernelGGL(k_cand_lists, dim3(h->d.m), dim3(1024), 0, st, h->y, h->negcls, h->cand, h->ncand, h->q,
+                       h->qp);
     TM_HIP(h, hipGetLastError());
     return TM_OK;
 }
@@ -1152,6 +1267,8 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
     h->ostar = (uint32_t *)(base + L.ostar);
     h->XT = (uint32_t *)(base + L.xt);
     h->negcls = (int32_t *)(base + L.negcls);
+    h->cand = (int32_t *)(base + L.cand);
+    h->ncand = (int32_t *)(base + L.ncand);
     h->fresh = (int32_t *)(base + L.fresh);
     h->counters = (unsigned long long *)(base + L.counters);
     h->flag = (int32_t *)(base + L.flag);
@@ -1334,6 +1451,8 @@ int tm_read_counters(tm_handle *h, uint64_t *out, void *stream)
         out[k] = 0;
         for (int c = 0; c < COUNTER_SETS; ++c) out[k] += tmp[c * 8 + k];
     }
+    out[0] = h->pairs_visited; // every clause visits every example of a pass; known on the host
+    h->pairs_visited = 0;
     return fill(h, h->counters, (size_t)COUNTER_SETS * 64, 0u, st);
 }
 

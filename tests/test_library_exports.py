@@ -39,9 +39,11 @@ def test_sizes_and_validation_are_host_only():
     assert B.tm_state_bytes(cfg) == C * W * 32 + C * W * 4
     ws = B.tm_train_ws_bytes(cfg, 60000)
     qp = 60032
-    # tallies + one bit per example per clause + transposed X + negative class + counters/flag
-    assert ws >= 10 * qp * 4 + C * qp // 8 + 25 * qp * 4 + qp * 4
-    assert ws < 1.01 * (10 * qp * 4 + C * qp // 8 + 25 * qp * 4 + qp * 4) + 4096
+    # tallies + one bit per example per clause + transposed X + negative class + candidate lists
+    # + per-clause freshness ranges + counters/flag
+    need = 10 * qp * 4 + C * qp // 8 + 25 * qp * 4 + qp * 4 + 10 * qp * 4 + C * 16
+    assert ws >= need
+    assert ws < 1.01 * need + 8192
     bad = [dict(m=1), dict(n=3), dict(n=0), dict(o=0), dict(N=0), dict(N=129), dict(T=0), dict(s=0.5)]
     for kw in bad:
         a = dict(m=2, n=4, o=8, N=10, T=5, s=3.0)
