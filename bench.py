@@ -47,14 +47,22 @@ GATE_OPS = PHILOX_OPS + 8                                # one block + clip, err
 # (--calibration-copy): FETCH_SIZE reads 524,310 KiB for 1,048,576 KiB fetched, WRITE_SIZE reads
 # 1,048,576 KiB for 1,048,576 KiB written.  Summaries are under profiles/.
 MEASURED_TRAFFIC = {
-    "image_like": {"fetch_kib": 58186.0, "fetch_scale": 2.0, "write_kib": 44227.0, "write_scale": 1.0},
+    "image_like": {"fetch_kib": 30086.0, "fetch_scale": 2.0, "write_kib": 47063.0, "write_scale": 1.0},
 }
 
 
-def train_kernel_ops(counters, W):
-    """Algorithmic lane-ops of a run of the training kernel from its event counters."""
-    return (counters["pairs"] * (W + 2)                    # one AND-OR per literal word + refresh
-            + counters["candidates"] * GATE_OPS
+def train_kernel_ops(counters, W, nominal=False):
+    """Algorithmic lane-ops of a run of the training kernel from its event counters.
+
+    nominal=False counts what the method needs on this run: evaluation and refresh only for the
+    (clause, 64-example block) pairs whose stored outputs could be outdated or in which a gate
+    fired, one random draw per gate whose error is positive.  nominal=True counts the method as
+    literally read (every visited pair evaluated and refreshed, one draw per candidate): the
+    difference is work the kernel proves unnecessary and skips, with identical results."""
+    pairs = counters["pairs"] if nominal else counters["blocks_evaluated"] * 64
+    draws = counters["candidates"] if nominal else counters["gate_draws"]
+    return (pairs * (W + 2)                                # one AND-OR per literal word + refresh
+            + counters["candidates"] * (GATE_OPS - PHILOX_OPS) + draws * PHILOX_OPS
             + counters["type1"] * W * TYPE1_OPS_PER_WORD
             + counters["type2_active"] * W * TYPE2_OPS_PER_WORD)
 
@@ -220,6 +228,7 @@ def main():
     n_launch = (q + chunk - 1) // chunk
     launch_ms = fit_avg / n_launch
     ops = train_kernel_ops(cnt, W) / args.steps / n_launch
+    ops_nominal = train_kernel_ops(cnt, W, nominal=True) / args.steps / n_launch
     achieved = ops / (launch_ms * 1e-3) / 1e12
     # algorithmic HBM bytes of one training launch: TA planes in + out and include masks out for
     # every clause, and the launch's share of X, transposed X, previous-output bits in + out,
@@ -272,6 +281,8 @@ def main():
             "launches_per_epoch": n_launch,
             "examples_per_launch": chunk,
             "algorithmic_lane_ops_per_launch": ops,
+            "nominal_lane_ops_per_launch": ops_nominal,
+            "nominal_frac": ops_nominal / (launch_ms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
             "hbm_algorithmic_bytes_per_launch": hbm_bytes,
             "hbm_achieved_GBs": hbm_bytes / (launch_ms * 1e-3) / 1e9,
             "hbm_frac": hbm_bytes / (launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,

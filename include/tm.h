@@ -153,12 +153,13 @@ int tm_set_epoch(tm_handle *h, uint32_t epoch);
 int tm_get_epoch(tm_handle *h, uint32_t *epoch);
 
 /* Device-side event counters of the training kernel since the last call of
- * this function (or since tm_bind_train): out is HOST uint64 [7]:
+ * this function (or since tm_bind_train): out is HOST uint64 [8]:
  * [0] visited (clause, example) pairs, [1] fired gates, [2] Type I feedbacks,
  * [3] tally changes, [4] pairs whose class was trained for the example (gate
  * candidates), [5] Type II feedbacks given to a clause with output 1,
  * [6] blocks of 64 examples that a clause had to evaluate (blocks whose stored
- * outputs are known to be current and in which no gate fires are skipped).
+ * outputs are known to be current and in which no gate fires are skipped),
+ * [7] gate candidates whose error e was positive (a random draw was needed).
  * Synchronises the stream. */
 int tm_read_counters(tm_handle *h, uint64_t *out, void *stream);
 

@@ -169,10 +169,11 @@ def tm_get_epoch(h):
 
 
 def tm_read_counters(h):
-    out = (ctypes.c_uint64 * 7)()
+    out = (ctypes.c_uint64 * 8)()
     _check(lib().tm_read_counters(h, out, _stream()), "tm_read_counters")
     return {"pairs": out[0], "fired": out[1], "type1": out[2], "tally_changes": out[3],
-            "candidates": out[4], "type2_active": out[5], "blocks_evaluated": out[6]}
+            "candidates": out[4], "type2_active": out[5], "blocks_evaluated": out[6],
+            "gate_draws": out[7]}
 
 
 class TsetlinMachine:

@@ -651,7 +651,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     const int first_blk = min(tz >> 2, 4);
     const uint32_t ge_init = d.thr >= 65536u ? 0u : ~0u;
 
-    unsigned long long n_fired = 0, n_type1 = 0, n_changes = 0, n_cand = 0, n_type2 = 0, n_eval = 0;
+    unsigned long long n_fired = 0, n_type1 = 0, n_changes = 0, n_cand = 0, n_type2 = 0, n_eval = 0, n_draw = 0;
 
     // Which stored previous outputs o* can differ from the clause's current output: only
     // those not re-evaluated since the include mask last changed.  Kept per clause as two
@@ -713,11 +713,12 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
             const bool valid = ent >= 0;
             iv = ent >> 1;
             const bool target = (ent & 1) != 0;
-            bool fire = false;
+            bool fire = false, open = false;
             if (valid) {
                 const int vc = min(max(v, -T), T);
                 const int e = target ? T - vc : T + vc; // Algorithm 1: error of the recorded vote sum
-                if (e > 0) {
+                open = e > 0;
+                if (open) {
                     const U4 r = draw(d.key, STREAM_GATE, 0, (uint32_t)g, (uint64_t)(uint32_t)iv, a.epoch);
                     fire = (uint64_t)r.x * (uint64_t)(2 * (int64_t)T) < ((uint64_t)e << 32);
                 }
@@ -725,6 +726,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
             fmask = ballot(fire);
             tmask = ballot(target);
             n_cand += __builtin_popcountll(ballot(valid));
+            n_draw += __builtin_popcountll(ballot(open));
             n_fired += __builtin_popcountll(fmask);
         }
 
@@ -915,9 +917,9 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     }
     // event counters: 64 interleaved sets, because thousands of wavefronts ending at the
     // same time on one address serialise in the L2 atomic unit (measured: ~1.7 ms per launch)
-    if (lane >= 1 && lane < 7) {
+    if (lane >= 1 && lane < 8) {
         const unsigned long long v = lane == 1 ? n_fired : lane == 2 ? n_type1 : lane == 3 ? n_changes
-                                   : lane == 4 ? n_cand : lane == 5 ? n_type2 : n_eval;
+                                   : lane == 4 ? n_cand : lane == 5 ? n_type2 : lane == 6 ? n_eval : n_draw;
         if (v) atomicAdd(&a.counters[(g & (COUNTER_SETS - 1)) * 8 + lane], v);
     }
 }
@@ -1447,7 +1449,7 @@ int tm_read_counters(tm_handle *h, uint64_t *out, void *stream)
     unsigned long long tmp[COUNTER_SETS * 8];
     TM_HIP(h, hipMemcpyAsync(tmp, h->counters, sizeof(tmp), hipMemcpyDeviceToHost, st));
     TM_HIP(h, hipStreamSynchronize(st));
-    for (int k = 0; k < 7; ++k) {
+    for (int k = 0; k < 8; ++k) {
         out[k] = 0;
         for (int c = 0; c < COUNTER_SETS; ++c) out[k] += tmp[c * 8 + k];
     }
