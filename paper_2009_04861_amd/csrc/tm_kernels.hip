@@ -504,14 +504,16 @@ struct TrainArgs {
     int64_t q, qp, Qw, i_begin, i_end;
     uint32_t epoch;
     int lds_mask_words; // W rounded up to a multiple of 4
-    int lds_off_words;  // Wf + 8 rounded up to a multiple of 4
+    int lds_off_words;  // Wf + EVAL_PAD rounded up to a multiple of 4
     int lds_wave_words; // LDS words per wavefront
 };
+
+constexpr int EVAL_PAD = 8; // empty entries after the list: a group may read that far past its end
 
 // The clause as the evaluation loop wants it: one entry per feature word whose
 // plain or negated mask word is non-zero, compacted in LDS: eoff[k] = byte
 // offset of that word's row in XT, emask[k] = {mask of plain literals, mask of
-// negated literals}; padded with eight empty entries.  Rebuilt whenever plane 7
+// negated literals}; padded with EVAL_PAD empty entries.  Rebuilt whenever plane 7
 // changes.
 template <int WPL>
 __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lmask, uint32_t *eoff,
@@ -538,7 +540,7 @@ __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lm
         }
         n += __builtin_popcountll(b);
     }
-    if (lane < 8) {
+    if (lane < EVAL_PAD) {
         eoff[n + lane] = 0u;
         emask[n + lane] = make_uint2(0u, 0u);
     }
@@ -547,29 +549,34 @@ __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lm
 }
 
 // Clause outputs for 64 examples, lane = example: bit l of the result is
-// C(X_{i0+l}).  xt_block points at XT[0][i0].  Entries are taken eight at a
-// time: their eight coalesced 256-byte loads are in flight together, the masks
-// arrive as LDS broadcasts, and each entry costs two bit operations.  Stops as
-// soon as all 64 examples are violated.
+// C(X_{i0+l}).  xt_block points at XT[0][i0].  An entry costs one coalesced
+// 256-byte load, an LDS broadcast of its masks and two bit operations.
+// Entries are taken eight at a time (eight loads in flight; more in flight
+// costs registers, hence occupancy, and measured slower); a dense (young)
+// clause violates all 64 examples within the first group and the loop stops.
+constexpr int EVAL_GROUP = 8;
+
 __device__ __forceinline__ uint64_t eval64(const uint32_t *eoff, const uint2 *emask, int nent,
                                            const uint32_t *__restrict__ xt_block, int lane)
 {
     uint32_t viol = 0;
     const char *base = reinterpret_cast<const char *>(xt_block);
     const uint32_t lane4 = (uint32_t)lane * 4u;
-    for (int k = 0; k < nent; k += 8) {
-        const uint4 oa = *reinterpret_cast<const uint4 *>(eoff + k);
-        const uint4 ob = *reinterpret_cast<const uint4 *>(eoff + k + 4);
-        const uint32_t off[8] = {oa.x, oa.y, oa.z, oa.w, ob.x, ob.y, ob.z, ob.w};
-        uint32_t x[8];
+    for (int k = 0; k < nent; k += EVAL_GROUP) {
+        uint32_t off[EVAL_GROUP], x[EVAL_GROUP];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) x[j] = *reinterpret_cast<const uint32_t *>(base + (off[j] + lane4));
+        for (int j = 0; j < EVAL_GROUP; j += 4) {
+            const uint4 o = *reinterpret_cast<const uint4 *>(eoff + k + j);
+            off[j] = o.x; off[j + 1] = o.y; off[j + 2] = o.z; off[j + 3] = o.w;
+        }
+#pragma unroll
+        for (int j = 0; j < EVAL_GROUP; ++j) x[j] = *reinterpret_cast<const uint32_t *>(base + (off[j] + lane4));
         const uint4 *mq = reinterpret_cast<const uint4 *>(emask + k);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < EVAL_GROUP / 2; ++j) {
             const uint4 m = mq[j]; // {plain, negated} masks of entries 2j and 2j+1
             // a plain literal is violated where x = 0, a negated one where x = 1
-            viol |= ((x[2 * j] & m.y) | (~x[2 * j] & m.x)) | ((x[2 * j + 1] & m.w) | (~x[2 * j + 1] & m.z));
+            viol |= bitselect(x[2 * j], m.y, m.x) | bitselect(x[2 * j + 1], m.w, m.z);
         }
         if (ballot(viol == 0u) == 0) break;
     }
@@ -620,7 +627,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     const int g = blockIdx.x * TRAIN_WAVES + wave;
     if (g >= d.C) return; // whole wavefront; the kernel has no workgroup-wide barrier
     uint32_t *lmask = lds + wave * a.lds_wave_words;        // [W] include masks, literal-word order
-    uint32_t *eoff = lmask + a.lds_mask_words;              // [Wf + 8] (rounded to 4 words)
+    uint32_t *eoff = lmask + a.lds_mask_words;              // [Wf + EVAL_PAD] (rounded to 4 words)
     uint2 *emask = reinterpret_cast<uint2 *>(eoff + a.lds_off_words);
 
     const int c = g / d.n;
@@ -1114,12 +1121,14 @@ void launch_train_t(const TrainPtrs &p, const TrainArgs &a, bool full, hipStream
 }
 
 // Examples per launch of the training kernel.  An epoch is cut into ranges
-// whose slice of XT (Wf rows of `chunk` words) stays resident in one XCD's
-// 4 MiB L2 while all clauses stream over it; without the cut, wavefronts
-// drift apart over the whole of XT and re-fetch it from HBM many times.
+// whose slice of XT (Wf rows of `chunk` words) is at most 2 MiB, half of one
+// XCD's L2, so that it stays resident while all clauses stream over it; with
+// the whole epoch in one launch wavefronts drift apart over all of XT and
+// re-fetch it from HBM many times (measured: 6x the fetch traffic), while
+// shorter ranges only add launches.
 int64_t train_chunk(const Dims &d)
 {
-    int64_t chunk = ((int64_t)(1 << 20) / (4 * (int64_t)d.Wf)) & ~(int64_t)63;
+    int64_t chunk = ((int64_t)(2 << 20) / (4 * (int64_t)d.Wf)) & ~(int64_t)63;
     if (chunk < 512) chunk = 512;
     return chunk;
 }
@@ -1133,8 +1142,8 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     a.vhat = vhat; a.ostar = h->ostar; a.fresh = h->fresh; a.counters = h->counters;
     a.q = h->q; a.qp = h->qp; a.Qw = h->Qw; a.epoch = h->epoch;
     a.lds_mask_words = (d.W + 3) & ~3;
-    a.lds_off_words = (d.Wf + 8 + 3) & ~3;
-    a.lds_wave_words = a.lds_mask_words + a.lds_off_words + 2 * ((d.Wf + 8 + 1) & ~1);
+    a.lds_off_words = (d.Wf + EVAL_PAD + 3) & ~3;
+    a.lds_wave_words = a.lds_mask_words + a.lds_off_words + 2 * ((d.Wf + EVAL_PAD + 1) & ~1);
     const bool full = (d.N == 128);
     const int wpl = (d.W + 63) / 64;
     const int64_t chunk = train_chunk(d);
