@@ -63,6 +63,8 @@ typedef struct {
     double s;                  /* specificity, >= 1.0                                 */
     uint64_t seed;             /* key of the counter-based random generator           */
     int32_t device;            /* HIP device ordinal                                  */
+    int32_t boost_true_positive; /* 0/1: strong Type I probability (s-1)/s replaced by 1
+                                    (footnote of Section 2.2)                          */
 } tm_config;
 
 /* Size in bytes of the model state buffer (bit-sliced TA states + include

@@ -54,6 +54,8 @@ typedef struct {
     int32_t  T;      /* voting margin               */
     double   s;      /* specificity                 */
     uint64_t seed;
+    int32_t  boost;  /* boost true positives: the strong Type I probability (s-1)/s becomes 1
+                        (footnote of Section 2.2) */
 } otm_config;
 
 enum { OTM_INIT = 0, OTM_GATE = 1, OTM_TYPE1 = 2, OTM_NEGCLASS = 3 };
@@ -257,8 +259,9 @@ void otm_type1(const otm_config *cfg, int32_t *st, const uint8_t *lit, int Cout,
         for (int b = 0; b < 16; ++b)
             u |= (int32_t)((R[b] >> j) & 1u) << b;
         if (Cout == 1 && lit[k] == 1) {
-            /* strong: reward Include / penalise Exclude, probability (s-1)/s */
-            if (u >= thr && st[k] < 2 * cfg->N)
+            /* strong: reward Include / penalise Exclude, probability (s-1)/s,
+             * or 1 when true positives are boosted */
+            if ((cfg->boost || u >= thr) && st[k] < 2 * cfg->N)
                 st[k] += 1;
         } else {
             /* weak: penalise Include / reward Exclude, probability 1/s */

@@ -31,7 +31,7 @@ def build(force=False):
 class Config(ctypes.Structure):
     _fields_ = [("m", ctypes.c_int32), ("n", ctypes.c_int32), ("o", ctypes.c_int32),
                 ("N", ctypes.c_int32), ("T", ctypes.c_int32), ("s", ctypes.c_double),
-                ("seed", ctypes.c_uint64)]
+                ("seed", ctypes.c_uint64), ("boost", ctypes.c_int32)]
 
 
 _lib = None
@@ -61,8 +61,8 @@ def _chk(a, dtype, shape=None):
 class Oracle:
     """Holds a configuration and the TA states; methods mirror the C functions."""
 
-    def __init__(self, m, n, o, N, T, s, seed, init=True):
-        self.cfg = Config(m, n, o, N, T, float(s), seed)
+    def __init__(self, m, n, o, N, T, s, seed, init=True, boost=False):
+        self.cfg = Config(m, n, o, N, T, float(s), seed, 1 if boost else 0)
         self.m, self.n, self.o, self.N, self.T, self.s, self.seed = m, n, o, N, T, float(s), seed
         self.C, self.L = m * n, 2 * o
         self.state = np.zeros((self.C, self.L), dtype=np.int32)

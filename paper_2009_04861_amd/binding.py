@@ -27,7 +27,7 @@ class tm_config(ctypes.Structure):
     _fields_ = [("n_classes", ctypes.c_int32), ("clauses_per_class", ctypes.c_int32),
                 ("n_features", ctypes.c_int32), ("states_per_action", ctypes.c_int32),
                 ("T", ctypes.c_int32), ("s", ctypes.c_double), ("seed", ctypes.c_uint64),
-                ("device", ctypes.c_int32)]
+                ("device", ctypes.c_int32), ("boost_true_positive", ctypes.c_int32)]
 
 
 class TMError(RuntimeError):
@@ -76,8 +76,8 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def make_config(m, n, o, N, T, s, seed, device=0):
-    return tm_config(int(m), int(n), int(o), int(N), int(T), float(s), int(seed), int(device))
+def make_config(m, n, o, N, T, s, seed, device=0, boost=False):
+    return tm_config(int(m), int(n), int(o), int(N), int(T), float(s), int(seed), int(device), 1 if boost else 0)
 
 
 def tm_state_bytes(cfg):
@@ -182,11 +182,11 @@ class TsetlinMachine:
     Bit-packed uint32 data travels in int32 tensors (torch has no full uint32
     support); the bit patterns are what matters."""
 
-    def __init__(self, m, n, o, N, T, s, seed, device=0):
+    def __init__(self, m, n, o, N, T, s, seed, device=0, boost=False):
         self.m, self.n, self.o, self.N, self.T, self.s, self.seed = m, n, o, N, T, float(s), seed
         self.C, self.L, self.Wf = m * n, 2 * o, (o + 31) // 32
         self.dev = torch.device("cuda", device)
-        self.cfg = make_config(m, n, o, N, T, s, seed, device)
+        self.cfg = make_config(m, n, o, N, T, s, seed, device, boost)
         with torch.cuda.device(self.dev):
             self.state_buf = torch.empty(tm_state_bytes(self.cfg), dtype=torch.uint8, device=self.dev)
             self.h = tm_create(self.cfg, self.state_buf)

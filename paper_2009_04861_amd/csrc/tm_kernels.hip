@@ -34,6 +34,7 @@ namespace tsetlin {
 struct Dims {
     int m, n, o, N, T, C, Wf, W;
     uint32_t thr;      // 16-bit threshold: P(u < thr) = 1/s
+    uint32_t boost;    // ~0 if true positives are boosted (strong Type I event certain), else 0
     uint32_t tailmask; // valid bits of the last feature word
     RngKey key;
 };
@@ -884,8 +885,8 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
                     uint32_t sp[8];
                     get_slot(p[r], sp);
                     const uint32_t old7 = sp[7];
-                    if (Cout) { // strong: literals that are 1 move towards Include with probability (s-1)/s
-                        const uint32_t m = lit & ge & ~at_value<FULL>(sp, a.sat.kmax, true);
+                    if (Cout) { // strong: literals that are 1 move towards Include with probability (s-1)/s (1 if boosted)
+                        const uint32_t m = lit & (ge | d.boost) & ~at_value<FULL>(sp, a.sat.kmax, true);
                         ripple_inc(sp, m);
                     }
                     // weak: everything else moves towards Exclude with probability 1/s
@@ -977,6 +978,7 @@ int check_config(const tm_config *cfg)
     if (cfg->T < 1 || cfg->T > (1 << 29)) return TM_EINVAL;
     if (!(cfg->s >= 1.0) || !isfinite(cfg->s)) return TM_EINVAL;
     if (cfg->device < 0) return TM_EINVAL;
+    if (cfg->boost_true_positive != 0 && cfg->boost_true_positive != 1) return TM_EINVAL;
     if (cfg->n_features > TM_MAX_FEATURES) return TM_ELIMIT;
     if ((int64_t)cfg->n_classes * cfg->clauses_per_class > (int64_t)1 << 30) return TM_ELIMIT;
     return TM_OK;
@@ -997,6 +999,7 @@ Dims make_dims(const tm_config *cfg)
     if (t < 0.0) t = 0.0;
     if (t > 65536.0) t = 65536.0;
     d.thr = (uint32_t)t;
+    d.boost = cfg->boost_true_positive ? ~0u : 0u;
     d.tailmask = (d.o & 31) ? ((1u << (d.o & 31)) - 1u) : ~0u;
     d.key.seed_lo = (uint32_t)(cfg->seed & 0xffffffffu);
     d.key.seed_hi = (uint32_t)(cfg->seed >> 32);

@@ -8,9 +8,9 @@ from paper_2009_04861_amd import binding as B
 from paper_2009_04861_amd import synth
 
 
-def make_pair(m, n, o, N, T, s, seed):
+def make_pair(m, n, o, N, T, s, seed, boost=False):
     """An oracle and a GPU machine with the same configuration."""
-    return O.Oracle(m, n, o, N, T, s, seed), B.TsetlinMachine(m, n, o, N, T, s, seed)
+    return O.Oracle(m, n, o, N, T, s, seed, boost=boost), B.TsetlinMachine(m, n, o, N, T, s, seed, boost=boost)
 
 
 def dev_bits(gpu, X_u8):

@@ -216,6 +216,27 @@ def test_quiet_epochs_skip_evaluation_but_change_nothing(device):
     print("blocks evaluated: %d of %d" % (c["blocks_evaluated"], blocks), flush=True)
 
 
+@pytest.mark.parametrize("N", [5, 128])
+def test_feedback_with_boosted_true_positives(N, device):
+    m, n, o, T, s = 3, 8, 70, 6, 4.0
+    rng = np.random.default_rng(91)
+    q = 200
+    ora, gpu = make_pair(m, n, o, N, T, s, 23, boost=True)
+    X, y = rand_problem(rng, q, o, m, density=0.5)
+    X[::3] = 1
+    ora.state[:] = sparse_random_state(rng, ora.C, ora.L, N, 2.0 / o)
+    push_state(gpu, ora.state)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    for ep in range(6):
+        B.tm_set_epoch(gpu.h, ep)
+        run_frozen(ora, gpu, X, y, ep, 0, q, tally, ostar)
+    assert np.array_equal(gpu_state_as_oracle(gpu), ora.state)
+    assert np.array_equal(gpu.tallies().cpu().numpy(), tally)
+    assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar)
+    assert ora.state.max() > N
+
+
 def test_noisy_xor_frozen_epochs_match(device):
     # the small benchmark configuration, whole epochs, snapshot = tallies at epoch start
     Xtr, ytr, Xte, yte = synth.noisy_xor(1000, 500)

@@ -528,3 +528,23 @@ def test_subset_step_equals_full_step_on_those_clauses():
     b.feedback_step_subset(X, y, vhat, sub, 2, 0, 120, ids)
     assert np.array_equal(a.state[ids], b.state[ids])
     assert np.array_equal(sub, ostar[ids])
+
+
+def test_boost_true_positive_makes_the_strong_event_certain():
+    # footnote of Section 2.2: (s-1)/s is replaced by 1; the weak event keeps probability 1/s
+    o, N, s = 24, 50, 4.0
+    t = O.Oracle(2, 2, o, N, 5, s, 3, init=False, boost=True)
+    rng = np.random.default_rng(4)
+    weak_moves = weak_total = 0
+    for i in range(300):
+        lit = rng.integers(0, 2, size=2 * o).astype(np.uint8)
+        st = np.full(2 * o, N, dtype=np.int32)
+        t.type1(st, lit, 1, 0, i, 0)
+        assert np.all(st[lit == 1] == N + 1)                 # strong: every literal that is 1
+        assert np.all((st[lit == 0] == N) | (st[lit == 0] == N - 1))
+        weak_moves += int((st[lit == 0] == N - 1).sum()); weak_total += int((lit == 0).sum())
+        st = np.full(2 * o, N, dtype=np.int32)
+        t.type1(st, lit, 0, 0, i, 0)                         # clause 0: boost changes nothing
+        assert np.all(st <= N)
+    p = 1 / s
+    assert abs(weak_moves / weak_total - p) < 4.5 * np.sqrt(p * (1 - p) / weak_total)
