@@ -1269,8 +1269,10 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
     hipStream_t st = (hipStream_t)stream;
     TM_HIP(h, hipSetDevice(h->cfg.device));
     const Dims &d = h->d;
-    // the evaluation loop addresses XT rows with 32-bit byte offsets
+    // the evaluation loop addresses XT rows with 32-bit byte offsets, and candidate-list
+    // entries pack the example index into 31 bits
     if ((int64_t)d.Wf * ((q + 63) & ~(int64_t)63) * 4 >= ((int64_t)1 << 32)) return TM_ELIMIT;
+    if (q > ((int64_t)1 << 30) - 64) return TM_ELIMIT;
     const WsLayout L = ws_layout(d, q);
     char *base = (char *)ws;
     h->bound = false;
