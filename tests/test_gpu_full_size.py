@@ -97,3 +97,66 @@ def test_full_size_inference_sampled_examples(workload, device):
     assert sums.min() >= -hp["T"] and sums.max() <= hp["T"]
     assert np.array_equal(pred, sums.argmax(axis=1))
     gpu.close()
+
+
+@pytest.mark.parametrize("name,q,n_small", [("text_like", 25000, 64), ("stress", 20000, 32)])
+def test_wide_feature_workloads_sampled_clauses(name, q, n_small, device):
+    """The text-like (10,000 features, 10 register slots per lane) and stress (20,000 features,
+    20 slots) workloads at their real feature width and example counts (stress: a 10 % subsample
+    of the examples), with a reduced number of clauses so that the oracle can initialise the
+    machine; per-clause work, kernels and launch shapes per clause are those of the full machine."""
+    hp = dict(synth.WORKLOADS[name])
+    hp["n"] = n_small
+    hp["T"] = max(2, int(0.8 * n_small))
+    if name == "text_like":
+        Xtr, ytr, Xte, yte = synth.text_like(q, 2000)
+    else:
+        X, y = synth.planted_conjunctions(q + 2000)
+        Xtr, ytr, Xte, yte = X[:q], y[:q], X[q:], y[q:]
+    m, n = hp["m"], hp["n"]
+    rng = np.random.default_rng(2)
+    print(name, "oracle init", flush=True)
+    ora = O.Oracle(seed=5, **hp)
+    gpu = B.TsetlinMachine(seed=5, **hp)
+    assert np.array_equal(gpu.get_ta_state().cpu().numpy().astype(np.int32) + 1, ora.state)
+    # the second half of the clauses: a trained-looking state (ten negated literals included,
+    # everything else excluded), so that clauses are satisfied by most examples of these sparse data
+    half = m * n // 2
+    ora.state[half:] = rng.integers(1, hp["N"] + 1, size=(m * n - half, ora.L))
+    for g in range(half, m * n):
+        ora.state[g, hp["o"] + rng.integers(0, hp["o"], size=10)] = rng.integers(hp["N"] + 1, 2 * hp["N"] + 1, size=10)
+    push_state(gpu, ora.state)
+
+    print(name, "bind", flush=True)
+    gpu.bind_train(dev_bits(gpu, Xtr), dev_i32(gpu, ytr))
+    ids = np.array([1, m * n - 2, m * n - 1], dtype=np.int32)   # one young clause, two trained-looking ones
+    ostar_sub = ora.clause_outputs_subset(Xtr, ids)
+    assert ostar_sub[1:].mean() > 0.3
+    prev = gpu.prev_outputs()
+    sel = torch.from_numpy(ids).long().to(prev.device)
+    assert np.array_equal(bits_to_u8(prev[sel], q), ostar_sub)
+
+    print(name, "frozen pass", flush=True)
+    vhat = rng.integers(-hp["T"], hp["T"] + 1, size=(q, m)).astype(np.int32)
+    B.tm_set_epoch(gpu.h, 2)
+    gpu.feedback_step(dev_i32(gpu, vhat), 0, q)
+    fired = ora.feedback_step_subset(Xtr, ytr, vhat, ostar_sub, 2, 0, q, ids)
+    assert fired > 100
+    st = gpu.get_ta_state()[sel].cpu().numpy().astype(np.int32) + 1
+    assert np.array_equal(st, ora.state[ids])
+    prev = gpu.prev_outputs()
+    assert np.array_equal(bits_to_u8(prev[sel], q), ostar_sub)
+    tally = gpu.tallies().cpu().numpy()
+    sign = np.where(np.arange(n) % 2 == 1, 1, -1).astype(np.int32)
+    for c in range(m):
+        bits = bits_to_u8(prev[c * n:(c + 1) * n], q)
+        assert np.array_equal(tally[:, c], sign @ bits.astype(np.int32))
+
+    print(name, "inference", flush=True)
+    ora.state[:] = gpu.get_ta_state().cpu().numpy().astype(np.int32) + 1
+    Xd = dev_bits(gpu, Xte)
+    ex = rng.integers(0, len(yte), size=24)
+    Xs = np.ascontiguousarray(Xte[ex])
+    assert np.array_equal(gpu.class_sums(Xd).cpu().numpy()[ex], ora.class_sums(Xs))
+    assert np.array_equal(gpu.predict(Xd).cpu().numpy()[ex], ora.predict(Xs))
+    gpu.close()
