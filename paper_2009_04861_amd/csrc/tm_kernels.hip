@@ -241,6 +241,44 @@ __global__ void k_fresh_set(int32_t *fresh, int C, int qp, int all_stale)
     if (g < C) *reinterpret_cast<int4 *>(fresh + (int64_t)g * 4) = make_int4(0, all_stale ? qp : 0, qp, 0);
 }
 
+// Launch order of the clauses for the training kernel: those that start a launch with
+// outdated stored outputs sweep every block of the range (a long dependent chain) and go
+// first, so that they do not end up alone at the tail of the launch; the others follow in
+// index order.  One workgroup, stable partition by ballot prefixes.
+__global__ __launch_bounds__(1024) void k_order(const int32_t *__restrict__ fresh, int32_t *__restrict__ order, int C,
+                                                int i_begin, int i_end)
+{
+    __shared__ int wave_cnt[16];
+    __shared__ int base_sh[2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int pass = 0; pass < 2; ++pass) { // pass 0 places the clauses with outdated outputs, pass 1 the rest
+        if (tid == 0 && pass == 0) base_sh[0] = 0;
+        __syncthreads();
+        for (int g0 = 0; g0 < C; g0 += 1024) {
+            const int g = g0 + tid;
+            bool take = false;
+            if (g < C) {
+                const int4 f = *reinterpret_cast<const int4 *>(fresh + (int64_t)g * 4);
+                const bool stale = (f.x < f.y && f.x < i_end && f.y > i_begin) || (f.z < i_end);
+                take = (pass == 0) ? stale : !stale;
+            }
+            const uint64_t b = ballot(take);
+            const int pre = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, 0u));
+            if (lane == 0) wave_cnt[wave] = __builtin_popcountll(b);
+            __syncthreads();
+            int off = base_sh[0], total = 0;
+            for (int w = 0; w < 16; ++w) {
+                if (w < wave) off += wave_cnt[w];
+                total += wave_cnt[w];
+            }
+            if (take) order[off + pre] = g;
+            __syncthreads();
+            if (tid == 0) base_sh[0] += total;
+            __syncthreads();
+        }
+    }
+}
+
 // ------------------------------------------------------------------------
 // k_eval: clause evaluation, lane = clause   (Eq. 1, Eq. 3, Section 3.1)
 // ------------------------------------------------------------------------
@@ -501,6 +539,7 @@ struct TrainArgs {
     const int32_t *vhat; // [q][m] snapshot the gate reads instead of the live tally, or null
     uint32_t *ostar;
     int32_t *fresh; // [C][4] per clause: examples whose stored output may be outdated lie in [plo,phi) or [slo,qp)
+    const int32_t *order; // [C] clause handled by each wavefront of the launch
     unsigned long long *counters;
     int64_t q, qp, Qw, i_begin, i_end;
     uint32_t epoch;
@@ -509,7 +548,7 @@ struct TrainArgs {
     int lds_wave_words; // LDS words per wavefront
 };
 
-constexpr int EVAL_PAD = 8; // empty entries after the list: a group may read that far past its end
+constexpr int EVAL_PAD = 16; // empty entries after the list: a group may read that far past its end
 
 // The clause as the evaluation loop wants it: one entry per feature word whose
 // plain or negated mask word is non-zero, compacted in LDS: eoff[k] = byte
@@ -555,7 +594,7 @@ __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lm
 // Entries are taken eight at a time (eight loads in flight; more in flight
 // costs registers, hence occupancy, and measured slower); a dense (young)
 // clause violates all 64 examples within the first group and the loop stops.
-constexpr int EVAL_GROUP = 8;
+constexpr int EVAL_GROUP = 16;
 
 __device__ __forceinline__ uint64_t eval64(const uint32_t *eoff, const uint2 *emask, int nent,
                                            const uint32_t *__restrict__ xt_block, int lane)
@@ -625,8 +664,9 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     const Dims &d = a.d;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int g = blockIdx.x * TRAIN_WAVES + wave;
-    if (g >= d.C) return; // whole wavefront; the kernel has no workgroup-wide barrier
+    const int slot = blockIdx.x * TRAIN_WAVES + wave;
+    if (slot >= d.C) return; // whole wavefront; the kernel has no workgroup-wide barrier
+    const int g = __builtin_amdgcn_readfirstlane(a.order[slot]);
     uint32_t *lmask = lds + wave * a.lds_wave_words;        // [W] include masks, literal-word order
     uint32_t *eoff = lmask + a.lds_mask_words;              // [Wf + EVAL_PAD] (rounded to 4 words)
     uint2 *emask = reinterpret_cast<uint2 *>(eoff + a.lds_off_words);
@@ -958,6 +998,7 @@ struct tm_handle {
     int32_t *cand;  // [m][qp] candidate lists of the current epoch
     int32_t *ncand; // [m]
     int32_t *fresh;
+    int32_t *order; // [C] launch order of the clauses
     unsigned long long *counters;
     int32_t *flag;
     uint32_t epoch;
@@ -1007,7 +1048,7 @@ Dims make_dims(const tm_config *cfg)
 }
 
 struct WsLayout {
-    size_t tally, ostar, xt, negcls, cand, ncand, fresh, counters, flag, total;
+    size_t tally, ostar, xt, negcls, cand, ncand, fresh, order, counters, flag, total;
 };
 
 WsLayout ws_layout(const Dims &d, int64_t q)
@@ -1023,6 +1064,7 @@ WsLayout ws_layout(const Dims &d, int64_t q)
     L.cand = off; off += align256((size_t)d.m * qp * 4);
     L.ncand = off; off += align256((size_t)d.m * 4);
     L.fresh = off; off += align256((size_t)d.C * 16);
+    L.order = off; off += align256((size_t)d.C * 4);
     L.counters = off; off += align256((size_t)COUNTER_SETS * 8 * 8);
     L.flag = off; off += 256;
     L.total = off;
@@ -1142,7 +1184,7 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     TrainArgs a;
     const TrainPtrs p{h->X, h->XT, h->cand, h->ncand};
     a.d = d; a.sat = h->sat; a.planes = h->planes; a.inc = h->inc; a.tally = h->tally;
-    a.vhat = vhat; a.ostar = h->ostar; a.fresh = h->fresh; a.counters = h->counters;
+    a.vhat = vhat; a.ostar = h->ostar; a.fresh = h->fresh; a.order = h->order; a.counters = h->counters;
     a.q = h->q; a.qp = h->qp; a.Qw = h->Qw; a.epoch = h->epoch;
     a.lds_mask_words = (d.W + 3) & ~3;
     a.lds_off_words = (d.Wf + EVAL_PAD + 3) & ~3;
@@ -1154,6 +1196,8 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     for (int64_t b = (i_begin / chunk) * chunk; b < i_end; b += chunk) {
         a.i_begin = std::max(b, i_begin);
         a.i_end = std::min(b + chunk, i_end);
+        hipLaunchKernelGGL(k_order, dim3(1), dim3(1024), 0, st, h->fresh, h->order, d.C, (int)a.i_begin, (int)a.i_end);
+        TM_HIP(h, hipGetLastError());
         if (wpl <= 1) launch_train_t<1>(p, a, full, st);
         else if (wpl <= 2) launch_train_t<2>(p, a, full, st);
         else if (wpl <= 3) launch_train_t<3>(p, a, full, st);
@@ -1286,6 +1330,7 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
     h->cand = (int32_t *)(base + L.cand);
     h->ncand = (int32_t *)(base + L.ncand);
     h->fresh = (int32_t *)(base + L.fresh);
+    h->order = (int32_t *)(base + L.order);
     h->counters = (unsigned long long *)(base + L.counters);
     h->flag = (int32_t *)(base + L.flag);
 
