@@ -74,7 +74,8 @@ int tm_state_bytes(const tm_config *cfg, size_t *out);
 
 /* Size in bytes of the training workspace for q examples (voting tallies,
  * previous-output bits - one bit per example per clause -, transposed copy of
- * X, per-example negative class, counters).  Host-only computation. */
+ * X, per-example negative class, per-class candidate lists, per-clause
+ * bookkeeping, counters).  Host-only computation. */
 int tm_train_ws_bytes(const tm_config *cfg, int64_t q, size_t *out);
 
 /* Creates a machine whose state lives in state_buf (device, at least

@@ -9,16 +9,18 @@
 //                  XT     uint32 [Wf][qp]   transposed features (word-major) for lane = example evaluation
 //                  negcls int32  [qp]       class trained towards 0 for each example, this epoch
 //                  cand   int32  [m][qp]    per class: ascending list of (example << 1 | target) that may get feedback
-//                  counters uint64 [8], flag int32
+//                  fresh  int32  [C][4]     per clause: example ranges whose stored outputs may be outdated
+//                  order  int32  [C]        launch order of the clauses (outdated ones first)
+//                  counters uint64 [64][8] interleaved event counters, flag int32
 //   literal word lw < Wf holds x_(32 lw + j), literal word Wf + fw holds NOT x_(32 fw + j).
 //
 // Two evaluation layouts are used:
 //   k_eval_* lane = clause : include masks in VGPRs, example words arrive through
 //            scalar loads, one bit-select per feature word and pair; clause votes are
 //            summed with wave ballot + popcount (inference, tally pre-calculation).
-//   k_train  one wavefront = one clause (Algorithm 1: "every clause runs in its own
-//            thread"); lane = literal word for feedback, lane = example for the
-//            evaluation of a block of 64 examples.
+//   k_train  one wavefront = one clause (Algorithm 1 gives every clause its own
+//            thread); lane = candidate example for the gates, lane = literal word for
+//            feedback, lane = example for the evaluation of a block of 64 examples.
 #include <hip/hip_runtime.h>
 #include <algorithm>
 #include <math.h>
