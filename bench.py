@@ -48,7 +48,14 @@ GATE_OPS = PHILOX_OPS + 8                                # one block + clip, err
 # 1,048,576 KiB for 1,048,576 KiB written.  Summaries are under profiles/.
 MEASURED_TRAFFIC = {
     "image_like": {"fetch_kib": 48354.0, "fetch_scale": 2.0, "write_kib": 55477.0, "write_scale": 1.0},
+    # k_eval_resident<25,true,true> (tm_sync_tallies), per launch
+    "image_like_eval": {"fetch_kib": 174800.0, "fetch_scale": 2.0, "write_kib": 704400.0, "write_scale": 1.0},
 }
+
+# Evaluation kernel: one bit-select per feature word and pair plus half a 3-input OR, and per
+# (64-clause tile, example) a compare, the stored-output bit and the vote (about 3 per pair-lane)
+EVAL_OPS_PER_WORD = 1.5
+EVAL_OPS_EPILOGUE = 3.0
 
 
 def train_kernel_ops(counters, W, nominal=False):
@@ -287,6 +294,23 @@ def main():
             "hbm_achieved_GBs": hbm_bytes / (launch_ms * 1e-3) / 1e9,
             "hbm_frac": hbm_bytes / (launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         },
+    }
+    sync_avg = float(np.mean(sync_ms))
+    eval_ops = q * C * (EVAL_OPS_PER_WORD * tm.Wf + EVAL_OPS_EPILOGUE)
+    eval_achieved = eval_ops / (sync_avg * 1e-3) / 1e12
+    # algorithmic HBM bytes of the tally pre-calculation: masks and X once, previous-output bits and tallies out
+    eval_bytes = C * W * 4 + q * tm.Wf * 4 + C * ((q + 31) // 32) * 4 + tm.m * q * 4
+    eval_traffic = None
+    if traffic is not None:
+        t = MEASURED_TRAFFIC["image_like_eval"]
+        eval_traffic = 1024.0 * (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"])
+    out["roofline_eval"] = {
+        "kernel": "k_eval_resident (clause evaluation + votes, tm_sync_tallies over the training set)",
+        "bound": "alu", "achieved": eval_achieved, "peak": ALU_PEAK_TOPS, "unit": "Tlane-op/s (32-bit integer)",
+        "frac": eval_achieved / ALU_PEAK_TOPS, "traffic": eval_traffic, "avg_launch_ms": sync_avg,
+        "algorithmic_lane_ops_per_launch": eval_ops, "hbm_algorithmic_bytes_per_launch": eval_bytes,
+        "hbm_achieved_GBs": eval_bytes / (sync_avg * 1e-3) / 1e9,
+        "hbm_frac": eval_bytes / (sync_avg * 1e-3) / 1e9 / HBM_PEAK_GBS,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(hp, Xtr, ytr, Xte, args.seed)
