@@ -543,7 +543,7 @@ struct TrainArgs {
     int32_t *fresh; // [C][4] per clause: examples whose stored output may be outdated lie in [plo,phi) or [slo,qp)
     const int32_t *order; // [C] clause handled by each wavefront of the launch
     unsigned long long *counters;
-    int64_t q, qp, Qw, i_begin, i_end;
+    int32_t q, qp, Qw, i_begin, i_end; // example counts fit 31 bits (checked at bind)
     uint32_t epoch;
     int lds_mask_words; // W rounded up to a multiple of 4
     int lds_off_words;  // Wf + EVAL_PAD rounded up to a multiple of 4
@@ -678,7 +678,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     const int sign = pos ? 1 : -1;
     const int T = d.T;
     const uint32_t row_bytes = (uint32_t)a.qp * 4u;
-    const int i_begin = (int)a.i_begin, i_end = (int)a.i_end, q = (int)a.q;
+    const int i_begin = a.i_begin, i_end = a.i_end, q = a.q;
 
     u32x8 p[WPL];
 #pragma unroll
@@ -701,7 +701,8 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     const int first_blk = min(tz >> 2, 4);
     const uint32_t ge_init = d.thr >= 65536u ? 0u : ~0u;
 
-    unsigned long long n_fired = 0, n_type1 = 0, n_changes = 0, n_cand = 0, n_type2 = 0, n_eval = 0, n_draw = 0;
+    // per-wavefront event counts of one launch fit 32 bits (at most 2^30 examples per launch)
+    uint32_t n_fired = 0, n_type1 = 0, n_changes = 0, n_cand = 0, n_type2 = 0, n_eval = 0, n_draw = 0;
 
     // Which stored previous outputs o* can differ from the clause's current output: only
     // those not re-evaluated since the include mask last changed.  Kept per clause as two
@@ -968,9 +969,9 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     // event counters: 64 interleaved sets, because thousands of wavefronts ending at the
     // same time on one address serialise in the L2 atomic unit (measured: ~1.7 ms per launch)
     if (lane >= 1 && lane < 8) {
-        const unsigned long long v = lane == 1 ? n_fired : lane == 2 ? n_type1 : lane == 3 ? n_changes
-                                   : lane == 4 ? n_cand : lane == 5 ? n_type2 : lane == 6 ? n_eval : n_draw;
-        if (v) atomicAdd(&a.counters[(g & (COUNTER_SETS - 1)) * 8 + lane], v);
+        const uint32_t v = lane == 1 ? n_fired : lane == 2 ? n_type1 : lane == 3 ? n_changes
+                         : lane == 4 ? n_cand : lane == 5 ? n_type2 : lane == 6 ? n_eval : n_draw;
+        if (v) atomicAdd(&a.counters[(g & (COUNTER_SETS - 1)) * 8 + lane], (unsigned long long)v);
     }
 }
 
@@ -1187,7 +1188,7 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     const TrainPtrs p{h->X, h->XT, h->cand, h->ncand};
     a.d = d; a.sat = h->sat; a.planes = h->planes; a.inc = h->inc; a.tally = h->tally;
     a.vhat = vhat; a.ostar = h->ostar; a.fresh = h->fresh; a.order = h->order; a.counters = h->counters;
-    a.q = h->q; a.qp = h->qp; a.Qw = h->Qw; a.epoch = h->epoch;
+    a.q = (int32_t)h->q; a.qp = (int32_t)h->qp; a.Qw = (int32_t)h->Qw; a.epoch = h->epoch;
     a.lds_mask_words = (d.W + 3) & ~3;
     a.lds_off_words = (d.Wf + EVAL_PAD + 3) & ~3;
     a.lds_wave_words = a.lds_mask_words + a.lds_off_words + 2 * ((d.Wf + EVAL_PAD + 1) & ~1);
@@ -1196,8 +1197,8 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     const int64_t chunk = train_chunk(d);
     h->pairs_visited += (uint64_t)d.C * (uint64_t)(i_end - i_begin);
     for (int64_t b = (i_begin / chunk) * chunk; b < i_end; b += chunk) {
-        a.i_begin = std::max(b, i_begin);
-        a.i_end = std::min(b + chunk, i_end);
+        a.i_begin = (int32_t)std::max(b, i_begin);
+        a.i_end = (int32_t)std::min(b + chunk, i_end);
         hipLaunchKernelGGL(k_order, dim3(1), dim3(1024), 0, st, h->fresh, h->order, d.C, (int)a.i_begin, (int)a.i_end);
         TM_HIP(h, hipGetLastError());
         if (wpl <= 1) launch_train_t<1>(p, a, full, st);
