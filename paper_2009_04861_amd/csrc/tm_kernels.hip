@@ -628,27 +628,45 @@ __device__ __forceinline__ uint64_t eval64(const uint32_t *eoff, const uint2 *em
 constexpr int COUNTER_SETS = 64; // interleaved copies of the 8 event counters
 constexpr int TRAIN_WAVES = 4; // clauses (wavefronts) per workgroup of the training kernel
 
-// First position k in the ascending list[0..n) with list[k] >= key, found by the
-// whole wavefront: 64 probes per round, three rounds for a quarter million entries.
-__device__ __forceinline__ int wave_lower_bound(const int32_t *__restrict__ list, int n, int key, int lane)
+// First positions k1, k2 in the ascending list[0..n) with list[k] >= key1 resp. key2
+// (key1 <= key2), found by the whole wavefront: 64 probes per round and key, the probes of
+// both searches in flight together; three rounds for a quarter million entries.
+struct Bounds2 {
+    int lo, hi;
+};
+
+__device__ __forceinline__ Bounds2 wave_lower_bound2(const int32_t *__restrict__ list, int n, int key1, int key2,
+                                                     int lane)
 {
-    int lo = 0, hi = n; // answer in [lo, hi]
-    while (hi > lo) {
-        const int span = hi - lo;
-        const int step = (span + 63) >> 6;
-        const int idx = lo + lane * step;
-        const bool ge = idx < hi ? (list[idx] >= key) : true;
-        const uint64_t b = ballot(ge);
-        const int first = __builtin_ctzll(b | (1ull << 63)); // b is monotone; lane 63 counts as true if none is
-        // entries before probe `first` that are known to be < key: up to probe first-1
-        const int nlo = first == 0 ? lo : lo + (first - 1) * step + 1;
-        int nhi = lo + first * step;
-        if (nhi > hi || b == 0) nhi = hi;
-        if (step == 1) return b == 0 ? hi : min(hi, lo + first);
-        lo = min(nlo, hi);
-        hi = nhi;
+    int lo[2] = {0, 0}, hi[2] = {n, n}; // answers lie in [lo, hi]
+    const int key[2] = {key1, key2};
+    bool done[2] = {n == 0, n == 0};
+    while (!(done[0] && done[1])) {
+        int step[2], val[2];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int span = hi[s] - lo[s];
+            step[s] = max(1, (span + 63) >> 6);
+            const int idx = lo[s] + lane * step[s];
+            val[s] = (!done[s] && idx < hi[s]) ? list[idx] : 0x7fffffff;
+        }
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            if (done[s]) continue;
+            const uint64_t b = ballot(val[s] >= key[s]); // monotone in the lane index
+            const int first = b ? __builtin_ctzll(b) : 64; // probes before `first` are < key
+            // the answer lies in (lo + (first-1)*step, lo + first*step], capped by hi
+            const int nlo = first == 0 ? lo[s] : min(hi[s], lo[s] + (first - 1) * step[s] + 1);
+            const int nhi = first == 64 ? hi[s] : min(hi[s], lo[s] + first * step[s]);
+            lo[s] = nlo;
+            hi[s] = nhi;
+            if (step[s] == 1 || hi[s] <= lo[s]) {
+                lo[s] = hi[s] = (step[s] == 1) ? nhi : max(nlo, nhi);
+                done[s] = true;
+            }
+        }
     }
-    return lo;
+    return Bounds2{lo[0], lo[1]};
 }
 
 // One wavefront = one clause of class c.  The examples whose gate can open for this
@@ -725,8 +743,8 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     // the candidate list of this class, restricted to the examples of this launch
     const int32_t *list = cand + (int64_t)c * a.qp;
     const int n_list = ncand[c];
-    const int k_lo = wave_lower_bound(list, n_list, i_begin * 2, lane);
-    const int k_hi = wave_lower_bound(list, n_list, i_end * 2, lane);
+    const Bounds2 kb = wave_lower_bound2(list, n_list, i_begin * 2, i_end * 2, lane);
+    const int k_lo = kb.lo, k_hi = kb.hi;
     const int32_t *tally_c = a.tally + (int64_t)c * a.qp;
 
     // state of the block of 64 examples that is currently open (cb < 0: none)
