@@ -470,25 +470,42 @@ __global__ __launch_bounds__(64) void k_eval_stream(const uint32_t *__restrict__
 #pragma unroll
             for (int fb = 0; fb < 8; ++fb) {
                 const int ne = min(32, nb - fb * 32);
-                for (int e = 0; e < ne; ++e) {
-                    const uint32_t *xr = X + (b0 + fb * 32 + e) * a.Wf + w0; // wave-uniform
-                    uint32_t viol = 0;
-                    if (full) {
+                if (ne <= 0) continue;
+                if (full) {
+                    // two row buffers in turn: the next example's words are requested before the
+                    // current ones are consumed (scalar-load latency hides behind the bit operations)
+                    auto load = [&](uint32_t (&x)[CH], int e) {
+                        const int ee = min(e, ne - 1); // a surplus request re-reads the last row
+                        const uint32_t *xr = X + (b0 + fb * 32 + ee) * a.Wf + w0; // wave-uniform
 #pragma unroll
-                        for (int w = 0; w < CH; ++w) {
-                            const uint32_t x = xr[w];
-                            viol |= bitselect(x, mn[w], mp[w]); // negated literal violated where x = 1, plain where x = 0
-                        }
-                    } else {
+                        for (int w = 0; w < CH; ++w) x[w] = xr[w];
+                    };
+                    auto consume = [&](const uint32_t (&x)[CH], int e) {
+                        uint32_t viol = 0;
 #pragma unroll
-                        for (int w = 0; w < CH; ++w) {
-                            if (w0 + w < a.Wf) {
-                                const uint32_t x = xr[w];
-                                viol |= bitselect(x, mn[w], mp[w]); // negated literal violated where x = 1, plain where x = 0
-                            }
-                        }
+                        for (int w = 0; w < CH; ++w) viol |= bitselect(x[w], mn[w], mp[w]); // negated literal violated where x = 1, plain where x = 0
+                        flags[fb] |= (viol != 0u) ? (1u << e) : 0u;
+                    };
+                    uint32_t xa[CH], xb[CH];
+                    load(xa, 0);
+                    int e = 0;
+                    for (; e + 1 < ne; e += 2) {
+                        load(xb, e + 1);
+                        consume(xa, e);
+                        load(xa, e + 2);
+                        consume(xb, e + 1);
                     }
-                    flags[fb] |= (viol != 0u) ? (1u << e) : 0u;
+                    if (e < ne) consume(xa, e);
+                } else {
+                    for (int e = 0; e < ne; ++e) {
+                        const uint32_t *xr = X + (b0 + fb * 32 + e) * a.Wf + w0; // wave-uniform
+                        uint32_t viol = 0;
+#pragma unroll
+                        for (int w = 0; w < CH; ++w) {
+                            if (w0 + w < a.Wf) viol |= bitselect(xr[w], mn[w], mp[w]);
+                        }
+                        flags[fb] |= (viol != 0u) ? (1u << e) : 0u;
+                    }
                 }
             }
         }
