@@ -74,7 +74,7 @@ int tm_state_bytes(const tm_config *cfg, size_t *out);
 
 /* Size in bytes of the training workspace for q examples (voting tallies,
  * previous-output bits - one bit per example per clause -, transposed copy of
- * X, per-example negative class, per-class candidate lists, per-clause
+ * X, per-example negative class, per-class gate lists, per-clause
  * bookkeeping, counters).  Host-only computation. */
 int tm_train_ws_bytes(const tm_config *cfg, int64_t q, size_t *out);
 
@@ -100,8 +100,11 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
  * clause visits examples 0..q-1 in order, gates on the (possibly outdated)
  * tally, applies Type I or Type II feedback, re-evaluates, and refreshes tally
  * and previous-output bit.  Multi-class: class y_i is trained towards 1 and
- * one other class, drawn per (epoch, example), towards 0.  Advances the
- * handle's epoch counter (part of the random counter) by one. */
+ * one other class, drawn per (epoch, example), towards 0.  The pass is cut into
+ * launches (tm_train_chunk); an example whose error e is 0 under the tally as
+ * it stands at the start of its launch (gate probability 0) is not visited for
+ * feedback in that launch, all others are gated on the tally read at the visit.
+ * Advances the handle's epoch counter (part of the random counter) by one. */
 int tm_fit_epoch(tm_handle *h, void *stream);
 
 /* Eq. 3 per class, clamped to [-T, T]: sums device int32 [q][m].
@@ -162,7 +165,8 @@ int tm_get_epoch(tm_handle *h, uint32_t *epoch);
  * candidates), [5] Type II feedbacks given to a clause with output 1,
  * [6] blocks of 64 examples that a clause had to evaluate (blocks whose stored
  * outputs are known to be current and in which no gate fires are skipped),
- * [7] gate candidates whose error e was positive (a random draw was needed).
+ * [7] gate candidates whose error e was positive both at the start of the
+ * launch and at the visit (a random draw was needed).
  * Synchronises the stream. */
 int tm_read_counters(tm_handle *h, uint64_t *out, void *stream);
 

@@ -8,7 +8,7 @@
 //                  ostar  uint32 [C][Qw]    previous clause outputs, 1 bit per (clause, example), Qw = qp/32
 //                  XT     uint32 [Wf][qp]   transposed features (word-major) for lane = example evaluation
 //                  negcls int32  [qp]       class trained towards 0 for each example, this epoch
-//                  cand   int32  [m][qp]    per class: ascending list of (example << 1 | target) that may get feedback
+//                  gate   int32  [m][qp]    per class and launch: ascending list of (example << 1 | target) whose gate can open
 //                  fresh  int32  [C][4]     per clause: example ranges whose stored outputs may be outdated
 //                  order  int32  [C]        launch order of the clauses (outdated ones first)
 //                  counters uint64 [64][8] interleaved event counters, flag int32
@@ -19,7 +19,7 @@
 //            scalar loads, one bit-select per feature word and pair; clause votes are
 //            summed with wave ballot + popcount (inference, tally pre-calculation).
 //   k_train  one wavefront = one clause (Algorithm 1 gives every clause its own
-//            thread); lane = candidate example for the gates, lane = literal word for
+//            thread); lane = gate-list entry for the gates, lane = literal word for
 //            feedback, lane = example for the evaluation of a block of 64 examples.
 #include <hip/hip_runtime.h>
 #include <algorithm>
@@ -151,47 +151,6 @@ __global__ void k_negcls(Dims d, const int32_t *y, int32_t *negcls, int64_t q, i
     negcls[i] = r;
 }
 
-// Candidate list of class c = blockIdx.x: the examples, in ascending order, for which
-// the clauses of c may receive feedback this epoch, packed as (example << 1 | target):
-// target 1 where y_i = c, target 0 where c is the drawn negative class.  One workgroup
-// per class scans the examples 1024 at a time and compacts the matches with ballot
-// prefixes.  ncand[c] receives the length.
-__global__ __launch_bounds__(1024) void k_cand_lists(const int32_t *__restrict__ y, const int32_t *__restrict__ negcls,
-                                                     int32_t *__restrict__ cand, int32_t *__restrict__ ncand, int64_t q,
-                                                     int64_t qp)
-{
-    __shared__ int wave_cnt[16];
-    __shared__ int base_sh;
-    const int c = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int32_t *list = cand + (int64_t)c * qp;
-    if (tid == 0) base_sh = 0;
-    __syncthreads();
-    for (int64_t i0 = 0; i0 < q; i0 += 1024) {
-        const int64_t i = i0 + tid;
-        bool match = false;
-        int target = 0;
-        if (i < q) {
-            target = (y[i] == c) ? 1 : 0;
-            match = target || negcls[i] == c;
-        }
-        const uint64_t b = ballot(match);
-        const int pre = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, 0u));
-        if (lane == 0) wave_cnt[wave] = __builtin_popcountll(b);
-        __syncthreads();
-        int off = base_sh, total = 0;
-        for (int w = 0; w < 16; ++w) {
-            if (w < wave) off += wave_cnt[w];
-            total += wave_cnt[w];
-        }
-        if (match) list[off + pre] = (int32_t)((i << 1) | target);
-        __syncthreads();
-        if (tid == 0) base_sh += total;
-        __syncthreads();
-    }
-    if (tid == 0) ncand[c] = base_sh;
-}
-
 // sums[i][c] = clamp(sums[i][c], -T, T)
 __global__ void k_clamp(int32_t *sums, int64_t n, int T)
 {
@@ -243,41 +202,85 @@ __global__ void k_fresh_set(int32_t *fresh, int C, int qp, int all_stale)
     if (g < C) *reinterpret_cast<int4 *>(fresh + (int64_t)g * 4) = make_int4(0, all_stale ? qp : 0, qp, 0);
 }
 
-// Launch order of the clauses for the training kernel: those that start a launch with
-// outdated stored outputs sweep every block of the range (a long dependent chain) and go
-// first, so that they do not end up alone at the tail of the launch; the others follow in
-// index order.  One workgroup, stable partition by ballot prefixes.
-__global__ __launch_bounds__(1024) void k_order(const int32_t *__restrict__ fresh, int32_t *__restrict__ order, int C,
-                                                int i_begin, int i_end)
+// What a launch of the training kernel over the examples [i_begin, i_end) needs, one
+// workgroup of 1024 per task, each a stable compaction by ballot prefixes.
+//
+// blockIdx.x = c < m: gate list of class c = the examples of the range, ascending, whose
+// gate can open for a clause of c, packed as (example << 1 | target): target 1 where
+// y_i = c, target 0 where c is the class drawn against y_i, and error e > 0 under the
+// tally as it stands now (or under the snapshot vhat).  The examples with e = 0 are left
+// out: their gate probability e/2T is 0, so a clause that read this tally would not act,
+// and reading a tally that is one launch old is within the method's premise of outdated
+// tallies (Section 3.1).  The clause re-reads the tally of a listed example when it gets
+// there.  ngate[c] receives the length; counter 4 the number of (clause, example) pairs of
+// the range whose class is trained for the example.
+//
+// blockIdx.x = m: launch order of the clauses.  Those that start the launch with outdated
+// stored outputs sweep every block of the range and go first, so that they do not end up
+// alone at the tail of the launch; the others follow in index order.
+struct PrepArgs {
+    const int32_t *y, *negcls, *tally, *vhat, *fresh;
+    int32_t *gate, *ngate, *order;
+    unsigned long long *counters;
+    int i_begin, i_end, qp, m, n, C, T;
+};
+
+__global__ __launch_bounds__(1024) void k_launch_prep(const PrepArgs a)
 {
     __shared__ int wave_cnt[16];
-    __shared__ int base_sh[2];
+    __shared__ int base_sh, seen_sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int pass = 0; pass < 2; ++pass) { // pass 0 places the clauses with outdated outputs, pass 1 the rest
-        if (tid == 0 && pass == 0) base_sh[0] = 0;
-        __syncthreads();
-        for (int g0 = 0; g0 < C; g0 += 1024) {
-            const int g = g0 + tid;
-            bool take = false;
-            if (g < C) {
-                const int4 f = *reinterpret_cast<const int4 *>(fresh + (int64_t)g * 4);
-                const bool stale = (f.x < f.y && f.x < i_end && f.y > i_begin) || (f.z < i_end);
-                take = (pass == 0) ? stale : !stale;
+    const bool ordering = (int)blockIdx.x == a.m;
+    const int c = blockIdx.x;
+    int32_t *out = ordering ? a.order : a.gate + (int64_t)c * a.qp;
+    const int passes = ordering ? 2 : 1; // ordering: pass 0 places the outdated clauses, pass 1 the rest
+    const int lo = ordering ? 0 : a.i_begin, hi = ordering ? a.C : a.i_end;
+    if (tid == 0) base_sh = seen_sh = 0;
+    __syncthreads();
+    for (int pass = 0; pass < passes; ++pass) {
+        for (int t0 = lo; t0 < hi; t0 += 1024) {
+            const int t = t0 + tid;
+            bool take = false, match = false;
+            int value = 0;
+            if (t < hi) {
+                if (ordering) {
+                    const int4 f = *reinterpret_cast<const int4 *>(a.fresh + (int64_t)t * 4);
+                    const bool stale = (f.x < f.y && f.x < a.i_end && f.y > a.i_begin) || (f.z < a.i_end);
+                    take = (pass == 0) ? stale : !stale;
+                    value = t;
+                } else {
+                    const int target = (a.y[t] == c) ? 1 : 0;
+                    match = target || a.negcls[t] == c;
+                    if (match) {
+                        const int v = a.vhat ? a.vhat[(int64_t)t * a.m + c] : a.tally[(int64_t)c * a.qp + t];
+                        const int vc = min(max(v, -a.T), a.T);
+                        take = (target ? a.T - vc : a.T + vc) > 0; // Algorithm 1: error of the recorded vote sum
+                    }
+                    value = (t << 1) | target;
+                }
             }
             const uint64_t b = ballot(take);
+            const uint64_t bm = ballot(match);
             const int pre = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, 0u));
-            if (lane == 0) wave_cnt[wave] = __builtin_popcountll(b);
+            if (lane == 0) {
+                wave_cnt[wave] = __builtin_popcountll(b);
+                if (bm) atomicAdd(&seen_sh, __builtin_popcountll(bm));
+            }
             __syncthreads();
-            int off = base_sh[0], total = 0;
+            int off = base_sh, total = 0;
             for (int w = 0; w < 16; ++w) {
                 if (w < wave) off += wave_cnt[w];
                 total += wave_cnt[w];
             }
-            if (take) order[off + pre] = g;
+            if (take) out[off + pre] = value;
             __syncthreads();
-            if (tid == 0) base_sh[0] += total;
+            if (tid == 0) base_sh += total;
             __syncthreads();
         }
+    }
+    if (tid == 0 && !ordering) {
+        a.ngate[c] = base_sh;
+        if (seen_sh) atomicAdd(&a.counters[4], (unsigned long long)seen_sh * (unsigned long long)a.n);
     }
 }
 
@@ -621,9 +624,9 @@ __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lm
 // Clause outputs for 64 examples, lane = example: bit l of the result is
 // C(X_{i0+l}).  xt_block points at XT[0][i0].  An entry costs one coalesced
 // 256-byte load, an LDS broadcast of its masks and two bit operations.
-// Entries are taken eight at a time (eight loads in flight; more in flight
-// costs registers, hence occupancy, and measured slower); a dense (young)
-// clause violates all 64 examples within the first group and the loop stops.
+// Entries are taken EVAL_GROUP at a time (that many loads in flight; 8 and 24
+// measured slower); a dense (young) clause violates all 64 examples within the
+// first group and the loop stops.
 constexpr int EVAL_GROUP = 16;
 
 __device__ __forceinline__ uint64_t eval64(const uint32_t *eoff, const uint2 *emask, int nent,
@@ -653,60 +656,62 @@ __device__ __forceinline__ uint64_t eval64(const uint32_t *eoff, const uint2 *em
     return ballot(viol == 0u);
 }
 
+// The same for SWEEP_BLOCKS consecutive blocks at once, SWEEP_GROUP entries at a time:
+// block kk lies 256 bytes after block kk-1 in every row of XT, so one address serves all
+// blocks of an entry and its masks are read once.  No early exit: it would need every
+// example of every block violated, which trained (sparse) clauses hardly ever reach.
+constexpr int SWEEP_BLOCKS = 4;
+constexpr int SWEEP_GROUP = 8;
+
+__device__ __forceinline__ void eval_blocks(const uint32_t *eoff, const uint2 *emask, int nent,
+                                            const uint32_t *__restrict__ xt_block, int lane,
+                                            uint64_t (&out)[SWEEP_BLOCKS])
+{
+    uint32_t viol[SWEEP_BLOCKS];
+#pragma unroll
+    for (int kk = 0; kk < SWEEP_BLOCKS; ++kk) viol[kk] = 0u;
+    const char *base = reinterpret_cast<const char *>(xt_block);
+    const uint32_t lane4 = (uint32_t)lane * 4u;
+    int k = 0;
+    do { // an empty clause has one group of padding entries
+        uint32_t off[SWEEP_GROUP], x[SWEEP_BLOCKS][SWEEP_GROUP];
+#pragma unroll
+        for (int j = 0; j < SWEEP_GROUP; j += 4) {
+            const uint4 o = *reinterpret_cast<const uint4 *>(eoff + k + j);
+            off[j] = o.x + lane4; off[j + 1] = o.y + lane4; off[j + 2] = o.z + lane4; off[j + 3] = o.w + lane4;
+        }
+#pragma unroll
+        for (int j = 0; j < SWEEP_GROUP; ++j)
+#pragma unroll
+            for (int kk = 0; kk < SWEEP_BLOCKS; ++kk)
+                x[kk][j] = *reinterpret_cast<const uint32_t *>(base + off[j] + 256 * kk);
+        const uint4 *mq = reinterpret_cast<const uint4 *>(emask + k);
+#pragma unroll
+        for (int j = 0; j < SWEEP_GROUP / 2; ++j) {
+            const uint4 m = mq[j];
+#pragma unroll
+            for (int kk = 0; kk < SWEEP_BLOCKS; ++kk)
+                viol[kk] |= bitselect(x[kk][2 * j], m.y, m.x) | bitselect(x[kk][2 * j + 1], m.w, m.z);
+        }
+        k += SWEEP_GROUP;
+    } while (k < nent);
+#pragma unroll
+    for (int kk = 0; kk < SWEEP_BLOCKS; ++kk) out[kk] = ballot(viol[kk] == 0u);
+}
+
 constexpr int COUNTER_SETS = 64; // interleaved copies of the 8 event counters
 constexpr int TRAIN_WAVES = 4; // clauses (wavefronts) per workgroup of the training kernel
 
-// First positions k1, k2 in the ascending list[0..n) with list[k] >= key1 resp. key2
-// (key1 <= key2), found by the whole wavefront: 64 probes per round and key, the probes of
-// both searches in flight together; three rounds for a quarter million entries.
-struct Bounds2 {
-    int lo, hi;
-};
-
-__device__ __forceinline__ Bounds2 wave_lower_bound2(const int32_t *__restrict__ list, int n, int key1, int key2,
-                                                     int lane)
-{
-    int lo[2] = {0, 0}, hi[2] = {n, n}; // answers lie in [lo, hi]
-    const int key[2] = {key1, key2};
-    bool done[2] = {n == 0, n == 0};
-    while (!(done[0] && done[1])) {
-        int step[2], val[2];
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const int span = hi[s] - lo[s];
-            step[s] = max(1, (span + 63) >> 6);
-            const int idx = lo[s] + lane * step[s];
-            val[s] = (!done[s] && idx < hi[s]) ? list[idx] : 0x7fffffff;
-        }
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            if (done[s]) continue;
-            const uint64_t b = ballot(val[s] >= key[s]); // monotone in the lane index
-            const int first = b ? __builtin_ctzll(b) : 64; // probes before `first` are < key
-            // the answer lies in (lo + (first-1)*step, lo + first*step], capped by hi
-            const int nlo = first == 0 ? lo[s] : min(hi[s], lo[s] + (first - 1) * step[s] + 1);
-            const int nhi = first == 64 ? hi[s] : min(hi[s], lo[s] + first * step[s]);
-            lo[s] = nlo;
-            hi[s] = nhi;
-            if (step[s] == 1 || hi[s] <= lo[s]) {
-                lo[s] = hi[s] = (step[s] == 1) ? nhi : max(nlo, nhi);
-                done[s] = true;
-            }
-        }
-    }
-    return Bounds2{lo[0], lo[1]};
-}
-
 // One wavefront = one clause of class c.  The examples whose gate can open for this
-// clause are those of the candidate list of c (label c: trained towards 1; drawn
-// negative class c: trained towards 0); their gates are drawn 64 at a time, lane =
-// candidate.  Blocks of 64 consecutive examples are evaluated (lane = example) only
+// clause are those of the gate list of c for this launch (label c: trained towards 1;
+// drawn negative class c: trained towards 0); their gates are drawn 64 at a time, lane =
+// list entry.  Blocks of 64 consecutive examples are evaluated (lane = example) only
 // when a gate in them fired or their stored outputs may be outdated; all other blocks
 // of the pass are never touched.
 template <int WPL, bool FULL>
 __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
-                                                            const int32_t *__restrict__ cand,
-                                                            const int32_t *__restrict__ ncand, const TrainArgs a)
+                                                            const int32_t *__restrict__ gate,
+                                                            const int32_t *__restrict__ ngate, const TrainArgs a)
 {
     extern __shared__ uint32_t lds[];
     const Dims &d = a.d;
@@ -748,7 +753,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     const uint32_t ge_init = d.thr >= 65536u ? 0u : ~0u;
 
     // per-wavefront event counts of one launch fit 32 bits (at most 2^30 examples per launch)
-    uint32_t n_fired = 0, n_type1 = 0, n_changes = 0, n_cand = 0, n_type2 = 0, n_eval = 0, n_draw = 0;
+    uint32_t n_fired = 0, n_type1 = 0, n_changes = 0, n_type2 = 0, n_eval = 0, n_draw = 0;
 
     // Which stored previous outputs o* can differ from the clause's current output: only
     // those not re-evaluated since the include mask last changed.  Kept per clause as two
@@ -768,11 +773,9 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
         return r;
     };
 
-    // the candidate list of this class, restricted to the examples of this launch
-    const int32_t *list = cand + (int64_t)c * a.qp;
-    const int n_list = ncand[c];
-    const Bounds2 kb = wave_lower_bound2(list, n_list, i_begin * 2, i_end * 2, lane);
-    const int k_lo = kb.lo, k_hi = kb.hi;
+    // the gate list of this class for this launch
+    const int32_t *list = gate + (int64_t)c * a.qp;
+    const int k_lo = 0, k_hi = ngate[c];
     const int32_t *tally_c = a.tally + (int64_t)c * a.qp;
 
     // state of the block of 64 examples that is currently open (cb < 0: none)
@@ -780,6 +783,83 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     int cb = -1, next_block = i_begin >> 6;
     uint64_t obits = 0, ost = 0, rmask = 0;
     bool mask_changed = false;
+
+    auto range_mask = [&](int b0) { return ballot(b0 + lane >= i_begin && b0 + lane < i_end); };
+    auto pack64 = [&](uint32_t lo, uint32_t hi) {
+        return (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)lo) |
+               ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)hi) << 32);
+    };
+    // Refresh of tally and previous-output bits (last lines of Algorithm 1) for the 64
+    // examples of block b at once: ob = outputs with the current masks, os = stored ones,
+    // rm = examples of the block that belong to this launch.
+    auto refresh_block = [&](int b, uint64_t ob, uint64_t os, uint64_t rm) {
+        const int b0 = b << 6;
+        const uint64_t diff = (ob ^ os) & rm;
+        if (diff) {
+            if ((diff >> lane) & 1ull) {
+                const int delta = ((ob >> lane) & 1ull) ? sign : -sign;
+                atomicAdd(&a.tally[(int64_t)c * a.qp + b0 + lane], delta);
+            }
+            const uint64_t nw = os ^ diff;
+            if (lane == 0) {
+                uint32_t *op = a.ostar + (int64_t)g * a.Qw + (b0 >> 5);
+                op[0] = (uint32_t)nw;
+                op[1] = (uint32_t)(nw >> 32);
+            }
+            n_changes += __builtin_popcountll(diff);
+        }
+    };
+    // ... followed by the bookkeeping of which stored outputs may be outdated
+    auto close_block = [&](int b, uint64_t ob, uint64_t os, uint64_t rm, bool changed) {
+        refresh_block(b, ob, os, rm);
+        const int b0 = b << 6, b1 = b0 + 64;
+        const bool whole = b0 >= i_begin && (b1 <= i_end || i_end == q);
+        if (whole) { // this block is up to date again
+            if (b0 <= plo) plo = max(plo, b1);
+            if (b0 <= slo) slo = max(slo, b1);
+        }
+        if (changed) { // everything not visited after the change is outdated now
+            plo = 0;
+            phi = b1;
+            slo = b1;
+        }
+    };
+    // Refresh of every block in [from, to) that may hold outdated outputs; no gate fired in
+    // them, so the masks stay as they are.  After a mask change these are all the blocks up
+    // to the next fired gate, and their evaluation is most of what a trained machine's
+    // epoch costs, so runs of SWEEP_BLOCKS whole blocks are taken together: the entry
+    // offsets and masks are read from LDS once for all of them.
+    auto all_stale = [&](int b, int e) { // every block of [b, e) may hold outdated outputs
+        return b >= (slo >> 6) || (plo < phi && b >= (plo >> 6) && e <= ((phi + 63) >> 6));
+    };
+    auto sweep = [&](int from, int to) {
+        int b = next_stale(from);
+        while (b < to) {
+            const uint32_t *op = a.ostar + (int64_t)g * a.Qw + (b << 1);
+            if (WPL <= 8 && b + SWEEP_BLOCKS <= to && (b << 6) >= i_begin && ((b + SWEEP_BLOCKS) << 6) <= i_end &&
+                all_stale(b, b + SWEEP_BLOCKS)) {
+                uint2 os[SWEEP_BLOCKS];
+#pragma unroll
+                for (int kk = 0; kk < SWEEP_BLOCKS; ++kk) os[kk] = *reinterpret_cast<const uint2 *>(op + 2 * kk);
+                uint64_t ob[SWEEP_BLOCKS];
+                eval_blocks(eoff, emask, nent, XT + (b << 6), lane, ob);
+#pragma unroll
+                for (int kk = 0; kk < SWEEP_BLOCKS; ++kk)
+                    refresh_block(b + kk, ob[kk], pack64(os[kk].x, os[kk].y), ~0ull);
+                const int b0 = b << 6, b1 = (b + SWEEP_BLOCKS) << 6; // these blocks are up to date again
+                if (b0 <= plo) plo = max(plo, b1);
+                if (b0 <= slo) slo = max(slo, b1);
+                n_eval += SWEEP_BLOCKS;
+                b = next_stale(b + SWEEP_BLOCKS);
+            } else {
+                const uint32_t o0 = op[0], o1 = op[1];
+                const uint64_t ob = eval64(eoff, emask, nent, XT + (b << 6), lane);
+                close_block(b, ob, pack64(o0, o1), range_mask(b << 6), false);
+                ++n_eval;
+                b = next_stale(b + 1); // closing b does not change which later blocks are outdated
+            }
+        }
+    };
 
     // Candidate data are fetched ahead: entry words two candidate blocks ahead, tallies (which
     // need the entry's example index) one block ahead.  Reading a tally early is within the
@@ -822,7 +902,6 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
             }
             fmask = ballot(fire);
             tmask = ballot(target);
-            n_cand += __builtin_popcountll(ballot(valid));
             n_draw += __builtin_popcountll(ballot(open));
             n_fired += __builtin_popcountll(fmask);
         }
@@ -861,50 +940,27 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
             }
 
             // bring block B up: close the open block, refresh the outdated blocks in between
-            while (cb != B) {
+            if (cb != B) {
                 if (cb >= 0) {
-                    // refresh of tally and previous-output bits (last lines of Algorithm 1), 64 examples at once
-                    const int b0 = cb << 6, b1 = b0 + 64;
-                    const uint64_t diff = (obits ^ ost) & rmask;
-                    if (diff) {
-                        if ((diff >> lane) & 1ull) {
-                            const int delta = ((obits >> lane) & 1ull) ? sign : -sign;
-                            atomicAdd(&a.tally[(int64_t)c * a.qp + b0 + lane], delta);
-                        }
-                        const uint64_t nw = ost ^ diff;
-                        if (lane == 0) {
-                            uint32_t *op = a.ostar + (int64_t)g * a.Qw + (b0 >> 5);
-                            op[0] = (uint32_t)nw;
-                            op[1] = (uint32_t)(nw >> 32);
-                        }
-                        n_changes += __builtin_popcountll(diff);
-                    }
-                    const bool whole = b0 >= i_begin && (b1 <= i_end || i_end == q);
-                    if (whole) { // this block is up to date again
-                        if (b0 <= plo) plo = max(plo, b1);
-                        if (b0 <= slo) slo = max(slo, b1);
-                    }
-                    if (mask_changed) { // everything not visited after the change is outdated now
-                        plo = 0;
-                        phi = b1;
-                        slo = b1;
-                    }
+                    close_block(cb, obits, ost, rmask, mask_changed);
                     next_block = cb + 1;
                     cb = -1;
                 }
-                const int nb = min(next_stale(next_block), B);
-                if (nb >= end_block) break; // only when B is the end of the range
-                // open block nb: previous outputs, range mask, evaluation with the current masks
-                cb = nb;
-                const int b0 = nb << 6;
-                const uint32_t *op = a.ostar + (int64_t)g * a.Qw + (b0 >> 5);
-                const uint32_t o0 = op[0], o1 = op[1];
-                rmask = ballot(b0 + lane >= i_begin && b0 + lane < i_end);
-                obits = eval64(eoff, emask, nent, XT + b0, lane);
-                ost = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)o0) |
-                      ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)o1) << 32);
-                mask_changed = false;
-                ++n_eval;
+                const int lim = min(B, end_block);
+                sweep(next_block, lim);
+                next_block = max(next_block, lim);
+                if (B < end_block) {
+                    // open block B: previous outputs, range mask, evaluation with the current masks
+                    cb = B;
+                    const int b0 = B << 6;
+                    const uint32_t *op = a.ostar + (int64_t)g * a.Qw + (b0 >> 5);
+                    const uint32_t o0 = op[0], o1 = op[1];
+                    rmask = range_mask(b0);
+                    obits = eval64(eoff, emask, nent, XT + b0, lane);
+                    ost = pack64(o0, o1);
+                    mask_changed = false;
+                    ++n_eval;
+                }
             }
             if (!have) break; // the range is finished
 
@@ -1016,7 +1072,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     // same time on one address serialise in the L2 atomic unit (measured: ~1.7 ms per launch)
     if (lane >= 1 && lane < 8) {
         const uint32_t v = lane == 1 ? n_fired : lane == 2 ? n_type1 : lane == 3 ? n_changes
-                         : lane == 4 ? n_cand : lane == 5 ? n_type2 : lane == 6 ? n_eval : n_draw;
+                         : lane == 4 ? 0u : lane == 5 ? n_type2 : lane == 6 ? n_eval : n_draw;
         if (v) atomicAdd(&a.counters[(g & (COUNTER_SETS - 1)) * 8 + lane], (unsigned long long)v);
     }
 }
@@ -1044,8 +1100,8 @@ struct tm_handle {
     uint32_t *ostar;
     uint32_t *XT;
     int32_t *negcls;
-    int32_t *cand;  // [m][qp] candidate lists of the current epoch
-    int32_t *ncand; // [m]
+    int32_t *gate;  // [m][qp] gate lists of the current launch
+    int32_t *ngate; // [m]
     int32_t *fresh;
     int32_t *order; // [C] launch order of the clauses
     unsigned long long *counters;
@@ -1097,7 +1153,7 @@ Dims make_dims(const tm_config *cfg)
 }
 
 struct WsLayout {
-    size_t tally, ostar, xt, negcls, cand, ncand, fresh, order, counters, flag, total;
+    size_t tally, ostar, xt, negcls, gate, ngate, fresh, order, counters, flag, total;
 };
 
 WsLayout ws_layout(const Dims &d, int64_t q)
@@ -1110,8 +1166,8 @@ WsLayout ws_layout(const Dims &d, int64_t q)
     L.ostar = off; off += align256((size_t)d.C * Qw * 4);
     L.xt = off; off += align256((size_t)d.Wf * qp * 4);
     L.negcls = off; off += align256((size_t)qp * 4);
-    L.cand = off; off += align256((size_t)d.m * qp * 4);
-    L.ncand = off; off += align256((size_t)d.m * 4);
+    L.gate = off; off += align256((size_t)d.m * qp * 4);
+    L.ngate = off; off += align256((size_t)d.m * 4);
     L.fresh = off; off += align256((size_t)d.C * 16);
     L.order = off; off += align256((size_t)d.C * 4);
     L.counters = off; off += align256((size_t)COUNTER_SETS * 8 * 8);
@@ -1202,7 +1258,7 @@ int launch_eval(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *bits, int6
 
 struct TrainPtrs {
     const uint32_t *X, *XT;
-    const int32_t *cand, *ncand;
+    const int32_t *gate, *ngate;
 };
 
 template <int WPL>
@@ -1210,8 +1266,8 @@ void launch_train_t(const TrainPtrs &p, const TrainArgs &a, bool full, hipStream
 {
     const size_t lds = (size_t)a.lds_wave_words * TRAIN_WAVES * 4;
     const dim3 grid((unsigned)((a.d.C + TRAIN_WAVES - 1) / TRAIN_WAVES)), block(64 * TRAIN_WAVES);
-    if (full) hipLaunchKernelGGL((k_train<WPL, true>), grid, block, lds, st, p.X, p.XT, p.cand, p.ncand, a);
-    else hipLaunchKernelGGL((k_train<WPL, false>), grid, block, lds, st, p.X, p.XT, p.cand, p.ncand, a);
+    if (full) hipLaunchKernelGGL((k_train<WPL, true>), grid, block, lds, st, p.X, p.XT, p.gate, p.ngate, a);
+    else hipLaunchKernelGGL((k_train<WPL, false>), grid, block, lds, st, p.X, p.XT, p.gate, p.ngate, a);
 }
 
 // Examples per launch of the training kernel.  An epoch is cut into ranges
@@ -1231,7 +1287,7 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
 {
     const Dims &d = h->d;
     TrainArgs a;
-    const TrainPtrs p{h->X, h->XT, h->cand, h->ncand};
+    const TrainPtrs p{h->X, h->XT, h->gate, h->ngate};
     a.d = d; a.sat = h->sat; a.planes = h->planes; a.inc = h->inc; a.tally = h->tally;
     a.vhat = vhat; a.ostar = h->ostar; a.fresh = h->fresh; a.order = h->order; a.counters = h->counters;
     a.q = (int32_t)h->q; a.qp = (int32_t)h->qp; a.Qw = (int32_t)h->Qw; a.epoch = h->epoch;
@@ -1245,7 +1301,11 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     for (int64_t b = (i_begin / chunk) * chunk; b < i_end; b += chunk) {
         a.i_begin = (int32_t)std::max(b, i_begin);
         a.i_end = (int32_t)std::min(b + chunk, i_end);
-        hipLaunchKernelGGL(k_order, dim3(1), dim3(1024), 0, st, h->fresh, h->order, d.C, (int)a.i_begin, (int)a.i_end);
+        PrepArgs pa;
+        pa.y = h->y; pa.negcls = h->negcls; pa.tally = h->tally; pa.vhat = vhat; pa.fresh = h->fresh;
+        pa.gate = h->gate; pa.ngate = h->ngate; pa.order = h->order; pa.counters = h->counters;
+        pa.i_begin = a.i_begin; pa.i_end = a.i_end; pa.qp = a.qp; pa.m = d.m; pa.n = d.n; pa.C = d.C; pa.T = d.T;
+        hipLaunchKernelGGL(k_launch_prep, dim3(d.m + 1), dim3(1024), 0, st, pa);
         TM_HIP(h, hipGetLastError());
         if (wpl <= 1) launch_train_t<1>(p, a, full, st);
         else if (wpl <= 2) launch_train_t<2>(p, a, full, st);
@@ -1267,9 +1327,6 @@ int run_negcls(tm_handle *h, hipStream_t st)
 {
     hipLaunchKernelGGL(k_negcls, dim3(blocks_for(h->qp, 256)), dim3(256), 0, st, h->d, h->y, h->negcls, h->q,
                        h->qp, h->epoch);
-    TM_HIP(h, hipGetLastError());
-    hipLaunchKernelGGL(k_cand_lists, dim3(h->d.m), dim3(1024), 0, st, h->y, h->negcls, h->cand, h->ncand, h->q,
-                       h->qp);
     TM_HIP(h, hipGetLastError());
     return TM_OK;
 }
@@ -1362,7 +1419,7 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
     hipStream_t st = (hipStream_t)stream;
     TM_HIP(h, hipSetDevice(h->cfg.device));
     const Dims &d = h->d;
-    // the evaluation loop addresses XT rows with 32-bit byte offsets, and candidate-list
+    // the evaluation loop addresses XT rows with 32-bit byte offsets, and gate-list
     // entries pack the example index into 31 bits
     if ((int64_t)d.Wf * ((q + 63) & ~(int64_t)63) * 4 >= ((int64_t)1 << 32)) return TM_ELIMIT;
     if (q > ((int64_t)1 << 30) - 64) return TM_ELIMIT;
@@ -1376,8 +1433,8 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
     h->ostar = (uint32_t *)(base + L.ostar);
     h->XT = (uint32_t *)(base + L.xt);
     h->negcls = (int32_t *)(base + L.negcls);
-    h->cand = (int32_t *)(base + L.cand);
-    h->ncand = (int32_t *)(base + L.ncand);
+    h->gate = (int32_t *)(base + L.gate);
+    h->ngate = (int32_t *)(base + L.ngate);
     h->fresh = (int32_t *)(base + L.fresh);
     h->order = (int32_t *)(base + L.order);
     h->counters = (unsigned long long *)(base + L.counters);
