@@ -203,7 +203,7 @@ __global__ void k_fresh_set(int32_t *fresh, int C, int qp, int all_stale)
 }
 
 // What a launch of the training kernel over the examples [i_begin, i_end) needs, one
-// workgroup of 1024 per task, each a stable compaction by ballot prefixes.
+// workgroup of 1024 per task, each a compaction by ballot prefixes.
 //
 // blockIdx.x = c < m: gate list of class c = the examples of the range, ascending, whose
 // gate can open for a clause of c, packed as (example << 1 | target): target 1 where
@@ -216,8 +216,8 @@ __global__ void k_fresh_set(int32_t *fresh, int C, int qp, int all_stale)
 // the range whose class is trained for the example.
 //
 // blockIdx.x = m: launch order of the clauses.  Those that start the launch with outdated
-// stored outputs sweep every block of the range and go first, so that they do not end up
-// alone at the tail of the launch; the others follow in index order.
+// stored outputs sweep every block of the range and go first (ascending), so that they do
+// not end up alone at the tail of the launch; the others fill the order from its end.
 struct PrepArgs {
     const int32_t *y, *negcls, *tally, *vhat, *fresh;
     int32_t *gate, *ngate, *order;
@@ -225,62 +225,110 @@ struct PrepArgs {
     int i_begin, i_end, qp, m, n, C, T;
 };
 
+constexpr int COUNTER_SETS = 64; // interleaved copies of the 8 event counters
+constexpr int PREP_ITEMS = 4;    // consecutive items per thread and round
+
 __global__ __launch_bounds__(1024) void k_launch_prep(const PrepArgs a)
 {
-    __shared__ int wave_cnt[16];
-    __shared__ int base_sh, seen_sh;
+    __shared__ int wave_cnt[2][16][2]; // [round parity][wavefront][front, back]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const bool ordering = (int)blockIdx.x == a.m;
     const int c = blockIdx.x;
     int32_t *out = ordering ? a.order : a.gate + (int64_t)c * a.qp;
-    const int passes = ordering ? 2 : 1; // ordering: pass 0 places the outdated clauses, pass 1 the rest
     const int lo = ordering ? 0 : a.i_begin, hi = ordering ? a.C : a.i_end;
-    if (tid == 0) base_sh = seen_sh = 0;
-    __syncthreads();
-    for (int pass = 0; pass < passes; ++pass) {
-        for (int t0 = lo; t0 < hi; t0 += 1024) {
-            const int t = t0 + tid;
-            bool take = false, match = false;
-            int value = 0;
-            if (t < hi) {
-                if (ordering) {
-                    const int4 f = *reinterpret_cast<const int4 *>(a.fresh + (int64_t)t * 4);
-                    const bool stale = (f.x < f.y && f.x < a.i_end && f.y > a.i_begin) || (f.z < a.i_end);
-                    take = (pass == 0) ? stale : !stale;
-                    value = t;
-                } else {
-                    const int target = (a.y[t] == c) ? 1 : 0;
-                    match = target || a.negcls[t] == c;
-                    if (match) {
-                        const int v = a.vhat ? a.vhat[(int64_t)t * a.m + c] : a.tally[(int64_t)c * a.qp + t];
-                        const int vc = min(max(v, -a.T), a.T);
-                        take = (target ? a.T - vc : a.T + vc) > 0; // Algorithm 1: error of the recorded vote sum
-                    }
-                    value = (t << 1) | target;
+    int n_front = 0, n_back = 0, n_seen = 0; // the same in every thread
+    int round = 0;
+    for (int t0 = lo; t0 < hi; t0 += 1024 * PREP_ITEMS, ++round) {
+        // item j of a thread goes to the front part (gate list; outdated clause), to the
+        // back part (clause that is up to date), or nowhere
+        bool front[PREP_ITEMS], back[PREP_ITEMS];
+        int value[PREP_ITEMS];
+        int seen = 0;
+        if (ordering) {
+            int4 f[PREP_ITEMS];
+#pragma unroll
+            for (int j = 0; j < PREP_ITEMS; ++j) {
+                const int t = t0 + tid * PREP_ITEMS + j;
+                f[j] = make_int4(0, 0, a.i_end, 0);
+                if (t < hi) f[j] = *reinterpret_cast<const int4 *>(a.fresh + (int64_t)t * 4);
+            }
+#pragma unroll
+            for (int j = 0; j < PREP_ITEMS; ++j) {
+                const int t = t0 + tid * PREP_ITEMS + j;
+                const bool stale = (f[j].x < f[j].y && f[j].x < a.i_end && f[j].y > a.i_begin) || (f[j].z < a.i_end);
+                front[j] = t < hi && stale;
+                back[j] = t < hi && !stale;
+                value[j] = t;
+            }
+        } else {
+            // label, drawn class and tally of every item are requested before any is looked at
+            int yy[PREP_ITEMS], ng[PREP_ITEMS], v[PREP_ITEMS];
+#pragma unroll
+            for (int j = 0; j < PREP_ITEMS; ++j) {
+                const int t = t0 + tid * PREP_ITEMS + j;
+                yy[j] = ng[j] = -1;
+                v[j] = 0;
+                if (t < hi) {
+                    yy[j] = a.y[t];
+                    ng[j] = a.negcls[t];
+                    v[j] = a.vhat ? a.vhat[(int64_t)t * a.m + c] : a.tally[(int64_t)c * a.qp + t];
                 }
             }
-            const uint64_t b = ballot(take);
-            const uint64_t bm = ballot(match);
-            const int pre = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, 0u));
-            if (lane == 0) {
-                wave_cnt[wave] = __builtin_popcountll(b);
-                if (bm) atomicAdd(&seen_sh, __builtin_popcountll(bm));
+#pragma unroll
+            for (int j = 0; j < PREP_ITEMS; ++j) {
+                const int t = t0 + tid * PREP_ITEMS + j;
+                const int target = (yy[j] == c) ? 1 : 0;
+                const bool match = target || ng[j] == c;
+                const int vc = min(max(v[j], -a.T), a.T);
+                seen += match ? 1 : 0;
+                front[j] = match && (target ? a.T - vc : a.T + vc) > 0; // Algorithm 1: error of the recorded vote sum
+                back[j] = false;
+                value[j] = (t << 1) | target;
             }
-            __syncthreads();
-            int off = base_sh, total = 0;
-            for (int w = 0; w < 16; ++w) {
-                if (w < wave) off += wave_cnt[w];
-                total += wave_cnt[w];
+        }
+        // positions inside the wavefront, in item order: lanes before this one, then earlier items
+        int pre_f = 0, pre_b = 0, cnt_f = 0, cnt_b = 0, own_f = 0, own_b = 0;
+        int pos_f[PREP_ITEMS], pos_b[PREP_ITEMS];
+#pragma unroll
+        for (int j = 0; j < PREP_ITEMS; ++j) {
+            const uint64_t bf = ballot(front[j]), bb = ballot(back[j]);
+            pre_f += (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bf >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bf, 0u));
+            pre_b += (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bb >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bb, 0u));
+            cnt_f += __builtin_popcountll(bf);
+            cnt_b += __builtin_popcountll(bb);
+            pos_f[j] = own_f;
+            pos_b[j] = own_b;
+            own_f += front[j] ? 1 : 0;
+            own_b += back[j] ? 1 : 0;
+        }
+        int (*wc)[2] = wave_cnt[round & 1];
+        if (lane == 0) {
+            wc[wave][0] = cnt_f;
+            wc[wave][1] = cnt_b;
+        }
+        n_seen += seen;
+        __syncthreads(); // one barrier per round: the next round writes the other half of wave_cnt
+        int off_f = n_front, off_b = n_back;
+        for (int w = 0; w < 16; ++w) {
+            const int cf = wc[w][0], cb = wc[w][1];
+            if (w < wave) {
+                off_f += cf;
+                off_b += cb;
             }
-            if (take) out[off + pre] = value;
-            __syncthreads();
-            if (tid == 0) base_sh += total;
-            __syncthreads();
+            n_front += cf;
+            n_back += cb;
+        }
+#pragma unroll
+        for (int j = 0; j < PREP_ITEMS; ++j) {
+            if (front[j]) out[off_f + pre_f + pos_f[j]] = value[j];
+            if (back[j]) out[a.C - 1 - (off_b + pre_b + pos_b[j])] = value[j];
         }
     }
-    if (tid == 0 && !ordering) {
-        a.ngate[c] = base_sh;
-        if (seen_sh) atomicAdd(&a.counters[4], (unsigned long long)seen_sh * (unsigned long long)a.n);
+    if (!ordering) {
+        if (tid == 0) a.ngate[c] = n_front;
+        // pairs of the range whose class is trained for the example: per-thread counts, summed by the wavefront
+        for (int o = 32; o > 0; o >>= 1) n_seen += __shfl_down(n_seen, o, 64);
+        if (lane == 0 && n_seen) atomicAdd(&a.counters[(wave & (COUNTER_SETS - 1)) * 8 + 4], (unsigned long long)n_seen * (unsigned long long)a.n);
     }
 }
 
@@ -699,7 +747,6 @@ __device__ __forceinline__ void eval_blocks(const uint32_t *eoff, const uint2 *e
     for (int kk = 0; kk < SWEEP_BLOCKS; ++kk) out[kk] = ballot(viol[kk] == 0u);
 }
 
-constexpr int COUNTER_SETS = 64; // interleaved copies of the 8 event counters
 constexpr int TRAIN_WAVES = 4; // clauses (wavefronts) per workgroup of the training kernel
 
 // One wavefront = one clause of class c.  The examples whose gate can open for this
