@@ -7,6 +7,8 @@
 //                  tally  int32  [m][qp]    voting tallies, qp = q rounded up to 64
 //                  ostar  uint32 [C][Qw]    previous clause outputs, 1 bit per (clause, example), Qw = qp/32
 //                  XT     uint32 [Wf][qp]   transposed features (word-major) for lane = example evaluation
+//                  XB     uint32 [o+1][QW]  features as bit rows over the examples (row o all ones), QW = 64*ceil(q/2048)
+//                  lits   uint32 [C][128]   literal lists of the clauses, nlit int32 [C] their lengths
 //                  negcls int32  [qp]       class trained towards 0 for each example, this epoch
 //                  gate   int32  [m][qp]    per class and launch: ascending list of (example << 1 | target) whose gate can open
 //                  fresh  int32  [C][4]     per clause: example ranges whose stored outputs may be outdated
@@ -14,7 +16,10 @@
 //                  counters uint64 [64][8] interleaved event counters, flag int32
 //   literal word lw < Wf holds x_(32 lw + j), literal word Wf + fw holds NOT x_(32 fw + j).
 //
-// Two evaluation layouts are used:
+// Three evaluation layouts are used:
+//   k_eval_sparse lane = 32 examples : one clause per wavefront at a time, one word of XB
+//            per included literal; votes counted bit-sliced (tally pre-calculation and
+//            inference with a workspace).
 //   k_eval_* lane = clause : include masks in VGPRs, example words arrive through
 //            scalar loads, one bit-select per feature word and pair; clause votes are
 //            summed with wave ballot + popcount (inference, tally pre-calculation).
@@ -608,6 +613,225 @@ __global__ __launch_bounds__(64) void k_eval_stream(const uint32_t *__restrict__
 }
 
 // ------------------------------------------------------------------------
+// k_eval_sparse: clause evaluation from literal lists, lane = 32 examples
+// ------------------------------------------------------------------------
+//
+// A trained clause includes a few dozen of its 2o literals, so its output on 32 examples
+// is the AND of that many 32-bit words when the features are stored feature-major:
+// XB [o + 1][QW] uint32, bit b of word w of row k = x_k of example 32 w + b; row o is all
+// ones (padding of literal lists), QW = words per row, a multiple of 64.  A wavefront
+// then evaluates one clause on 2048 examples with one coalesced 256-byte load and one
+// bit operation per included literal - against one operation per feature WORD and
+// example in the lane = clause kernels above.  This is the GPU counterpart of indexing
+// clauses by their literals.  An untrained clause includes about half of all literals,
+// but then some literal is false on every example after a few loads and the loop stops.
+
+constexpr int LIT_MAX = 128;   // listed literals per clause; clauses with more are finished from their masks
+constexpr int SP_WAVES = 16;   // wavefronts per workgroup of k_eval_sparse
+constexpr int SP_PLANES = 8;   // bit planes of a wavefront's vote counter: at most 255 clauses per wavefront
+
+// XB from row-major X: one workgroup of 4 wavefronts per 64 examples, each wavefront a
+// contiguous share of the feature words; the 64 ballots of bit b of a word are two words
+// of row 32 fw + b.  Examples from q up to 32 QW read as 0.
+__global__ __launch_bounds__(256) void k_transpose_bits(const uint32_t *__restrict__ X, uint32_t *__restrict__ XB,
+                                                        int64_t q, int Wf, int o, int QW)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * 64 + lane;
+    const int per = (Wf + 3) / 4;
+    const int f_end = min(Wf, (wave + 1) * per);
+    for (int fw = wave * per; fw < f_end; ++fw) {
+        const uint32_t x = (i < q) ? X[i * Wf + fw] : 0u;
+        uint64_t r = 0;
+#pragma unroll
+        for (int b = 0; b < 32; ++b) {
+            const uint64_t bal = ballot(((x >> b) & 1u) != 0u);
+            r = (lane == b) ? bal : r;
+        }
+        const int k = fw * 32 + lane;
+        if (lane < 32 && k < o)
+            *reinterpret_cast<uint2 *>(XB + (int64_t)k * QW + (int64_t)blockIdx.x * 2) =
+                make_uint2((uint32_t)r, (uint32_t)(r >> 32));
+    }
+}
+
+// Literal list of every clause, one wavefront per clause: entry = byte offset of the
+// literal's feature row in XB, bit 0 set for a negated literal; the first LIT_MAX
+// included literals in literal order, padded to a multiple of 4 with the all-ones row.
+// nlit[g] = number of included literals (may exceed LIT_MAX).
+__global__ __launch_bounds__(256) void k_literal_lists(const uint32_t *__restrict__ inc, uint32_t *__restrict__ lits,
+                                                       int32_t *__restrict__ nlit, int C, int Wf, int W,
+                                                       uint32_t row_bytes, uint32_t ones_row)
+{
+    const int lane = threadIdx.x & 63;
+    const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (g >= C) return;
+    uint32_t *L = lits + (int64_t)g * LIT_MAX;
+    int base = 0;
+    for (int w0 = 0; w0 < W; w0 += 64) {
+        const int lw = w0 + lane;
+        uint32_t m = lw < W ? inc[(int64_t)g * W + lw] : 0u;
+        const int cnt = __builtin_popcount(m);
+        int incl = cnt; // inclusive prefix sum over the lanes
+#pragma unroll
+        for (int dlt = 1; dlt < 64; dlt <<= 1) {
+            const int t = __shfl_up(incl, dlt, 64);
+            if (lane >= dlt) incl += t;
+        }
+        int pos = base + incl - cnt;
+        const bool neg = lw >= Wf;
+        const uint32_t f0 = (uint32_t)(neg ? lw - Wf : lw) * 32u;
+        while (m) {
+            const int b = __builtin_ctz(m);
+            m &= m - 1u;
+            if (pos < LIT_MAX) L[pos] = (f0 + (uint32_t)b) * row_bytes | (neg ? 1u : 0u);
+            ++pos;
+        }
+        base += __shfl(incl, 63, 64);
+    }
+    const int listed = min(base, LIT_MAX);
+    if (lane < 4 && listed + lane < ((listed + 3) & ~3)) L[listed + lane] = ones_row;
+    if (lane == 0) nlit[g] = base;
+}
+
+struct SparseArgs {
+    uint32_t *bits;      // [C][bits_stride] clause outputs, or null
+    int64_t bits_stride;
+    int32_t *acc;        // votes of class c for example i go to acc[i*acc_si + c*acc_sc], or null
+    int64_t acc_si, acc_sc;
+    int64_t q;
+    int QW, QWq;         // words per row of XB; words that hold examples (ceil(q/32))
+    int n, Wf, W;
+    int S, chunk;        // clauses of a class are split over S workgroups, `chunk` (a multiple of 16) each
+    int T;               // > 0: the sums are clamped to [-T, T] (only with S = 1)
+};
+
+// Output of clause g on the 32 examples of this lane's word; `valid` masks examples >= q.
+__device__ __forceinline__ uint32_t sparse_clause(const uint32_t *__restrict__ lits, const int32_t *__restrict__ nlit,
+                                                  const uint32_t *__restrict__ inc, const char *xb_lane, int g,
+                                                  uint32_t valid, const SparseArgs &a)
+{
+    const int nl = nlit[g];
+    const uint32_t *L = lits + (int64_t)g * LIT_MAX;
+    uint32_t accv = valid;
+    const int listed = min(nl, LIT_MAX);
+    for (int k = 0; k < listed; k += 4) {
+        const uint4 e = *reinterpret_cast<const uint4 *>(L + k);
+        const uint32_t ent[4] = {e.x, e.y, e.z, e.w};
+        uint32_t x[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[j] = *reinterpret_cast<const uint32_t *>(xb_lane + (ent[j] & ~3u));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) accv &= x[j] ^ ((ent[j] & 1u) ? ~0u : 0u);
+        if (ballot(accv != 0u) == 0) return 0u; // some literal is false on every example of the range
+    }
+    if (nl > LIT_MAX && ballot(accv != 0u) != 0) {
+        // more literals than the list holds and still satisfied somewhere: go through the masks
+        accv = valid;
+        const uint32_t row_bytes = (uint32_t)a.QW * 4u;
+        for (int lw = 0; lw < a.W; ++lw) {
+            uint32_t m = inc[(int64_t)g * a.W + lw];
+            const bool neg = lw >= a.Wf;
+            const uint32_t f0 = (uint32_t)(neg ? lw - a.Wf : lw) * 32u;
+            while (m) {
+                const int b = __builtin_ctz(m);
+                m &= m - 1u;
+                const uint32_t x = *reinterpret_cast<const uint32_t *>(xb_lane + (f0 + (uint32_t)b) * row_bytes);
+                accv &= neg ? ~x : x;
+            }
+            if (ballot(accv != 0u) == 0) return 0u;
+        }
+    }
+    return accv;
+}
+
+// grid.x = ranges of 2048 examples, grid.y = m * S.  Workgroup (c, s) evaluates its share
+// of the clauses of class c on the range: wavefront w takes the clauses j = j_lo + w + 16 k
+// (all of one polarity, because j_lo and 16 are even), lane = word of 32 examples.
+// Votes are counted bit-sliced: the outputs of eight clauses go through a tree of
+// carry-save adders (two bit operations each) into ones/twos/fours and one ripple into
+// the higher planes, about three operations per clause and word instead of one counter
+// update per example.  At the end every wavefront adds its counts, signed by its
+// polarity, into the workgroup's sums in LDS, and the workgroup writes them out: stored
+// (and clamped when T > 0) if it holds all clauses of the class, added otherwise.
+__global__ __launch_bounds__(64 * SP_WAVES) void k_eval_sparse(const uint32_t *__restrict__ lits,
+                                                              const int32_t *__restrict__ nlit,
+                                                              const uint32_t *__restrict__ inc,
+                                                              const uint32_t *__restrict__ XB, const SparseArgs a)
+{
+    __shared__ int32_t sums[64 * 33]; // [word of the range][example of the word], rows padded against bank conflicts
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = blockIdx.y / a.S, s = blockIdx.y - c * a.S;
+    const int word0 = blockIdx.x * 64, word = word0 + lane;
+    uint32_t valid = 0u;
+    if (word < a.QWq) {
+        const int64_t rem = a.q - (int64_t)word * 32;
+        valid = rem >= 32 ? ~0u : ((1u << (int)rem) - 1u);
+    }
+    const char *xb_lane = reinterpret_cast<const char *>(XB + word);
+    if (a.acc) {
+        for (int t = tid; t < 64 * 33; t += 64 * SP_WAVES) sums[t] = 0;
+        __syncthreads();
+    }
+    uint32_t planes[SP_PLANES];
+#pragma unroll
+    for (int pl = 0; pl < SP_PLANES; ++pl) planes[pl] = 0u;
+    const int j_lo = s * a.chunk, j_hi = min(a.n, j_lo + a.chunk);
+    auto csa = [](uint32_t &hi, uint32_t &lo, uint32_t x, uint32_t y, uint32_t z) {
+        hi = majority3(x, y, z);
+        lo = xor3(x, y, z);
+    };
+    for (int j0 = j_lo + wave; j0 < j_hi; j0 += 8 * SP_WAVES) {
+        uint32_t x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int j = j0 + u * SP_WAVES;
+            x[u] = 0u;
+            if (j < j_hi) {
+                const int g = c * a.n + j;
+                x[u] = sparse_clause(lits, nlit, inc, xb_lane, g, valid, a);
+                if (a.bits && word < a.bits_stride) a.bits[(int64_t)g * a.bits_stride + word] = x[u];
+            }
+        }
+        if (a.acc) {
+            uint32_t t2a, t2b, t4a, t4b, e8;
+            csa(t2a, planes[0], planes[0], x[0], x[1]);
+            csa(t2b, planes[0], planes[0], x[2], x[3]);
+            csa(t4a, planes[1], planes[1], t2a, t2b);
+            csa(t2a, planes[0], planes[0], x[4], x[5]);
+            csa(t2b, planes[0], planes[0], x[6], x[7]);
+            csa(t4b, planes[1], planes[1], t2a, t2b);
+            csa(e8, planes[2], planes[2], t4a, t4b);
+#pragma unroll
+            for (int pl = 3; pl < SP_PLANES; ++pl) { // ripple the carry of weight 8 upwards
+                const uint32_t t = planes[pl] & e8;
+                planes[pl] ^= e8;
+                e8 = t;
+            }
+        }
+    }
+    if (!a.acc) return;
+    const bool positive = (wave & 1) != 0; // odd index within the class: positive polarity
+#pragma unroll 4
+    for (int e = 0; e < 32; ++e) {
+        int v = 0;
+#pragma unroll
+        for (int pl = 0; pl < SP_PLANES; ++pl) v |= (int)((planes[pl] >> e) & 1u) << pl;
+        if (v) atomicAdd(&sums[lane * 33 + e], positive ? v : -v);
+    }
+    __syncthreads();
+    for (int idx = tid; idx < 2048; idx += 64 * SP_WAVES) {
+        const int64_t i = (int64_t)word0 * 32 + idx;
+        if (i >= a.q) continue;
+        int v = sums[(idx >> 5) * 33 + (idx & 31)];
+        int32_t *dst = a.acc + i * a.acc_si + (int64_t)c * a.acc_sc;
+        if (a.S == 1) *dst = a.T > 0 ? min(max(v, -a.T), a.T) : v;
+        else if (v) atomicAdd(dst, v);
+    }
+}
+
+// ------------------------------------------------------------------------
 // k_train: Algorithm 1, one wavefront per clause
 // ------------------------------------------------------------------------
 
@@ -1147,6 +1371,9 @@ struct tm_handle {
     uint32_t *ostar;
     uint32_t *XT;
     int32_t *negcls;
+    uint32_t *XB;   // [o+1][QW] bit rows of the bound data
+    uint32_t *lits; // [C][LIT_MAX]
+    int32_t *nlit;  // [C]
     int32_t *gate;  // [m][qp] gate lists of the current launch
     int32_t *ngate; // [m]
     int32_t *fresh;
@@ -1199,8 +1426,12 @@ Dims make_dims(const tm_config *cfg)
     return d;
 }
 
+// words per row of XB for q examples: whole ranges of 2048 examples
+inline int64_t xb_row_words(int64_t q) { return ((q + 2047) / 2048) * 64; }
+inline size_t xb_bytes(const Dims &d, int64_t q) { return (size_t)(d.o + 1) * (size_t)xb_row_words(q) * 4; }
+
 struct WsLayout {
-    size_t tally, ostar, xt, negcls, gate, ngate, fresh, order, counters, flag, total;
+    size_t tally, ostar, xt, xb, lits, nlit, negcls, gate, ngate, fresh, order, counters, flag, total;
 };
 
 WsLayout ws_layout(const Dims &d, int64_t q)
@@ -1212,6 +1443,9 @@ WsLayout ws_layout(const Dims &d, int64_t q)
     L.tally = off; off += align256((size_t)d.m * qp * 4);
     L.ostar = off; off += align256((size_t)d.C * Qw * 4);
     L.xt = off; off += align256((size_t)d.Wf * qp * 4);
+    L.xb = off; off += align256(xb_bytes(d, q));
+    L.lits = off; off += align256((size_t)d.C * LIT_MAX * 4);
+    L.nlit = off; off += align256((size_t)d.C * 4);
     L.negcls = off; off += align256((size_t)qp * 4);
     L.gate = off; off += align256((size_t)d.m * qp * 4);
     L.ngate = off; off += align256((size_t)d.m * 4);
@@ -1317,6 +1551,59 @@ void launch_train_t(const TrainPtrs &p, const TrainArgs &a, bool full, hipStream
     else hipLaunchKernelGGL((k_train<WPL, false>), grid, block, lds, st, p.X, p.XT, p.gate, p.ngate, a);
 }
 
+// XB (rows of bits over the examples) of q examples given row-major, and its all-ones row.
+int build_xb(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *XB, hipStream_t st)
+{
+    const Dims &d = h->d;
+    const int64_t QW = xb_row_words(q);
+    hipLaunchKernelGGL(k_transpose_bits, dim3((unsigned)(QW / 2)), dim3(256), 0, st, X, XB, q, d.Wf, d.o, (int)QW);
+    TM_HIP(h, hipGetLastError());
+    return fill(h, XB + (int64_t)d.o * QW, (size_t)QW * 4, ~0u, st);
+}
+
+// Evaluation of all clauses on the q examples behind XB from their literal lists (rebuilt
+// here from the current masks); writes bits and/or the class sums.  With clampT > 0 the
+// sums are clamped.  acc need not be zeroed by the caller.
+int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *lits, int32_t *nlit, uint32_t *bits,
+                       int64_t bits_stride, int32_t *acc, int64_t acc_si, int64_t acc_sc, int clampT, hipStream_t st)
+{
+    const Dims &d = h->d;
+    const int64_t QW = xb_row_words(q);
+    hipLaunchKernelGGL(k_literal_lists, dim3(blocks_for(d.C, 4)), dim3(256), 0, st, h->inc, lits, nlit, d.C, d.Wf, d.W,
+                       (uint32_t)(QW * 4), (uint32_t)((int64_t)d.o * QW * 4));
+    TM_HIP(h, hipGetLastError());
+    SparseArgs a;
+    a.bits = bits; a.bits_stride = bits_stride; a.acc = acc; a.acc_si = acc_si; a.acc_sc = acc_sc;
+    a.q = q; a.QW = (int)QW; a.QWq = (int)((q + 31) / 32); a.n = d.n; a.Wf = d.Wf; a.W = d.W;
+    // enough workgroups to fill the chip (16 wavefronts each), at most 255 clauses per wavefront,
+    // at least 16 clauses per workgroup
+    const int64_t ranges = QW / 64;
+    int64_t S = (512 + d.m * ranges - 1) / (d.m * ranges);
+    S = std::max<int64_t>(S, (d.n + 4079) / 4080);
+    S = std::min<int64_t>(S, (d.n + 15) / 16);
+    int64_t chunk = (((d.n + S - 1) / S) + 15) & ~(int64_t)15;
+    S = (d.n + chunk - 1) / chunk;
+    a.S = (int)S; a.chunk = (int)chunk; a.T = (S == 1) ? clampT : 0;
+    if (acc && S > 1) {
+        // partial sums of several workgroups are added up: start from zero
+        if (acc_si == 1) {
+            const int rc = fill(h, acc, (size_t)d.m * acc_sc * 4, 0u, st);
+            if (rc) return rc;
+        } else {
+            const int rc = fill(h, acc, (size_t)q * d.m * 4, 0u, st);
+            if (rc) return rc;
+        }
+    }
+    hipLaunchKernelGGL(k_eval_sparse, dim3((unsigned)ranges, (unsigned)(d.m * S)), dim3(64 * SP_WAVES), 0, st, lits, nlit,
+                       h->inc, XB, a);
+    TM_HIP(h, hipGetLastError());
+    if (acc && S > 1 && clampT > 0) {
+        hipLaunchKernelGGL(k_clamp, dim3(blocks_for(q * d.m, 256)), dim3(256), 0, st, acc, q * d.m, clampT);
+        TM_HIP(h, hipGetLastError());
+    }
+    return TM_OK;
+}
+
 // Examples per launch of the training kernel.  An epoch is cut into ranges
 // whose slice of XT (Wf rows of `chunk` words) is at most 2 MiB, half of one
 // XCD's L2, so that it stays resident while all clauses stream over it; with
@@ -1388,10 +1675,7 @@ int fresh_set(tm_handle *h, bool all_stale, hipStream_t st)
 
 int sync_tallies(tm_handle *h, hipStream_t st)
 {
-    const Dims &d = h->d;
-    int rc = fill(h, h->tally, (size_t)d.m * h->qp * 4, 0u, st);
-    if (rc) return rc;
-    rc = launch_eval(h, h->X, h->q, h->ostar, h->Qw, h->tally, 1, h->qp, st);
+    const int rc = launch_eval_sparse(h, h->XB, h->q, h->lits, h->nlit, h->ostar, h->Qw, h->tally, 1, h->qp, 0, st);
     if (rc) return rc;
     return fresh_set(h, false, st); // every stored output is current
 }
@@ -1470,6 +1754,7 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
     // entries pack the example index into 31 bits
     if ((int64_t)d.Wf * ((q + 63) & ~(int64_t)63) * 4 >= ((int64_t)1 << 32)) return TM_ELIMIT;
     if (q > ((int64_t)1 << 30) - 64) return TM_ELIMIT;
+    if (xb_bytes(d, q) >= ((size_t)1 << 32)) return TM_ELIMIT; // literal lists hold 32-bit row offsets
     const WsLayout L = ws_layout(d, q);
     char *base = (char *)ws;
     h->bound = false;
@@ -1480,6 +1765,9 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
     h->ostar = (uint32_t *)(base + L.ostar);
     h->XT = (uint32_t *)(base + L.xt);
     h->negcls = (int32_t *)(base + L.negcls);
+    h->XB = (uint32_t *)(base + L.xb);
+    h->lits = (uint32_t *)(base + L.lits);
+    h->nlit = (int32_t *)(base + L.nlit);
     h->gate = (int32_t *)(base + L.gate);
     h->ngate = (int32_t *)(base + L.ngate);
     h->fresh = (int32_t *)(base + L.fresh);
@@ -1499,6 +1787,10 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
     if (bad) return TM_EINVAL;
 
     rc = fill(h, h->ostar, (size_t)d.C * h->Qw * 4, 0u, st);
+    if (rc) return rc;
+    rc = fill(h, h->tally, (size_t)d.m * h->qp * 4, 0u, st);
+    if (rc) return rc;
+    rc = build_xb(h, X, q, h->XB, st);
     if (rc) return rc;
     hipLaunchKernelGGL(k_transpose_x, dim3(blocks_for(h->qp * d.Wf, 256)), dim3(256), 0, st, X, h->XT, q, h->qp,
                        d.Wf);
