@@ -181,6 +181,7 @@ def main():
     Xte_d = tm.to_device_bits(synth.pack_features(Xte))
     pred = torch.empty(qt, dtype=torch.int32, device=tm.dev)
     scratch = torch.empty((qt, tm.m), dtype=torch.int32, device=tm.dev)
+    infer_ws = torch.empty(B.tm_infer_ws_bytes(tm.cfg, qt), dtype=torch.uint8, device=tm.dev)
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     e0, e1 = ev(), ev()
@@ -199,7 +200,7 @@ def main():
         B.tm_sync_tallies(tm.h)
         if evs:
             evs[2].record()
-        B.tm_predict(tm.h, Xte_d, pred, scratch)
+        B.tm_predict_ws(tm.h, Xte_d, pred, scratch, infer_ws)
         if evs:
             evs[3].record()
 

@@ -74,8 +74,9 @@ int tm_state_bytes(const tm_config *cfg, size_t *out);
 
 /* Size in bytes of the training workspace for q examples (voting tallies,
  * previous-output bits - one bit per example per clause -, transposed copy of
- * X, per-example negative class, per-class gate lists, per-clause
- * bookkeeping, counters).  Host-only computation. */
+ * X, the features as bit rows over the examples, literal lists of the clauses,
+ * per-example negative class, per-class gate lists, per-clause bookkeeping,
+ * counters).  Host-only computation. */
 int tm_train_ws_bytes(const tm_config *cfg, int64_t q, size_t *out);
 
 /* Creates a machine whose state lives in state_buf (device, at least
@@ -116,6 +117,21 @@ int tm_class_sums(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, voi
  * one bank per class).  `sums_scratch` is device int32 [q][m] scratch. */
 int tm_predict(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, int32_t *sums_scratch,
                void *stream);
+
+/* Size in bytes of the workspace of tm_class_sums_ws / tm_predict_ws for q
+ * examples (the literals as bit rows over the examples, and the list of
+ * included literals of every clause).  Host-only computation. */
+int tm_infer_ws_bytes(const tm_config *cfg, int64_t q, size_t *out);
+
+/* tm_class_sums / tm_predict with a workspace (device, tm_infer_ws_bytes, 256-
+ * byte aligned, contents need not be kept between calls).  Same results.  Eq. 1
+ * is a conjunction over the INCLUDED literals only, so each clause is evaluated
+ * from the list of its included literals instead of from its 2o mask bits; on a
+ * trained machine that is a few dozen literals per clause.  TM_ELIMIT when
+ * (2o + 1) * 64 * ceil(q / 2048) * 4 bytes reach 4 GiB: split q. */
+int tm_class_sums_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, void *ws, void *stream);
+int tm_predict_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, int32_t *sums_scratch, void *ws,
+                  void *stream);
 
 /* ---- hooks used by tests, checkpoints and measurements ---------------- */
 

@@ -17,7 +17,7 @@ TM_OK, TM_EINVAL, TM_ESTATE, TM_EHIP, TM_ELIMIT = 0, -1, -2, -3, -4
 
 EXPORTS = [
     "tm_state_bytes", "tm_train_ws_bytes", "tm_create", "tm_destroy", "tm_bind_train", "tm_fit_epoch",
-    "tm_class_sums", "tm_predict", "tm_get_ta_state", "tm_set_ta_state", "tm_clause_outputs",
+    "tm_class_sums", "tm_predict", "tm_infer_ws_bytes", "tm_class_sums_ws", "tm_predict_ws", "tm_get_ta_state", "tm_set_ta_state", "tm_clause_outputs",
     "tm_sync_tallies", "tm_get_tallies", "tm_get_prev_outputs", "tm_feedback_step", "tm_train_chunk", "tm_set_epoch",
     "tm_get_epoch", "tm_read_counters", "tm_strerror", "tm_last_hip_error",
 ]
@@ -122,6 +122,22 @@ def tm_predict(h, X, pred, sums_scratch):
                             _ptr(sums_scratch, torch.int32), _stream()), "tm_predict")
 
 
+def tm_infer_ws_bytes(cfg, q):
+    out = ctypes.c_size_t(0)
+    _check(lib().tm_infer_ws_bytes(ctypes.byref(cfg), ctypes.c_int64(q), ctypes.byref(out)), "tm_infer_ws_bytes")
+    return out.value
+
+
+def tm_class_sums_ws(h, X, sums, ws):
+    _check(lib().tm_class_sums_ws(h, _ptr(X, torch.int32), ctypes.c_int64(X.shape[0]), _ptr(sums, torch.int32),
+                                  _ptr(ws), _stream()), "tm_class_sums_ws")
+
+
+def tm_predict_ws(h, X, pred, sums_scratch, ws):
+    _check(lib().tm_predict_ws(h, _ptr(X, torch.int32), ctypes.c_int64(X.shape[0]), _ptr(pred, torch.int32),
+                               _ptr(sums_scratch, torch.int32), _ptr(ws), _stream()), "tm_predict_ws")
+
+
 def tm_get_ta_state(h, out):
     _check(lib().tm_get_ta_state(h, _ptr(out, torch.uint8), _stream()), "tm_get_ta_state")
 
@@ -191,6 +207,7 @@ class TsetlinMachine:
             self.state_buf = torch.empty(tm_state_bytes(self.cfg), dtype=torch.uint8, device=self.dev)
             self.h = tm_create(self.cfg, self.state_buf)
         self.ws = None
+        self.infer_ws = None
         self.X = self.y = None
 
     def close(self):
@@ -251,17 +268,32 @@ class TsetlinMachine:
             return tm_read_counters(self.h)
 
     # -- inference -------------------------------------------------------------
-    def class_sums(self, X):
+    def _infer_ws(self, q):
+        """Workspace of the literal-list inference calls, kept and grown as needed."""
+        need = tm_infer_ws_bytes(self.cfg, q)
+        if self.infer_ws is None or self.infer_ws.numel() < need:
+            self.infer_ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
+        return self.infer_ws
+
+    def class_sums(self, X, lists=True):
+        """lists=True: tm_class_sums_ws (clauses evaluated from their literal lists);
+        lists=False: tm_class_sums (from their include masks, no workspace)."""
         out = torch.empty((X.shape[0], self.m), dtype=torch.int32, device=self.dev)
         with torch.cuda.device(self.dev):
-            tm_class_sums(self.h, X, out)
+            if lists:
+                tm_class_sums_ws(self.h, X, out, self._infer_ws(X.shape[0]))
+            else:
+                tm_class_sums(self.h, X, out)
         return out
 
-    def predict(self, X):
+    def predict(self, X, lists=True):
         pred = torch.empty((X.shape[0],), dtype=torch.int32, device=self.dev)
         scratch = torch.empty((X.shape[0], self.m), dtype=torch.int32, device=self.dev)
         with torch.cuda.device(self.dev):
-            tm_predict(self.h, X, pred, scratch)
+            if lists:
+                tm_predict_ws(self.h, X, pred, scratch, self._infer_ws(X.shape[0]))
+            else:
+                tm_predict(self.h, X, pred, scratch)
         return pred
 
     def clause_outputs(self, X):

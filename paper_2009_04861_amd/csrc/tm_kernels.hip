@@ -7,7 +7,7 @@
 //                  tally  int32  [m][qp]    voting tallies, qp = q rounded up to 64
 //                  ostar  uint32 [C][Qw]    previous clause outputs, 1 bit per (clause, example), Qw = qp/32
 //                  XT     uint32 [Wf][qp]   transposed features (word-major) for lane = example evaluation
-//                  XB     uint32 [o+1][QW]  features as bit rows over the examples (row o all ones), QW = 64*ceil(q/2048)
+//                  XB     uint32 [2o+1][QW] literals as bit rows over the examples (row 2o all ones), QW = 64*ceil(q/2048)
 //                  lits   uint32 [C][128]   literal lists of the clauses, nlit int32 [C] their lengths
 //                  negcls int32  [qp]       class trained towards 0 for each example, this epoch
 //                  gate   int32  [m][qp]    per class and launch: ascending list of (example << 1 | target) whose gate can open
@@ -617,9 +617,10 @@ __global__ __launch_bounds__(64) void k_eval_stream(const uint32_t *__restrict__
 // ------------------------------------------------------------------------
 //
 // A trained clause includes a few dozen of its 2o literals, so its output on 32 examples
-// is the AND of that many 32-bit words when the features are stored feature-major:
-// XB [o + 1][QW] uint32, bit b of word w of row k = x_k of example 32 w + b; row o is all
-// ones (padding of literal lists), QW = words per row, a multiple of 64.  A wavefront
+// is the AND of that many 32-bit words when the literals are stored literal-major:
+// XB [2o + 1][QW] uint32, bit b of word w of row k = literal k of example 32 w + b (rows
+// 0..o-1 the features, rows o..2o-1 their negations); row 2o is all ones (padding of
+// literal lists), QW = words per row, a multiple of 64.  A wavefront
 // then evaluates one clause on 2048 examples with one coalesced 256-byte load and one
 // bit operation per included literal - against one operation per feature WORD and
 // example in the lane = clause kernels above.  This is the GPU counterpart of indexing
@@ -632,7 +633,8 @@ constexpr int SP_PLANES = 8;   // bit planes of a wavefront's vote counter: at m
 
 // XB from row-major X: one workgroup of 4 wavefronts per 64 examples, each wavefront a
 // contiguous share of the feature words; the 64 ballots of bit b of a word are two words
-// of row 32 fw + b.  Examples from q up to 32 QW read as 0.
+// of row 32 fw + b, their complement two words of row o + 32 fw + b.  Examples from q up
+// to 32 QW read as feature 0 (no clause output is taken from them).
 __global__ __launch_bounds__(256) void k_transpose_bits(const uint32_t *__restrict__ X, uint32_t *__restrict__ XB,
                                                         int64_t q, int Wf, int o, int QW)
 {
@@ -649,19 +651,22 @@ __global__ __launch_bounds__(256) void k_transpose_bits(const uint32_t *__restri
             r = (lane == b) ? bal : r;
         }
         const int k = fw * 32 + lane;
-        if (lane < 32 && k < o)
+        if (lane < 32 && k < o) {
             *reinterpret_cast<uint2 *>(XB + (int64_t)k * QW + (int64_t)blockIdx.x * 2) =
                 make_uint2((uint32_t)r, (uint32_t)(r >> 32));
+            *reinterpret_cast<uint2 *>(XB + (int64_t)(o + k) * QW + (int64_t)blockIdx.x * 2) =
+                make_uint2(~(uint32_t)r, ~(uint32_t)(r >> 32));
+        }
     }
 }
 
 // Literal list of every clause, one wavefront per clause: entry = byte offset of the
-// literal's feature row in XB, bit 0 set for a negated literal; the first LIT_MAX
-// included literals in literal order, padded to a multiple of 4 with the all-ones row.
-// nlit[g] = number of included literals (may exceed LIT_MAX).
+// literal's row in XB; the first LIT_MAX included literals in literal order, the rest of
+// the LIT_MAX slots filled with the all-ones row so that several clauses can be walked in
+// step.  nlit[g] = number of included literals (may exceed LIT_MAX).
 __global__ __launch_bounds__(256) void k_literal_lists(const uint32_t *__restrict__ inc, uint32_t *__restrict__ lits,
-                                                       int32_t *__restrict__ nlit, int C, int Wf, int W,
-                                                       uint32_t row_bytes, uint32_t ones_row)
+                                                       int32_t *__restrict__ nlit, int C, int Wf, int W, int o,
+                                                       uint32_t row_bytes)
 {
     const int lane = threadIdx.x & 63;
     const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -679,18 +684,16 @@ __global__ __launch_bounds__(256) void k_literal_lists(const uint32_t *__restric
             if (lane >= dlt) incl += t;
         }
         int pos = base + incl - cnt;
-        const bool neg = lw >= Wf;
-        const uint32_t f0 = (uint32_t)(neg ? lw - Wf : lw) * 32u;
+        const uint32_t k0 = lw >= Wf ? (uint32_t)o + (uint32_t)(lw - Wf) * 32u : (uint32_t)lw * 32u; // literal of bit 0
         while (m) {
             const int b = __builtin_ctz(m);
             m &= m - 1u;
-            if (pos < LIT_MAX) L[pos] = (f0 + (uint32_t)b) * row_bytes | (neg ? 1u : 0u);
+            if (pos < LIT_MAX) L[pos] = (k0 + (uint32_t)b) * row_bytes;
             ++pos;
         }
         base += __shfl(incl, 63, 64);
     }
-    const int listed = min(base, LIT_MAX);
-    if (lane < 4 && listed + lane < ((listed + 3) & ~3)) L[listed + lane] = ones_row;
+    for (int t = min(base, LIT_MAX) + lane; t < LIT_MAX; t += 64) L[t] = 2u * (uint32_t)o * row_bytes;
     if (lane == 0) nlit[g] = base;
 }
 
@@ -701,46 +704,28 @@ struct SparseArgs {
     int64_t acc_si, acc_sc;
     int64_t q;
     int QW, QWq;         // words per row of XB; words that hold examples (ceil(q/32))
-    int n, Wf, W;
+    int n, o, Wf, W;
     int S, chunk;        // clauses of a class are split over S workgroups, `chunk` (a multiple of 16) each
     int T;               // > 0: the sums are clamped to [-T, T] (only with S = 1)
 };
 
-// Output of clause g on the 32 examples of this lane's word; `valid` masks examples >= q.
-__device__ __forceinline__ uint32_t sparse_clause(const uint32_t *__restrict__ lits, const int32_t *__restrict__ nlit,
-                                                  const uint32_t *__restrict__ inc, const char *xb_lane, int g,
-                                                  uint32_t valid, const SparseArgs &a)
+// Output of clause g on the 32 examples of this lane's word, taken from its include masks
+// (for the rare clause that has more than LIT_MAX literals and is still satisfied somewhere
+// after the listed ones); `valid` masks examples >= q.
+__device__ __forceinline__ uint32_t clause_from_masks(const uint32_t *__restrict__ inc, const char *xb_lane, int g,
+                                                      uint32_t valid, const SparseArgs &a)
 {
-    const int nl = nlit[g];
-    const uint32_t *L = lits + (int64_t)g * LIT_MAX;
     uint32_t accv = valid;
-    const int listed = min(nl, LIT_MAX);
-    for (int k = 0; k < listed; k += 4) {
-        const uint4 e = *reinterpret_cast<const uint4 *>(L + k);
-        const uint32_t ent[4] = {e.x, e.y, e.z, e.w};
-        uint32_t x[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) x[j] = *reinterpret_cast<const uint32_t *>(xb_lane + (ent[j] & ~3u));
-#pragma unroll
-        for (int j = 0; j < 4; ++j) accv &= x[j] ^ ((ent[j] & 1u) ? ~0u : 0u);
-        if (ballot(accv != 0u) == 0) return 0u; // some literal is false on every example of the range
-    }
-    if (nl > LIT_MAX && ballot(accv != 0u) != 0) {
-        // more literals than the list holds and still satisfied somewhere: go through the masks
-        accv = valid;
-        const uint32_t row_bytes = (uint32_t)a.QW * 4u;
-        for (int lw = 0; lw < a.W; ++lw) {
-            uint32_t m = inc[(int64_t)g * a.W + lw];
-            const bool neg = lw >= a.Wf;
-            const uint32_t f0 = (uint32_t)(neg ? lw - a.Wf : lw) * 32u;
-            while (m) {
-                const int b = __builtin_ctz(m);
-                m &= m - 1u;
-                const uint32_t x = *reinterpret_cast<const uint32_t *>(xb_lane + (f0 + (uint32_t)b) * row_bytes);
-                accv &= neg ? ~x : x;
-            }
-            if (ballot(accv != 0u) == 0) return 0u;
+    const uint32_t row_bytes = (uint32_t)a.QW * 4u;
+    for (int lw = 0; lw < a.W; ++lw) {
+        uint32_t m = inc[(int64_t)g * a.W + lw];
+        const uint32_t k0 = lw >= a.Wf ? (uint32_t)a.o + (uint32_t)(lw - a.Wf) * 32u : (uint32_t)lw * 32u;
+        while (m) {
+            const int b = __builtin_ctz(m);
+            m &= m - 1u;
+            accv &= *reinterpret_cast<const uint32_t *>(xb_lane + (k0 + (uint32_t)b) * row_bytes);
         }
+        if (ballot(accv != 0u) == 0) return 0u;
     }
     return accv;
 }
@@ -770,6 +755,9 @@ __global__ __launch_bounds__(64 * SP_WAVES) void k_eval_sparse(const uint32_t *_
         valid = rem >= 32 ? ~0u : ((1u << (int)rem) - 1u);
     }
     const char *xb_lane = reinterpret_cast<const char *>(XB + word);
+    const char *xb_base = reinterpret_cast<const char *>(XB);
+    uint32_t word_off = (uint32_t)word * 4u;
+    asm volatile("" : "+v"(word_off)); // keep the sum in the vector unit
     if (a.acc) {
         for (int t = tid; t < 64 * 33; t += 64 * SP_WAVES) sums[t] = 0;
         __syncthreads();
@@ -783,14 +771,46 @@ __global__ __launch_bounds__(64 * SP_WAVES) void k_eval_sparse(const uint32_t *_
         lo = xor3(x, y, z);
     };
     for (int j0 = j_lo + wave; j0 < j_hi; j0 += 8 * SP_WAVES) {
+        // eight clauses are walked in step, four literals each per round: 32 loads in flight
         uint32_t x[8];
+        const uint32_t *L[8];
+        int nl[8], longest = 0;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int j = j0 + u * SP_WAVES;
-            x[u] = 0u;
+            const bool ok = j < j_hi;
+            const int g = c * a.n + (ok ? j : j_lo);
+            L[u] = lits + (int64_t)g * LIT_MAX;
+            nl[u] = ok ? nlit[g] : 0;
+            x[u] = ok ? valid : 0u;
+            longest = max(longest, min(nl[u], LIT_MAX));
+        }
+        for (int k = 0; k < longest; k += 4) {
+            uint32_t r[8][4];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                // past a list's end: the all-ones row.  Row offset (uniform) + word offset (per lane)
+                // are added in the vector unit: one operation instead of a 64-bit scalar add per load
+                const uint4 e = *reinterpret_cast<const uint4 *>(L[u] + k);
+                r[u][0] = *reinterpret_cast<const uint32_t *>(xb_base + (e.x + word_off));
+                r[u][1] = *reinterpret_cast<const uint32_t *>(xb_base + (e.y + word_off));
+                r[u][2] = *reinterpret_cast<const uint32_t *>(xb_base + (e.z + word_off));
+                r[u][3] = *reinterpret_cast<const uint32_t *>(xb_base + (e.w + word_off));
+            }
+            uint32_t any = 0u;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                x[u] &= r[u][0] & r[u][1] & r[u][2] & r[u][3];
+                any |= x[u];
+            }
+            if (ballot(any != 0u) == 0) break; // every clause has a false literal on every example of the range
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int j = j0 + u * SP_WAVES;
             if (j < j_hi) {
                 const int g = c * a.n + j;
-                x[u] = sparse_clause(lits, nlit, inc, xb_lane, g, valid, a);
+                if (nl[u] > LIT_MAX && ballot(x[u] != 0u) != 0) x[u] = clause_from_masks(inc, xb_lane, g, valid, a);
                 if (a.bits && word < a.bits_stride) a.bits[(int64_t)g * a.bits_stride + word] = x[u];
             }
         }
@@ -1371,7 +1391,7 @@ struct tm_handle {
     uint32_t *ostar;
     uint32_t *XT;
     int32_t *negcls;
-    uint32_t *XB;   // [o+1][QW] bit rows of the bound data
+    uint32_t *XB;   // [2o+1][QW] literal rows of the bound data
     uint32_t *lits; // [C][LIT_MAX]
     int32_t *nlit;  // [C]
     int32_t *gate;  // [m][qp] gate lists of the current launch
@@ -1428,7 +1448,7 @@ Dims make_dims(const tm_config *cfg)
 
 // words per row of XB for q examples: whole ranges of 2048 examples
 inline int64_t xb_row_words(int64_t q) { return ((q + 2047) / 2048) * 64; }
-inline size_t xb_bytes(const Dims &d, int64_t q) { return (size_t)(d.o + 1) * (size_t)xb_row_words(q) * 4; }
+inline size_t xb_bytes(const Dims &d, int64_t q) { return (size_t)(2 * d.o + 1) * (size_t)xb_row_words(q) * 4; }
 
 struct WsLayout {
     size_t tally, ostar, xt, xb, lits, nlit, negcls, gate, ngate, fresh, order, counters, flag, total;
@@ -1558,7 +1578,7 @@ int build_xb(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *XB, hipStream
     const int64_t QW = xb_row_words(q);
     hipLaunchKernelGGL(k_transpose_bits, dim3((unsigned)(QW / 2)), dim3(256), 0, st, X, XB, q, d.Wf, d.o, (int)QW);
     TM_HIP(h, hipGetLastError());
-    return fill(h, XB + (int64_t)d.o * QW, (size_t)QW * 4, ~0u, st);
+    return fill(h, XB + (int64_t)2 * d.o * QW, (size_t)QW * 4, ~0u, st);
 }
 
 // Evaluation of all clauses on the q examples behind XB from their literal lists (rebuilt
@@ -1570,11 +1590,11 @@ int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *li
     const Dims &d = h->d;
     const int64_t QW = xb_row_words(q);
     hipLaunchKernelGGL(k_literal_lists, dim3(blocks_for(d.C, 4)), dim3(256), 0, st, h->inc, lits, nlit, d.C, d.Wf, d.W,
-                       (uint32_t)(QW * 4), (uint32_t)((int64_t)d.o * QW * 4));
+                       d.o, (uint32_t)(QW * 4));
     TM_HIP(h, hipGetLastError());
     SparseArgs a;
     a.bits = bits; a.bits_stride = bits_stride; a.acc = acc; a.acc_si = acc_si; a.acc_sc = acc_sc;
-    a.q = q; a.QW = (int)QW; a.QWq = (int)((q + 31) / 32); a.n = d.n; a.Wf = d.Wf; a.W = d.W;
+    a.q = q; a.QW = (int)QW; a.QWq = (int)((q + 31) / 32); a.n = d.n; a.o = d.o; a.Wf = d.Wf; a.W = d.W;
     // enough workgroups to fill the chip (16 wavefronts each), at most 255 clauses per wavefront,
     // at least 16 clauses per workgroup
     const int64_t ranges = QW / 64;
@@ -1853,6 +1873,48 @@ int tm_predict(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, int32_
     if (q == 0) return TM_OK;
     if (!pred || !sums_scratch) return TM_EINVAL;
     const int rc = tm_class_sums(h, X, q, sums_scratch, stream);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_argmax, dim3(blocks_for(q, 256)), dim3(256), 0, (hipStream_t)stream, sums_scratch, pred, q,
+                       h->d.m);
+    TM_HIP(h, hipGetLastError());
+    return TM_OK;
+}
+
+int tm_infer_ws_bytes(const tm_config *cfg, int64_t q, size_t *out)
+{
+    const int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!out || q < 0) return TM_EINVAL;
+    const Dims d = make_dims(cfg);
+    *out = align256(xb_bytes(d, q)) + align256((size_t)d.C * LIT_MAX * 4) + align256((size_t)d.C * 4);
+    return TM_OK;
+}
+
+int tm_class_sums_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, void *ws, void *stream)
+{
+    if (!h || q < 0) return TM_EINVAL;
+    if (q == 0) return TM_OK;
+    if (!X || !sums || !ws || ((uintptr_t)ws & 255)) return TM_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    const Dims &d = h->d;
+    if (xb_bytes(d, q) >= ((size_t)1 << 32)) return TM_ELIMIT;
+    char *base = (char *)ws;
+    uint32_t *XB = (uint32_t *)base;
+    uint32_t *lits = (uint32_t *)(base + align256(xb_bytes(d, q)));
+    int32_t *nlit = (int32_t *)(base + align256(xb_bytes(d, q)) + align256((size_t)d.C * LIT_MAX * 4));
+    const int rc = build_xb(h, X, q, XB, st);
+    if (rc) return rc;
+    return launch_eval_sparse(h, XB, q, lits, nlit, nullptr, 0, sums, d.m, 1, d.T, st);
+}
+
+int tm_predict_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, int32_t *sums_scratch, void *ws,
+                  void *stream)
+{
+    if (!h || q < 0) return TM_EINVAL;
+    if (q == 0) return TM_OK;
+    if (!pred || !sums_scratch) return TM_EINVAL;
+    const int rc = tm_class_sums_ws(h, X, q, sums_scratch, ws, stream);
     if (rc) return rc;
     hipLaunchKernelGGL(k_argmax, dim3(blocks_for(q, 256)), dim3(256), 0, (hipStream_t)stream, sums_scratch, pred, q,
                        h->d.m);

@@ -87,6 +87,8 @@ def test_full_size_inference_sampled_examples(workload, device):
     Xd = dev_bits(gpu, Xte)
     sums = gpu.class_sums(Xd).cpu().numpy()
     pred = gpu.predict(Xd).cpu().numpy()
+    assert np.array_equal(sums, gpu.class_sums(Xd, lists=False).cpu().numpy())   # both evaluation schemes
+    assert np.array_equal(pred, gpu.predict(Xd, lists=False).cpu().numpy())
     ex = np.concatenate([[0, 255, 256, len(yte) - 1], rng.integers(0, len(yte), size=44)])
     Xs = np.ascontiguousarray(Xte[ex])
     want = ora.class_sums(Xs)
@@ -157,6 +159,8 @@ def test_wide_feature_workloads_sampled_clauses(name, q, n_small, device):
     Xd = dev_bits(gpu, Xte)
     ex = rng.integers(0, len(yte), size=24)
     Xs = np.ascontiguousarray(Xte[ex])
-    assert np.array_equal(gpu.class_sums(Xd).cpu().numpy()[ex], ora.class_sums(Xs))
+    sums = gpu.class_sums(Xd).cpu().numpy()
+    assert np.array_equal(sums[ex], ora.class_sums(Xs))
+    assert np.array_equal(sums, gpu.class_sums(Xd, lists=False).cpu().numpy())
     assert np.array_equal(gpu.predict(Xd).cpu().numpy()[ex], ora.predict(Xs))
     gpu.close()

@@ -66,8 +66,44 @@ def test_inference_matches(shape, q, device):
     assert np.array_equal(bits_to_u8(gpu.clause_outputs(Xd), q), ora.clause_outputs(X).T)
     want = ora.class_sums(X)
     assert q < 63 or np.abs(want).max() > 0
-    assert np.array_equal(gpu.class_sums(Xd).cpu().numpy(), want)
-    assert np.array_equal(gpu.predict(Xd).cpu().numpy(), ora.predict(X))
+    for lists in (True, False):   # literal-list evaluation with a workspace / mask evaluation without
+        assert np.array_equal(gpu.class_sums(Xd, lists=lists).cpu().numpy(), want)
+        assert np.array_equal(gpu.predict(Xd, lists=lists).cpu().numpy(), ora.predict(X))
+
+
+@pytest.mark.parametrize("q", [70, 2048, 2049, 4500])
+def test_literal_list_lengths_and_dense_clauses(q, device):
+    """Clauses with 0 .. 300 included literals that are nevertheless satisfied (the lists
+    hold 128 literals; longer clauses are finished from their masks), next to untrained
+    clauses that include about half of all literals; ranges of 2048 examples with a tail."""
+    m, n, o, N, T = 2, 24, 420, 128, 9
+    print("literal lists", q, flush=True)
+    rng = np.random.default_rng(q)
+    ora, gpu = make_pair(m, n, o, N, T, 4.0, 5)
+    X = (rng.random((q, o)) < 0.5).astype(np.uint8)
+    X[:, 100:420] = 0                     # features that are always 0: their negated literals always hold
+    y = rng.integers(0, m, size=q).astype(np.int32)
+    st = np.ones((ora.C, ora.L), dtype=np.int32)
+    lengths = [0, 1, 3, 4, 5, 127, 128, 129, 131, 132, 133, 300]
+    for g, k in enumerate(lengths):                    # class 0: k always-true literals
+        st[g, o + 100:o + 100 + k] = 2 * N
+    for g, k in enumerate(lengths):                    # class 1: the same plus one literal that depends on the data
+        st[n + g, o + 100:o + 100 + k] = 2 * N
+        st[n + g, g if g % 3 else o + g] = 2 * N       # x_g or NOT x_g
+    st[12:24] = rng.integers(1, 2 * N + 1, size=(12, ora.L))        # untrained: half of the literals included
+    st[n + 12:n + 24] = rng.integers(1, 2 * N + 1, size=(12, ora.L))
+    ora.state[:] = st
+    push_state(gpu, ora.state)
+    Xd = dev_bits(gpu, X)
+    want = ora.class_sums(X)
+    assert np.abs(want).max() > 0
+    for lists in (True, False):
+        assert np.array_equal(gpu.class_sums(Xd, lists=lists).cpu().numpy(), want)
+        assert np.array_equal(gpu.predict(Xd, lists=lists).cpu().numpy(), ora.predict(X))
+    # the tally pre-calculation of bind uses the lists as well
+    gpu.bind_train(Xd, dev_i32(gpu, y))
+    assert np.array_equal(gpu.tallies().cpu().numpy(), ora.class_sums(X, clamp=False))
+    assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ora.clause_outputs(X).T)
 
 
 def test_class_sums_are_clamped(device):
@@ -77,9 +113,10 @@ def test_class_sums_are_clamped(device):
     ora.state[64 + np.arange(0, 64, 2), :] = 256
     push_state(gpu, ora.state)
     X = np.zeros((5, 20), dtype=np.uint8)
-    got = gpu.class_sums(dev_bits(gpu, X)).cpu().numpy()
-    assert np.array_equal(got, ora.class_sums(X))
-    assert got[0].tolist() == [0, 5]
+    for lists in (True, False):
+        got = gpu.class_sums(dev_bits(gpu, X), lists=lists).cpu().numpy()
+        assert np.array_equal(got, ora.class_sums(X))
+        assert got[0].tolist() == [0, 5]
 
 
 @pytest.mark.parametrize("shape", SHAPES)
