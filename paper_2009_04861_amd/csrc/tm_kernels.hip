@@ -871,6 +871,7 @@ struct TrainArgs {
     int lds_mask_words; // W rounded up to a multiple of 4
     int lds_off_words;  // Wf + EVAL_PAD rounded up to a multiple of 4
     int lds_wave_words; // LDS words per wavefront
+    int QW;             // words per row of XB
 };
 
 constexpr int EVAL_PAD = 16; // empty entries after the list: a group may read that far past its end
@@ -879,18 +880,21 @@ constexpr int EVAL_PAD = 16; // empty entries after the list: a group may read t
 // plain or negated mask word is non-zero, compacted in LDS: eoff[k] = byte
 // offset of that word's row in XT, emask[k] = {mask of plain literals, mask of
 // negated literals}; padded with EVAL_PAD empty entries.  Rebuilt whenever plane 7
-// changes.
+// changes.  *lit_count (LDS) receives the number of included literals.
 template <int WPL>
 __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lmask, uint32_t *eoff,
-                                             uint2 *emask, int lane, int Wf, int W, uint32_t row_bytes)
+                                             uint2 *emask, uint32_t *lit_count, int lane, int Wf, int W,
+                                             uint32_t row_bytes)
 {
 #pragma unroll
     for (int r = 0; r < WPL; ++r) {
         const int lw = r * 64 + lane;
         if (lw < W) lmask[lw] = p[r][7];
     }
+    if (lane == 0) *lit_count = 0u;
     wave_lds_sync();
     int n = 0;
+    uint32_t lits = 0;
     for (int f0 = 0; f0 < Wf; f0 += 64) {
         const int fw = f0 + lane;
         const bool ok = fw < Wf;
@@ -903,8 +907,10 @@ __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lm
             eoff[n + pre] = (uint32_t)fw * row_bytes;
             emask[n + pre] = make_uint2(mp, mn);
         }
+        lits += (uint32_t)(__builtin_popcount(mp) + __builtin_popcount(mn));
         n += __builtin_popcountll(b);
     }
+    if (lits) atomicAdd(lit_count, lits); // number of included literals of the clause, summed in LDS
     if (lane < EVAL_PAD) {
         eoff[n + lane] = 0u;
         emask[n + lane] = make_uint2(0u, 0u);
@@ -948,47 +954,38 @@ __device__ __forceinline__ uint64_t eval64(const uint32_t *eoff, const uint2 *em
     return ballot(viol == 0u);
 }
 
-// The same for SWEEP_BLOCKS consecutive blocks at once, SWEEP_GROUP entries at a time:
-// block kk lies 256 bytes after block kk-1 in every row of XT, so one address serves all
-// blocks of an entry and its masks are read once.  No early exit: it would need every
-// example of every block violated, which trained (sparse) clauses hardly ever reach.
-constexpr int SWEEP_BLOCKS = 4;
-constexpr int SWEEP_GROUP = 8;
+// Literals a clause's list in LDS can hold for the sweeps over outdated outputs; clauses
+// with more (untrained ones) are swept block by block with eval64.
+constexpr int TRAIN_LIT_MAX = 64;
 
-__device__ __forceinline__ void eval_blocks(const uint32_t *eoff, const uint2 *emask, int nent,
-                                            const uint32_t *__restrict__ xt_block, int lane,
-                                            uint64_t (&out)[SWEEP_BLOCKS])
+// List of the included literals of the clause held in p (lane = literal word), as byte
+// offsets of their rows in XB, padded to a multiple of 4 with the all-ones row; returns
+// the number of included literals.  Only called for clauses with at most TRAIN_LIT_MAX.
+// The order of the list does not matter (the output is their conjunction): literals are
+// taken bit position by bit position, each position compacted over the lanes by ballot.
+template <int WPL>
+__device__ __forceinline__ int build_literals(const u32x8 (&p)[WPL], uint32_t *llist, int lane, int Wf, int W, int o,
+                                              uint32_t xb_row_bytes)
 {
-    uint32_t viol[SWEEP_BLOCKS];
+    int base = 0;
 #pragma unroll
-    for (int kk = 0; kk < SWEEP_BLOCKS; ++kk) viol[kk] = 0u;
-    const char *base = reinterpret_cast<const char *>(xt_block);
-    const uint32_t lane4 = (uint32_t)lane * 4u;
-    int k = 0;
-    do { // an empty clause has one group of padding entries
-        uint32_t off[SWEEP_GROUP], x[SWEEP_BLOCKS][SWEEP_GROUP];
-#pragma unroll
-        for (int j = 0; j < SWEEP_GROUP; j += 4) {
-            const uint4 o = *reinterpret_cast<const uint4 *>(eoff + k + j);
-            off[j] = o.x + lane4; off[j + 1] = o.y + lane4; off[j + 2] = o.z + lane4; off[j + 3] = o.w + lane4;
+    for (int r = 0; r < WPL; ++r) {
+        const int lw = r * 64 + lane;
+        const uint32_t m = lw < W ? p[r][7] : 0u;
+        if (ballot(m != 0u) == 0) continue;
+        const uint32_t k0 = lw >= Wf ? (uint32_t)o + (uint32_t)(lw - Wf) * 32u : (uint32_t)lw * 32u; // literal of bit 0
+        for (int b = 0; b < 32; ++b) {
+            const bool set = ((m >> b) & 1u) != 0u;
+            const uint64_t bal = ballot(set);
+            if (bal == 0) continue;
+            const int pos = base + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+            if (set && pos < TRAIN_LIT_MAX) llist[pos] = (k0 + (uint32_t)b) * xb_row_bytes;
+            base += __builtin_popcountll(bal);
         }
-#pragma unroll
-        for (int j = 0; j < SWEEP_GROUP; ++j)
-#pragma unroll
-            for (int kk = 0; kk < SWEEP_BLOCKS; ++kk)
-                x[kk][j] = *reinterpret_cast<const uint32_t *>(base + off[j] + 256 * kk);
-        const uint4 *mq = reinterpret_cast<const uint4 *>(emask + k);
-#pragma unroll
-        for (int j = 0; j < SWEEP_GROUP / 2; ++j) {
-            const uint4 m = mq[j];
-#pragma unroll
-            for (int kk = 0; kk < SWEEP_BLOCKS; ++kk)
-                viol[kk] |= bitselect(x[kk][2 * j], m.y, m.x) | bitselect(x[kk][2 * j + 1], m.w, m.z);
-        }
-        k += SWEEP_GROUP;
-    } while (k < nent);
-#pragma unroll
-    for (int kk = 0; kk < SWEEP_BLOCKS; ++kk) out[kk] = ballot(viol[kk] == 0u);
+    }
+    if (lane < 4) llist[min(base, TRAIN_LIT_MAX) + lane] = 2u * (uint32_t)o * xb_row_bytes;
+    wave_lds_sync();
+    return base;
 }
 
 constexpr int TRAIN_WAVES = 4; // clauses (wavefronts) per workgroup of the training kernel
@@ -1001,6 +998,7 @@ constexpr int TRAIN_WAVES = 4; // clauses (wavefronts) per workgroup of the trai
 // of the pass are never touched.
 template <int WPL, bool FULL>
 __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
+                                                            const uint32_t *__restrict__ XB,
                                                             const int32_t *__restrict__ gate,
                                                             const int32_t *__restrict__ ngate, const TrainArgs a)
 {
@@ -1014,6 +1012,8 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     uint32_t *lmask = lds + wave * a.lds_wave_words;        // [W] include masks, literal-word order
     uint32_t *eoff = lmask + a.lds_mask_words;              // [Wf + EVAL_PAD] (rounded to 4 words)
     uint2 *emask = reinterpret_cast<uint2 *>(eoff + a.lds_off_words);
+    uint32_t *llist = lmask + a.lds_wave_words - (TRAIN_LIT_MAX + 8); // [TRAIN_LIT_MAX + 4] literal list for the sweeps
+    uint32_t *lit_count = llist + TRAIN_LIT_MAX + 4;                   // number of included literals
 
     const int c = g / d.n;
     const bool pos = ((g - c * d.n) & 1) != 0; // odd index within the class: positive polarity
@@ -1035,7 +1035,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
         }
         p[r] = t;
     }
-    int nent = build_entries<WPL>(p, lmask, eoff, emask, lane, d.Wf, d.W, row_bytes);
+    int nent = build_entries<WPL>(p, lmask, eoff, emask, lit_count, lane, d.Wf, d.W, row_bytes);
 
     // lowest Philox block of the Type I comparator that can matter: bits of the
     // uniform below the lowest set bit of thr never decide u < thr
@@ -1117,38 +1117,75 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     };
     // Refresh of every block in [from, to) that may hold outdated outputs; no gate fired in
     // them, so the masks stay as they are.  After a mask change these are all the blocks up
-    // to the next fired gate, and their evaluation is most of what a trained machine's
-    // epoch costs, so runs of SWEEP_BLOCKS whole blocks are taken together: the entry
-    // offsets and masks are read from LDS once for all of them.
-    auto all_stale = [&](int b, int e) { // every block of [b, e) may hold outdated outputs
-        return b >= (slo >> 6) || (plo < phi && b >= (plo >> 6) && e <= ((phi + 63) >> 6));
+    // to the next fired gate, most of what an epoch of a trained machine has to evaluate.
+    // A trained clause has few literals, so the sweep walks its literal list over the rows
+    // of XB, lane = word of 32 examples: 2048 examples per pass and one load per literal.
+    int n_listed = -1;          // literals of the current masks, -1: list not built since the last change
+    uint32_t n_changes_v = 0;   // tally changes found by the passes, per lane
+    const char *xb_base = reinterpret_cast<const char *>(XB);
+    uint32_t *ostar_row = a.ostar + (int64_t)g * a.Qw;
+    auto sweep_listed = [&](int bs, int be) { // blocks [bs, be), all of them possibly outdated
+        for (int w0 = 2 * bs; w0 < 2 * be; w0 += 64) {
+            const int w = w0 + lane;
+            const bool act = w < 2 * be;
+            const int e0 = w << 5;
+            const int lo = min(max(i_begin - e0, 0), 32), hi = min(max(i_end - e0, 0), 32);
+            uint32_t rm = 0u; // examples of the word that belong to this launch
+            if (act && hi > lo) rm = (hi == 32 ? ~0u : (1u << hi) - 1u) & ~((1u << lo) - 1u);
+            const uint32_t woff = act ? (uint32_t)w * 4u : 0u;
+            const uint32_t ost = act ? ostar_row[w] : 0u;
+            uint32_t accv = rm;
+            for (int k = 0; k < n_listed; k += 4) {
+                const uint4 e = *reinterpret_cast<const uint4 *>(llist + k);
+                const uint32_t x0 = *reinterpret_cast<const uint32_t *>(xb_base + (e.x + woff));
+                const uint32_t x1 = *reinterpret_cast<const uint32_t *>(xb_base + (e.y + woff));
+                const uint32_t x2 = *reinterpret_cast<const uint32_t *>(xb_base + (e.z + woff));
+                const uint32_t x3 = *reinterpret_cast<const uint32_t *>(xb_base + (e.w + woff));
+                accv &= x0 & x1 & x2 & x3;
+            }
+            uint32_t diff = (accv ^ ost) & rm;
+            if (diff) ostar_row[w] = ost ^ diff;
+            n_changes_v += (uint32_t)__builtin_popcount(diff);
+            while (diff) { // one tally correction per changed example
+                const int bit = __builtin_ctz(diff);
+                diff &= diff - 1u;
+                atomicAdd(&a.tally[(int64_t)c * a.qp + e0 + bit], ((accv >> bit) & 1u) ? sign : -sign);
+            }
+        }
+        n_eval += (uint32_t)(be - bs);
+        // the whole blocks among them are up to date again
+        const int fs = max(bs, (i_begin + 63) >> 6), fe = (i_end == q) ? be : min(be, i_end >> 6);
+        if (fs < fe) {
+            const int b0 = fs << 6, b1 = fe << 6;
+            if (b0 <= plo) plo = max(plo, b1);
+            if (b0 <= slo) slo = max(slo, b1);
+        }
     };
     auto sweep = [&](int from, int to) {
-        int b = next_stale(from);
-        while (b < to) {
-            const uint32_t *op = a.ostar + (int64_t)g * a.Qw + (b << 1);
-            if (WPL <= 8 && b + SWEEP_BLOCKS <= to && (b << 6) >= i_begin && ((b + SWEEP_BLOCKS) << 6) <= i_end &&
-                all_stale(b, b + SWEEP_BLOCKS)) {
-                uint2 os[SWEEP_BLOCKS];
-#pragma unroll
-                for (int kk = 0; kk < SWEEP_BLOCKS; ++kk) os[kk] = *reinterpret_cast<const uint2 *>(op + 2 * kk);
-                uint64_t ob[SWEEP_BLOCKS];
-                eval_blocks(eoff, emask, nent, XT + (b << 6), lane, ob);
-#pragma unroll
-                for (int kk = 0; kk < SWEEP_BLOCKS; ++kk)
-                    refresh_block(b + kk, ob[kk], pack64(os[kk].x, os[kk].y), ~0ull);
-                const int b0 = b << 6, b1 = (b + SWEEP_BLOCKS) << 6; // these blocks are up to date again
-                if (b0 <= plo) plo = max(plo, b1);
-                if (b0 <= slo) slo = max(slo, b1);
-                n_eval += SWEEP_BLOCKS;
-                b = next_stale(b + SWEEP_BLOCKS);
-            } else {
-                const uint32_t o0 = op[0], o1 = op[1];
-                const uint64_t ob = eval64(eoff, emask, nent, XT + (b << 6), lane);
-                close_block(b, ob, pack64(o0, o1), range_mask(b << 6), false);
-                ++n_eval;
-                b = next_stale(b + 1); // closing b does not change which later blocks are outdated
-            }
+        if (next_stale(from) >= to) return;
+        // the outdated blocks are those of [plo, phi) and of [slo, qp), in this order
+        int s1 = from, e1 = from;
+        if (plo < phi) {
+            s1 = max(from, plo >> 6);
+            e1 = max(s1, min(to, (phi + 63) >> 6));
+        }
+        const int s2 = max(max(from, slo >> 6), e1);
+        const int n_blocks = (e1 - s1) + max(to - s2, 0);
+        // The list pays for runs of blocks: a few blocks, or a list that the last mask change
+        // left to be rebuilt for a short run, are cheaper block by block below; so are wide
+        // clauses (their registers hold the automata) and untrained ones (hundreds of literals).
+        if (WPL <= 4 && n_blocks >= (n_listed < 0 ? 8 : 3) && (int)*lit_count <= TRAIN_LIT_MAX) {
+            if (n_listed < 0) n_listed = build_literals<WPL>(p, llist, lane, d.Wf, d.W, d.o, (uint32_t)a.QW * 4u);
+            if (s1 < e1) sweep_listed(s1, e1);
+            if (s2 < to) sweep_listed(s2, to);
+            return;
+        }
+        for (int b = next_stale(from); b < to; b = next_stale(b + 1)) { // closing b does not change which later blocks are outdated
+            const uint32_t *op = ostar_row + (b << 1);
+            const uint32_t o0 = op[0], o1 = op[1];
+            const uint64_t ob = eval64(eoff, emask, nent, XT + (b << 6), lane);
+            close_block(b, ob, pack64(o0, o1), range_mask(b << 6), false);
+            ++n_eval;
         }
     };
 
@@ -1337,7 +1374,8 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
             }
             if (ballot(changed != 0u)) { // the conjunction changed: re-evaluate this and the later examples of the block
                 mask_changed = true;
-                nent = build_entries<WPL>(p, lmask, eoff, emask, lane, d.Wf, d.W, row_bytes);
+                n_listed = -1;
+                nent = build_entries<WPL>(p, lmask, eoff, emask, lit_count, lane, d.Wf, d.W, row_bytes);
                 const uint64_t nb = eval64(eoff, emask, nent, XT + (cb << 6), lane);
                 const uint64_t keep = (1ull << bl) - 1ull;
                 obits = (obits & keep) | (nb & ~keep);
@@ -1359,6 +1397,8 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
             a.inc[(int64_t)g * d.W + lw] = t[7];
         }
     }
+    for (int sh = 32; sh > 0; sh >>= 1) n_changes_v += __shfl_xor(n_changes_v, sh, 64);
+    n_changes += n_changes_v;
     // event counters: 64 interleaved sets, because thousands of wavefronts ending at the
     // same time on one address serialise in the L2 atomic unit (measured: ~1.7 ms per launch)
     if (lane >= 1 && lane < 8) {
@@ -1558,7 +1598,7 @@ int launch_eval(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *bits, int6
 }
 
 struct TrainPtrs {
-    const uint32_t *X, *XT;
+    const uint32_t *X, *XT, *XB;
     const int32_t *gate, *ngate;
 };
 
@@ -1567,8 +1607,8 @@ void launch_train_t(const TrainPtrs &p, const TrainArgs &a, bool full, hipStream
 {
     const size_t lds = (size_t)a.lds_wave_words * TRAIN_WAVES * 4;
     const dim3 grid((unsigned)((a.d.C + TRAIN_WAVES - 1) / TRAIN_WAVES)), block(64 * TRAIN_WAVES);
-    if (full) hipLaunchKernelGGL((k_train<WPL, true>), grid, block, lds, st, p.X, p.XT, p.gate, p.ngate, a);
-    else hipLaunchKernelGGL((k_train<WPL, false>), grid, block, lds, st, p.X, p.XT, p.gate, p.ngate, a);
+    if (full) hipLaunchKernelGGL((k_train<WPL, true>), grid, block, lds, st, p.X, p.XT, p.XB, p.gate, p.ngate, a);
+    else hipLaunchKernelGGL((k_train<WPL, false>), grid, block, lds, st, p.X, p.XT, p.XB, p.gate, p.ngate, a);
 }
 
 // XB (rows of bits over the examples) of q examples given row-major, and its all-ones row.
@@ -1641,13 +1681,14 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
 {
     const Dims &d = h->d;
     TrainArgs a;
-    const TrainPtrs p{h->X, h->XT, h->gate, h->ngate};
+    const TrainPtrs p{h->X, h->XT, h->XB, h->gate, h->ngate};
     a.d = d; a.sat = h->sat; a.planes = h->planes; a.inc = h->inc; a.tally = h->tally;
     a.vhat = vhat; a.ostar = h->ostar; a.fresh = h->fresh; a.order = h->order; a.counters = h->counters;
     a.q = (int32_t)h->q; a.qp = (int32_t)h->qp; a.Qw = (int32_t)h->Qw; a.epoch = h->epoch;
     a.lds_mask_words = (d.W + 3) & ~3;
     a.lds_off_words = (d.Wf + EVAL_PAD + 3) & ~3;
-    a.lds_wave_words = a.lds_mask_words + a.lds_off_words + 2 * ((d.Wf + EVAL_PAD + 1) & ~1);
+    a.lds_wave_words = a.lds_mask_words + a.lds_off_words + 2 * ((d.Wf + EVAL_PAD + 1) & ~1) + TRAIN_LIT_MAX + 8;
+    a.QW = (int)xb_row_words(h->q);
     const bool full = (d.N == 128);
     const int wpl = (d.W + 63) / 64;
     const int64_t chunk = train_chunk(d);
