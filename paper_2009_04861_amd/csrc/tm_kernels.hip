@@ -207,134 +207,143 @@ __global__ void k_fresh_set(int32_t *fresh, int C, int qp, int all_stale)
     if (g < C) *reinterpret_cast<int4 *>(fresh + (int64_t)g * 4) = make_int4(0, all_stale ? qp : 0, qp, 0);
 }
 
-// What a launch of the training kernel over the examples [i_begin, i_end) needs, one
-// workgroup of 1024 per task, each a compaction by ballot prefixes.
+// What a launch of the training kernel over the examples [i_begin, i_end) needs: two stable
+// compactions.
 //
-// blockIdx.x = c < m: gate list of class c = the examples of the range, ascending, whose
-// gate can open for a clause of c, packed as (example << 1 | target): target 1 where
-// y_i = c, target 0 where c is the class drawn against y_i, and error e > 0 under the
-// tally as it stands now (or under the snapshot vhat).  The examples with e = 0 are left
-// out: their gate probability e/2T is 0, so a clause that read this tally would not act,
-// and reading a tally that is one launch old is within the method's premise of outdated
-// tallies (Section 3.1).  The clause re-reads the tally of a listed example when it gets
-// there.  ngate[c] receives the length; counter 4 the number of (clause, example) pairs of
-// the range whose class is trained for the example.
+// Task c < m: gate list of class c = the examples of the range, ascending, whose gate can
+// open for a clause of c, packed as (example << 1 | target): target 1 where y_i = c,
+// target 0 where c is the class drawn against y_i, and error e > 0 under the tally as it
+// stands now (or under the snapshot vhat).  The examples with e = 0 are left out: their
+// gate probability e/2T is 0, so a clause that read this tally would not act, and reading
+// a tally that is one launch old is within the method's premise of outdated tallies
+// (Section 3.1).  The clause re-reads the tally of a listed example when it gets there.
+// ngate[c] receives the length; counter 4 the number of (clause, example) pairs of the
+// range whose class is trained for the example.
 //
-// blockIdx.x = m: launch order of the clauses.  Those that start the launch with outdated
-// stored outputs sweep every block of the range and go first (ascending), so that they do
-// not end up alone at the tail of the launch; the others fill the order from its end.
+// Task m: launch order of the clauses.  Those that start the launch with outdated stored
+// outputs sweep every block of the range and go first (ascending), so that they do not end
+// up alone at the tail of the launch; the others fill the order from its end.
+//
+// The items of a task (examples of the range, clauses) are cut into segments of
+// PREP_SEG, one workgroup of 1024 each, so that the loads of the whole range are in flight
+// at once; the kernel runs twice: the first run leaves the number of flagged items of
+// every segment in seg_cnt, the second run places them.
 struct PrepArgs {
     const int32_t *y, *negcls, *tally, *vhat, *fresh;
-    int32_t *gate, *ngate, *order;
+    int32_t *gate, *ngate, *order, *seg_cnt; // seg_cnt [m + 1][segs][2]
     unsigned long long *counters;
-    int i_begin, i_end, qp, m, n, C, T;
+    int i_begin, i_end, qp, m, n, C, T, segs;
 };
 
 constexpr int COUNTER_SETS = 64; // interleaved copies of the 8 event counters
-constexpr int PREP_ITEMS = 4;    // consecutive items per thread and round
+constexpr int PREP_ROUNDS = 4;   // rounds of 1024 items per segment
+constexpr int PREP_SEG = 1024 * PREP_ROUNDS;
 
+template <bool PLACE>
 __global__ __launch_bounds__(1024) void k_launch_prep(const PrepArgs a)
 {
-    __shared__ int wave_cnt[2][16][2]; // [round parity][wavefront][front, back]
+    __shared__ int cnt[PREP_ROUNDS * 16][2]; // [round][wavefront] x [front, back]
+    __shared__ int seg_base[2];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const bool ordering = (int)blockIdx.x == a.m;
-    const int c = blockIdx.x;
-    int32_t *out = ordering ? a.order : a.gate + (int64_t)c * a.qp;
+    const int task = blockIdx.y, seg = blockIdx.x;
+    const bool ordering = task == a.m;
+    const int c = task;
     const int lo = ordering ? 0 : a.i_begin, hi = ordering ? a.C : a.i_end;
-    int n_front = 0, n_back = 0, n_seen = 0; // the same in every thread
-    int round = 0;
-    for (int t0 = lo; t0 < hi; t0 += 1024 * PREP_ITEMS, ++round) {
-        // item j of a thread goes to the front part (gate list; outdated clause), to the
-        // back part (clause that is up to date), or nowhere
-        bool front[PREP_ITEMS], back[PREP_ITEMS];
-        int value[PREP_ITEMS];
-        int seen = 0;
+    const int p0 = lo + seg * PREP_SEG;
+    if (p0 >= hi) return; // the grid is sized for the longer of the two kinds of task
+    const int32_t *vsrc = a.vhat ? a.vhat + c : a.tally + (int64_t)c * a.qp;
+    const int64_t vstride = a.vhat ? a.m : 1;
+    int32_t *sc = a.seg_cnt + ((int64_t)task * a.segs) * 2;
+    // an item past the end is read as the last item (no branch around the loads) and dropped
+    bool f[PREP_ROUNDS], bk[PREP_ROUNDS], tg[PREP_ROUNDS];
+    int n_seen = 0;
+#pragma unroll
+    for (int r = 0; r < PREP_ROUNDS; ++r) {
+        const int t = p0 + r * 1024 + tid;
+        const bool live = t < hi;
+        const int tc = min(t, hi - 1);
+        bk[r] = tg[r] = false;
         if (ordering) {
-            int4 f[PREP_ITEMS];
+            const int4 fr = *reinterpret_cast<const int4 *>(a.fresh + (int64_t)tc * 4);
+            const bool stale = (fr.x < fr.y && fr.x < a.i_end && fr.y > a.i_begin) || (fr.z < a.i_end);
+            f[r] = live && stale;
+            bk[r] = live && !stale;
+        } else {
+            const int yy = a.y[tc], ng = a.negcls[tc], v = vsrc[(int64_t)tc * vstride];
+            tg[r] = live && yy == c;
+            const bool match = live && (tg[r] || ng == c);
+            const int vc = min(max(v, -a.T), a.T);
+            n_seen += match ? 1 : 0;
+            f[r] = match && (tg[r] ? a.T - vc : a.T + vc) > 0; // Algorithm 1: error of the recorded vote sum
+        }
+    }
+    uint64_t bf[PREP_ROUNDS], bb[PREP_ROUNDS];
 #pragma unroll
-            for (int j = 0; j < PREP_ITEMS; ++j) {
-                const int t = t0 + tid * PREP_ITEMS + j;
-                f[j] = make_int4(0, 0, a.i_end, 0);
-                if (t < hi) f[j] = *reinterpret_cast<const int4 *>(a.fresh + (int64_t)t * 4);
+    for (int r = 0; r < PREP_ROUNDS; ++r) {
+        bf[r] = ballot(f[r]);
+        bb[r] = ballot(bk[r]);
+        if (lane == 0) {
+            cnt[r * 16 + wave][0] = __builtin_popcountll(bf[r]);
+            cnt[r * 16 + wave][1] = __builtin_popcountll(bb[r]);
+        }
+    }
+    if (PLACE && tid < 2) { // where this segment starts: the flagged items of the segments before it
+        int sum = 0;
+        for (int k = 0; k < seg; ++k) sum += sc[k * 2 + tid];
+        seg_base[tid] = sum;
+    }
+    __syncthreads();
+    // flagged items of the (round, wavefront) slots before the own one, and of the whole segment
+    int before_f = 0, before_b = 0, all_f = 0, all_b = 0;
+    if (wave == 0) {
+        const int vf = cnt[lane][0], vb = cnt[lane][1]; // PREP_ROUNDS * 16 = 64 slots: one per lane
+        int inf = vf, inb = vb;
+#pragma unroll
+        for (int dlt = 1; dlt < 64; dlt <<= 1) {
+            const int tf = __shfl_up(inf, dlt, 64), tb = __shfl_up(inb, dlt, 64);
+            if (lane >= dlt) {
+                inf += tf;
+                inb += tb;
             }
-#pragma unroll
-            for (int j = 0; j < PREP_ITEMS; ++j) {
-                const int t = t0 + tid * PREP_ITEMS + j;
-                const bool stale = (f[j].x < f[j].y && f[j].x < a.i_end && f[j].y > a.i_begin) || (f[j].z < a.i_end);
-                front[j] = t < hi && stale;
-                back[j] = t < hi && !stale;
-                value[j] = t;
+        }
+        all_f = __shfl(inf, 63, 64);
+        all_b = __shfl(inb, 63, 64);
+        if (!PLACE) {
+            if (lane == 0) {
+                sc[seg * 2] = all_f;
+                sc[seg * 2 + 1] = all_b;
             }
         } else {
-            // label, drawn class and tally of every item are requested before any is looked at
-            int yy[PREP_ITEMS], ng[PREP_ITEMS], v[PREP_ITEMS];
-#pragma unroll
-            for (int j = 0; j < PREP_ITEMS; ++j) {
-                const int t = t0 + tid * PREP_ITEMS + j;
-                yy[j] = ng[j] = -1;
-                v[j] = 0;
-                if (t < hi) {
-                    yy[j] = a.y[t];
-                    ng[j] = a.negcls[t];
-                    v[j] = a.vhat ? a.vhat[(int64_t)t * a.m + c] : a.tally[(int64_t)c * a.qp + t];
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < PREP_ITEMS; ++j) {
-                const int t = t0 + tid * PREP_ITEMS + j;
-                const int target = (yy[j] == c) ? 1 : 0;
-                const bool match = target || ng[j] == c;
-                const int vc = min(max(v[j], -a.T), a.T);
-                seen += match ? 1 : 0;
-                front[j] = match && (target ? a.T - vc : a.T + vc) > 0; // Algorithm 1: error of the recorded vote sum
-                back[j] = false;
-                value[j] = (t << 1) | target;
-            }
-        }
-        // positions inside the wavefront, in item order: lanes before this one, then earlier items
-        int pre_f = 0, pre_b = 0, cnt_f = 0, cnt_b = 0, own_f = 0, own_b = 0;
-        int pos_f[PREP_ITEMS], pos_b[PREP_ITEMS];
-#pragma unroll
-        for (int j = 0; j < PREP_ITEMS; ++j) {
-            const uint64_t bf = ballot(front[j]), bb = ballot(back[j]);
-            pre_f += (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bf >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bf, 0u));
-            pre_b += (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bb >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bb, 0u));
-            cnt_f += __builtin_popcountll(bf);
-            cnt_b += __builtin_popcountll(bb);
-            pos_f[j] = own_f;
-            pos_b[j] = own_b;
-            own_f += front[j] ? 1 : 0;
-            own_b += back[j] ? 1 : 0;
-        }
-        int (*wc)[2] = wave_cnt[round & 1];
-        if (lane == 0) {
-            wc[wave][0] = cnt_f;
-            wc[wave][1] = cnt_b;
-        }
-        n_seen += seen;
-        __syncthreads(); // one barrier per round: the next round writes the other half of wave_cnt
-        int off_f = n_front, off_b = n_back;
-        for (int w = 0; w < 16; ++w) {
-            const int cf = wc[w][0], cb = wc[w][1];
-            if (w < wave) {
-                off_f += cf;
-                off_b += cb;
-            }
-            n_front += cf;
-            n_back += cb;
-        }
-#pragma unroll
-        for (int j = 0; j < PREP_ITEMS; ++j) {
-            if (front[j]) out[off_f + pre_f + pos_f[j]] = value[j];
-            if (back[j]) out[a.C - 1 - (off_b + pre_b + pos_b[j])] = value[j];
+            cnt[lane][0] = inf - vf;
+            cnt[lane][1] = inb - vb;
         }
     }
-    if (!ordering) {
-        if (tid == 0) a.ngate[c] = n_front;
-        // pairs of the range whose class is trained for the example: per-thread counts, summed by the wavefront
-        for (int o = 32; o > 0; o >>= 1) n_seen += __shfl_down(n_seen, o, 64);
-        if (lane == 0 && n_seen) atomicAdd(&a.counters[(wave & (COUNTER_SETS - 1)) * 8 + 4], (unsigned long long)n_seen * (unsigned long long)a.n);
+    if (!PLACE) {
+        if (!ordering) { // pairs of the range whose class is trained for the example
+            for (int sh = 32; sh > 0; sh >>= 1) n_seen += __shfl_down(n_seen, sh, 64);
+            if (lane == 0 && n_seen)
+                atomicAdd(&a.counters[((seg * 16 + wave) & (COUNTER_SETS - 1)) * 8 + 4],
+                          (unsigned long long)n_seen * (unsigned long long)a.n);
+        }
+        return;
     }
+    __syncthreads();
+    int32_t *out = ordering ? a.order : a.gate + (int64_t)c * a.qp;
+#pragma unroll
+    for (int r = 0; r < PREP_ROUNDS; ++r) {
+        const int t = p0 + r * 1024 + tid;
+        const int value = ordering ? t : ((t << 1) | (tg[r] ? 1 : 0));
+        before_f = seg_base[0] + cnt[r * 16 + wave][0];
+        before_b = seg_base[1] + cnt[r * 16 + wave][1];
+        if (f[r])
+            out[before_f + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bf[r] >> 32),
+                                                          __builtin_amdgcn_mbcnt_lo((uint32_t)bf[r], 0u))] = value;
+        if (bk[r])
+            out[a.C - 1 - (before_b + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bb[r] >> 32),
+                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)bb[r], 0u)))] = value;
+    }
+    // the last segment of a gate list knows its length
+    if (!ordering && wave == 0 && lane == 0 && p0 + PREP_SEG >= hi) a.ngate[c] = seg_base[0] + all_f;
 }
 
 // ------------------------------------------------------------------------
@@ -1438,6 +1447,7 @@ struct tm_handle {
     int32_t *ngate; // [m]
     int32_t *fresh;
     int32_t *order; // [C] launch order of the clauses
+    int32_t *seg_cnt; // [m + 1][segments][2] flagged items per segment of the launch preparation
     unsigned long long *counters;
     int32_t *flag;
     uint32_t epoch;
@@ -1490,8 +1500,11 @@ Dims make_dims(const tm_config *cfg)
 inline int64_t xb_row_words(int64_t q) { return ((q + 2047) / 2048) * 64; }
 inline size_t xb_bytes(const Dims &d, int64_t q) { return (size_t)(2 * d.o + 1) * (size_t)xb_row_words(q) * 4; }
 
+// segments of the launch preparation: of the longest range of examples, or of the clauses
+inline int64_t prep_segments(const Dims &d, int64_t qp) { return (std::max<int64_t>(qp, d.C) + PREP_SEG - 1) / PREP_SEG; }
+
 struct WsLayout {
-    size_t tally, ostar, xt, xb, lits, nlit, negcls, gate, ngate, fresh, order, counters, flag, total;
+    size_t tally, ostar, xt, xb, lits, nlit, negcls, gate, ngate, fresh, order, seg_cnt, counters, flag, total;
 };
 
 WsLayout ws_layout(const Dims &d, int64_t q)
@@ -1511,6 +1524,7 @@ WsLayout ws_layout(const Dims &d, int64_t q)
     L.ngate = off; off += align256((size_t)d.m * 4);
     L.fresh = off; off += align256((size_t)d.C * 16);
     L.order = off; off += align256((size_t)d.C * 4);
+    L.seg_cnt = off; off += align256((size_t)(d.m + 1) * prep_segments(d, qp) * 8);
     L.counters = off; off += align256((size_t)COUNTER_SETS * 8 * 8);
     L.flag = off; off += 256;
     L.total = off;
@@ -1664,15 +1678,17 @@ int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *li
     return TM_OK;
 }
 
-// Examples per launch of the training kernel.  An epoch is cut into ranges
-// whose slice of XT (Wf rows of `chunk` words) is at most 2 MiB, half of one
-// XCD's L2, so that it stays resident while all clauses stream over it; with
-// the whole epoch in one launch wavefronts drift apart over all of XT and
-// re-fetch it from HBM many times (measured: 6x the fetch traffic), while
-// shorter ranges only add launches.
+// Examples per launch of the training kernel.  Wide clauses (more than 4 register slots
+// per lane) evaluate every block from the word-major XT, and an epoch is cut into ranges
+// whose slice of XT (Wf rows of `chunk` words) is at most 2 MiB, half of one XCD's L2, so
+// that it stays resident while all clauses stream over it (measured: 6x the fetch traffic
+// with the whole epoch in one launch).  Narrow clauses sweep through literal rows and do
+// better with few launches (measured: one launch of 60,000 examples 0.27 ms against 0.37 ms
+// for three): 16 MiB.  Each launch re-reads the tallies for its gate lists.
 int64_t train_chunk(const Dims &d)
 {
-    int64_t chunk = ((int64_t)(2 << 20) / (4 * (int64_t)d.Wf)) & ~(int64_t)63;
+    const int wpl = (d.W + 63) / 64;
+    int64_t chunk = ((int64_t)((wpl <= 4 ? 16 : 2) << 20) / (4 * (int64_t)d.Wf)) & ~(int64_t)63;
     if (chunk < 512) chunk = 512;
     return chunk;
 }
@@ -1698,9 +1714,14 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
         a.i_end = (int32_t)std::min(b + chunk, i_end);
         PrepArgs pa;
         pa.y = h->y; pa.negcls = h->negcls; pa.tally = h->tally; pa.vhat = vhat; pa.fresh = h->fresh;
-        pa.gate = h->gate; pa.ngate = h->ngate; pa.order = h->order; pa.counters = h->counters;
+        pa.gate = h->gate; pa.ngate = h->ngate; pa.order = h->order; pa.seg_cnt = h->seg_cnt; pa.counters = h->counters;
         pa.i_begin = a.i_begin; pa.i_end = a.i_end; pa.qp = a.qp; pa.m = d.m; pa.n = d.n; pa.C = d.C; pa.T = d.T;
-        hipLaunchKernelGGL(k_launch_prep, dim3(d.m + 1), dim3(1024), 0, st, pa);
+        pa.segs = (int)prep_segments(d, h->qp);
+        const int64_t items = std::max<int64_t>(a.i_end - a.i_begin, d.C);
+        const dim3 pgrid((unsigned)((items + PREP_SEG - 1) / PREP_SEG), (unsigned)(d.m + 1));
+        hipLaunchKernelGGL(k_launch_prep<false>, pgrid, dim3(1024), 0, st, pa);
+        TM_HIP(h, hipGetLastError());
+        hipLaunchKernelGGL(k_launch_prep<true>, pgrid, dim3(1024), 0, st, pa);
         TM_HIP(h, hipGetLastError());
         if (wpl <= 1) launch_train_t<1>(p, a, full, st);
         else if (wpl <= 2) launch_train_t<2>(p, a, full, st);
@@ -1833,6 +1854,7 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
     h->ngate = (int32_t *)(base + L.ngate);
     h->fresh = (int32_t *)(base + L.fresh);
     h->order = (int32_t *)(base + L.order);
+    h->seg_cnt = (int32_t *)(base + L.seg_cnt);
     h->counters = (unsigned long long *)(base + L.counters);
     h->flag = (int32_t *)(base + L.flag);
 
