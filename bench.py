@@ -8,9 +8,10 @@ One "step" is one pass of the whole hot path over the image-like workload
     tm_sync_tallies   tally pre-calculation over all (clause, example) pairs
     tm_predict        class sums + argmax over the 10,000 test examples
 `value` is training examples per second of whole steps with all inputs resident
-in HBM.  The roofline object is for the dominant kernel (the training kernel)
-and is measured inside this program with events on the launch stream; the CPU
-oracle is timed on a bounded sample of the same workload in the same run.
+in HBM.  The roofline objects (training kernel, literal-list evaluation kernel)
+are measured inside this program with events that the library records on the
+launch stream around each launch of these kernels; the CPU oracle is timed on a
+bounded sample of the same workload in the same run.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 """
@@ -40,36 +41,40 @@ TYPE2_OPS_PER_WORD = 2 + 16                              # mask + one ripple
 GATE_OPS = PHILOX_OPS + 8                                # one block + clip, error, 64-bit compare
 
 
-# HBM traffic of one launch of the training kernel in the timed (steady) epochs of the default
-# workload, from two separate `rocprofv3 --pmc` runs of this program (FETCH_SIZE, then
-# WRITE_SIZE, KiB per dispatch, averaged over the launches of the last timed epoch).  The scale
-# factors come from the same counters read for a plain 1 GiB device copy in the same runs
-# (--calibration-copy): FETCH_SIZE reads 524,310 KiB for 1,048,576 KiB fetched, WRITE_SIZE reads
-# 1,048,576 KiB for 1,048,576 KiB written.  Summaries are under profiles/.
+# HBM traffic per launch in the timed (steady) epochs of the default workload, from two separate
+# `rocprofv3 --pmc` runs of this program (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch, averaged
+# over the timed launches).  The scale factors come from the same counters read for a plain
+# 1 GiB device copy in the same runs (--calibration-copy): FETCH_SIZE reads 524,310 KiB for
+# 1,048,576 KiB fetched, WRITE_SIZE reads 1,048,576 KiB for 1,048,576 KiB written.  Summaries are
+# under profiles/.
 MEASURED_TRAFFIC = {
-    "image_like": {"fetch_kib": 48354.0, "fetch_scale": 2.0, "write_kib": 55477.0, "write_scale": 1.0},
-    # k_eval_resident<25,true,true> (tm_sync_tallies), per launch
-    "image_like_eval": {"fetch_kib": 174800.0, "fetch_scale": 2.0, "write_kib": 704400.0, "write_scale": 1.0},
+    "image_like_train": {"fetch_kib": 0.0, "fetch_scale": 2.0, "write_kib": 0.0, "write_scale": 1.0},
+    # k_eval_sparse in tm_sync_tallies
+    "image_like_precalc": {"fetch_kib": 0.0, "fetch_scale": 2.0, "write_kib": 0.0, "write_scale": 1.0},
 }
 
-# Evaluation kernel: one bit-select per feature word and pair plus half a 3-input OR, and per
-# (64-clause tile, example) a compare, the stored-output bit and the vote (about 3 per pair-lane)
-EVAL_OPS_PER_WORD = 1.5
-EVAL_OPS_EPILOGUE = 3.0
 
-
-def train_kernel_ops(counters, W, nominal=False):
+def train_kernel_ops(counters, W, lits, entries, nominal=False):
     """Algorithmic lane-ops of a run of the training kernel from its event counters.
 
-    nominal=False counts what the method needs on this run: evaluation and refresh only for the
-    (clause, 64-example block) pairs whose stored outputs could be outdated or in which a gate
-    fired, one random draw per gate whose error is positive.  nominal=True counts the method as
-    literally read (every visited pair evaluated and refreshed, one draw per candidate): the
-    difference is work the kernel proves unnecessary and skips, with identical results."""
-    pairs = counters["pairs"] if nominal else counters["blocks_evaluated"] * 64
-    draws = counters["candidates"] if nominal else counters["gate_draws"]
-    return (pairs * (W + 2)                                # one AND-OR per literal word + refresh
-            + counters["candidates"] * (GATE_OPS - PHILOX_OPS) + draws * PHILOX_OPS
+    nominal=False counts what the kernel's own algorithm needs on this run.  A block of 64
+    examples is evaluated only if its stored outputs could be outdated or a gate fired in it:
+    through the clause's literal list (one AND per literal and word of 32 examples, plus the
+    compare and refresh), or from its include masks, lane = example (1.5 operations per
+    non-zero mask word, plus refresh).  One gate draw per listed example whose error is
+    positive at the visit.  `lits`, `entries`: mean number of included literals and of non-zero
+    feature words per clause, taken from the final state.
+    nominal=True counts the method as literally read (every visited pair evaluated against all
+    2*Wf mask words and refreshed, one draw per candidate): the difference is work that the
+    kernel proves unnecessary and skips, with identical results."""
+    if nominal:
+        ev = counters["pairs"] * (W + 2)
+        draws = counters["candidates"]
+    else:
+        listed = counters["blocks_listed"]
+        ev = listed * 2 * (lits + 2) + (counters["blocks_evaluated"] - listed) * 64 * (1.5 * entries + 2)
+        draws = counters["gate_draws"]
+    return (ev + draws * GATE_OPS
             + counters["type1"] * W * TYPE1_OPS_PER_WORD
             + counters["type2_active"] * W * TYPE2_OPS_PER_WORD)
 
@@ -215,6 +220,7 @@ def main():
         step()
     torch.cuda.synchronize()
     tm.counters()  # reset the device counters
+    B.tm_kernel_timing(tm.h, True)
 
     evs = [[ev() for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
@@ -231,22 +237,31 @@ def main():
     sync_ms = [e[1].elapsed_time(e[2]) for e in evs]
     pred_ms = [e[2].elapsed_time(e[3]) for e in evs]
     fit_avg = float(np.mean(fit_ms))
-    # tm_fit_epoch launches the training kernel once per range of `chunk` examples
-    chunk = B.tm_train_chunk(tm.h)
-    n_launch = (q + chunk - 1) // chunk
-    launch_ms = fit_avg / n_launch
-    ops = train_kernel_ops(cnt, W) / args.steps / n_launch
-    ops_nominal = train_kernel_ops(cnt, W, nominal=True) / args.steps / n_launch
+    kt = B.tm_read_kernel_timing(tm.h)   # events around every launch of the two main kernels
+    B.tm_kernel_timing(tm.h, False)
+    train_ms, n_train = kt["train"]
+    launch_ms = train_ms / max(1, n_train)
+    # sparsity of the final state: included literals and non-zero feature words per clause
+    inc = (tm.get_ta_state() >= tm.N).cpu().numpy()
+    lits = float(inc.sum(1).mean())
+    pad = tm.Wf * 32 - tm.o
+    anyw = np.pad(inc[:, :tm.o] | inc[:, tm.o:], ((0, 0), (0, pad))).reshape(C, tm.Wf, 32).any(2)
+    entries = float(anyw.sum(1).mean())
+    ops = train_kernel_ops(cnt, W, lits, entries) / max(1, n_train)
+    ops_nominal = train_kernel_ops(cnt, W, lits, entries, nominal=True) / max(1, n_train)
     achieved = ops / (launch_ms * 1e-3) / 1e12
     # algorithmic HBM bytes of one training launch: TA planes in + out and include masks out for
-    # every clause, and the launch's share of X, transposed X, previous-output bits in + out,
-    # tallies in + out and labels
+    # every clause, and the launch's share of the examples (row-major for feedback, word-major
+    # and literal rows for evaluation), previous-output bits in + out, tallies in + out, labels
+    chunk = B.tm_train_chunk(tm.h)
     share = min(1.0, chunk / q)
     hbm_bytes = (2 * C * W * 32 + C * W * 4
-                 + share * (2 * q * tm.Wf * 4 + 2 * C * ((q + 63) // 64) * 8 + tm.m * q * 4 * 2 + q * 8))
+                 + share * (2 * q * tm.Wf * 4 + 2 * tm.o * q / 8 + 2 * C * ((q + 63) // 64) * 8
+                            + tm.m * q * 4 * 2 + q * 8))
+    headline = args.workload == "image_like" and not (args.small or args.clauses_per_class or args.q_train)
     traffic = None
-    if args.workload == "image_like" and not (args.small or args.clauses_per_class or args.q_train):
-        t = MEASURED_TRAFFIC["image_like"]
+    if headline and MEASURED_TRAFFIC["image_like_train"]["fetch_kib"] > 0:
+        t = MEASURED_TRAFFIC["image_like_train"]
         traffic = 1024.0 * (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"])
 
     out = {
@@ -268,6 +283,7 @@ def main():
             "clauses_total": C, "pairs_per_epoch": q * C,
             "fit_epoch_ms": fit_avg, "sync_tallies_ms": float(np.mean(sync_ms)), "predict_ms": float(np.mean(pred_ms)),
             "bind_train_ms": bind_ms,
+            "train_kernel_launches_per_epoch": n_train // max(1, args.steps),
             "train_pairs_per_s": q * C / (fit_avg * 1e-3),
             "inference_clause_evals_per_s": qt * C / (float(np.mean(pred_ms)) * 1e-3),
             "sync_clause_evals_per_s": q * C / (float(np.mean(sync_ms)) * 1e-3),
@@ -277,42 +293,65 @@ def main():
             "blocks_evaluated_fraction": cnt["blocks_evaluated"] / max(1, args.steps * C * ((q + 63) // 64)),
             "test_accuracy_after_run": acc,
         },
-        "roofline": {
-            "kernel": "k_train (Algorithm 1, one wavefront per clause)",
-            "bound": "alu",
-            "achieved": achieved,
-            "peak": ALU_PEAK_TOPS,
-            "unit": "Tlane-op/s (32-bit integer)",
-            "frac": achieved / ALU_PEAK_TOPS,
-            "traffic": traffic,
-            "avg_launch_ms": launch_ms,
-            "launches_per_epoch": n_launch,
-            "examples_per_launch": chunk,
-            "algorithmic_lane_ops_per_launch": ops,
-            "nominal_lane_ops_per_launch": ops_nominal,
-            "nominal_frac": ops_nominal / (launch_ms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
-            "hbm_algorithmic_bytes_per_launch": hbm_bytes,
-            "hbm_achieved_GBs": hbm_bytes / (launch_ms * 1e-3) / 1e9,
-            "hbm_frac": hbm_bytes / (launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        },
     }
-    sync_avg = float(np.mean(sync_ms))
-    eval_ops = q * C * (EVAL_OPS_PER_WORD * tm.Wf + EVAL_OPS_EPILOGUE)
-    eval_achieved = eval_ops / (sync_avg * 1e-3) / 1e12
-    # algorithmic HBM bytes of the tally pre-calculation: masks and X once, previous-output bits and tallies out
-    eval_bytes = C * W * 4 + q * tm.Wf * 4 + C * ((q + 31) // 32) * 4 + tm.m * q * 4
-    eval_traffic = None
-    if traffic is not None:
-        t = MEASURED_TRAFFIC["image_like_eval"]
-        eval_traffic = 1024.0 * (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"])
-    out["roofline_eval"] = {
-        "kernel": "k_eval_resident (clause evaluation + votes, tm_sync_tallies over the training set)",
-        "bound": "alu", "achieved": eval_achieved, "peak": ALU_PEAK_TOPS, "unit": "Tlane-op/s (32-bit integer)",
-        "frac": eval_achieved / ALU_PEAK_TOPS, "traffic": eval_traffic, "avg_launch_ms": sync_avg,
-        "algorithmic_lane_ops_per_launch": eval_ops, "hbm_algorithmic_bytes_per_launch": eval_bytes,
-        "hbm_achieved_GBs": eval_bytes / (sync_avg * 1e-3) / 1e9,
-        "hbm_frac": eval_bytes / (sync_avg * 1e-3) / 1e9 / HBM_PEAK_GBS,
+    roof_train = {
+        "kernel": "k_train (Algorithm 1, one wavefront per clause)",
+        "bound": "alu",
+        "achieved": achieved,
+        "peak": ALU_PEAK_TOPS,
+        "unit": "Tlane-op/s (32-bit integer)",
+        "frac": achieved / ALU_PEAK_TOPS,
+        "traffic": traffic,
+        "avg_launch_ms": launch_ms,
+        "launches": n_train,
+        "share_of_timed_region": train_ms / (1e3 * wall),
+        "examples_per_launch": min(chunk, q),
+        "algorithmic_lane_ops_per_launch": ops,
+        "nominal_lane_ops_per_launch": ops_nominal,
+        "nominal_frac": ops_nominal / (launch_ms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
+        "hbm_algorithmic_bytes_per_launch": hbm_bytes,
+        "hbm_achieved_GBs": hbm_bytes / (launch_ms * 1e-3) / 1e9,
+        "hbm_frac": hbm_bytes / (launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "mean_literals_per_clause": lits,
+        "mean_nonzero_words_per_clause": entries,
     }
+    # Literal-list evaluation kernel in the tally pre-calculation.  Algorithmic HBM bytes: every
+    # literal row once, the literal lists, previous-output bits and tallies out.  Algorithmic
+    # lane-ops: per clause and word of 32 examples one AND per literal and about 3 for the vote
+    # count.  Neither is what binds it (L1 throughput and instruction issue).
+    pre_ms, n_pre = kt["precalc"]
+    pre_launch_ms = pre_ms / max(1, n_pre)
+    words = (q + 31) // 32
+    pre_bytes = 2 * tm.o * words * 4 + C * lits * 4 + C * words * 4 + tm.m * q * 4
+    pre_ops = C * words * (lits + 3)
+    pre_traffic = None
+    if headline and MEASURED_TRAFFIC["image_like_precalc"]["fetch_kib"] > 0:
+        t = MEASURED_TRAFFIC["image_like_precalc"]
+        pre_traffic = 1024.0 * (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"])
+    roof_eval = {
+        "kernel": "k_eval_sparse (clause evaluation from literal lists + votes, in tm_sync_tallies)",
+        "bound": "hbm",
+        "achieved": pre_bytes / (pre_launch_ms * 1e-3) / 1e9,
+        "peak": HBM_PEAK_GBS,
+        "unit": "GB/s",
+        "frac": pre_bytes / (pre_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "traffic": pre_traffic,
+        "avg_launch_ms": pre_launch_ms,
+        "launches": n_pre,
+        "share_of_timed_region": pre_ms / (1e3 * wall),
+        "hbm_algorithmic_bytes_per_launch": pre_bytes,
+        "algorithmic_lane_ops_per_launch": pre_ops,
+        "alu_frac": pre_ops / (pre_launch_ms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
+        "l1_bytes_per_launch": C * words * (4 * ((lits + 3) // 4)) * 4,
+        "clause_evals_per_s": q * C / (pre_launch_ms * 1e-3),
+    }
+    inf_ms, n_inf = kt["infer"]
+    out["config"]["infer_kernel_ms"] = inf_ms / max(1, n_inf)
+    # "roofline" is the kernel with the larger share of the timed region
+    if train_ms >= pre_ms:
+        out["roofline"], out["roofline_other"] = roof_train, roof_eval
+    else:
+        out["roofline"], out["roofline_other"] = roof_eval, roof_train
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(hp, Xtr, ytr, Xte, args.seed)
     print(json.dumps(out))

@@ -175,16 +175,30 @@ int tm_set_epoch(tm_handle *h, uint32_t epoch);
 int tm_get_epoch(tm_handle *h, uint32_t *epoch);
 
 /* Device-side event counters of the training kernel since the last call of
- * this function (or since tm_bind_train): out is HOST uint64 [8]:
+ * this function (or since tm_bind_train): out is HOST uint64 [9]:
  * [0] visited (clause, example) pairs, [1] fired gates, [2] Type I feedbacks,
  * [3] tally changes, [4] pairs whose class was trained for the example (gate
  * candidates), [5] Type II feedbacks given to a clause with output 1,
  * [6] blocks of 64 examples that a clause had to evaluate (blocks whose stored
  * outputs are known to be current and in which no gate fires are skipped),
  * [7] gate candidates whose error e was positive both at the start of the
- * launch and at the visit (a random draw was needed).
+ * launch and at the visit (a random draw was needed),
+ * [8] those of the blocks of [6] that were evaluated 32 at a time through the
+ * clause's literal list (outdated blocks of a sparse clause in which no gate
+ * fired) rather than one by one from its include masks.
  * Synchronises the stream. */
 int tm_read_counters(tm_handle *h, uint64_t *out, void *stream);
+
+/* Kernel timing (measurement aid).  While enabled, every launch of the training
+ * kernel (kind 0) and of the literal-list evaluation kernel (kind 1: in the
+ * tally pre-calculation, kind 2: in tm_class_sums_ws / tm_predict_ws) is
+ * bracketed by two events on its stream.  tm_read_kernel_timing waits for the
+ * recorded events and returns, per kind, the summed kernel time in ms[3] and
+ * the number of launches in launches[3] (both HOST arrays) since the last read
+ * or enable, and forgets them.  Enabling or disabling forgets what was
+ * recorded. */
+int tm_kernel_timing(tm_handle *h, int enable);
+int tm_read_kernel_timing(tm_handle *h, double *ms, int64_t *launches);
 
 /* Text for an error code; hipError_t of the last failed HIP call on a handle. */
 const char *tm_strerror(int code);

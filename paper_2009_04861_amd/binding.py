@@ -19,7 +19,7 @@ EXPORTS = [
     "tm_state_bytes", "tm_train_ws_bytes", "tm_create", "tm_destroy", "tm_bind_train", "tm_fit_epoch",
     "tm_class_sums", "tm_predict", "tm_infer_ws_bytes", "tm_class_sums_ws", "tm_predict_ws", "tm_get_ta_state", "tm_set_ta_state", "tm_clause_outputs",
     "tm_sync_tallies", "tm_get_tallies", "tm_get_prev_outputs", "tm_feedback_step", "tm_train_chunk", "tm_set_epoch",
-    "tm_get_epoch", "tm_read_counters", "tm_strerror", "tm_last_hip_error",
+    "tm_get_epoch", "tm_read_counters", "tm_kernel_timing", "tm_read_kernel_timing", "tm_strerror", "tm_last_hip_error",
 ]
 
 
@@ -184,12 +184,24 @@ def tm_get_epoch(h):
     return e.value
 
 
+def tm_kernel_timing(h, enable):
+    _check(lib().tm_kernel_timing(h, ctypes.c_int(1 if enable else 0)), "tm_kernel_timing")
+
+
+def tm_read_kernel_timing(h):
+    """{"train" | "precalc" | "infer": (ms, launches)} since the last read."""
+    ms = (ctypes.c_double * 3)()
+    n = (ctypes.c_int64 * 3)()
+    _check(lib().tm_read_kernel_timing(h, ms, n), "tm_read_kernel_timing")
+    return {"train": (ms[0], n[0]), "precalc": (ms[1], n[1]), "infer": (ms[2], n[2])}
+
+
 def tm_read_counters(h):
-    out = (ctypes.c_uint64 * 8)()
+    out = (ctypes.c_uint64 * 9)()
     _check(lib().tm_read_counters(h, out, _stream()), "tm_read_counters")
     return {"pairs": out[0], "fired": out[1], "type1": out[2], "tally_changes": out[3],
             "candidates": out[4], "type2_active": out[5], "blocks_evaluated": out[6],
-            "gate_draws": out[7]}
+            "gate_draws": out[7], "blocks_listed": out[8]}
 
 
 class TsetlinMachine:

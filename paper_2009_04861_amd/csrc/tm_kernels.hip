@@ -32,6 +32,7 @@
 #include <new>
 #include <stdint.h>
 #include <string.h>
+#include <vector>
 
 #include "../../include/tm.h"
 #include "tm_device.hpp"
@@ -799,7 +800,10 @@ __global__ __launch_bounds__(64 * SP_WAVES) void k_eval_sparse(const uint32_t *_
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 // past a list's end: the all-ones row.  Row offset (uniform) + word offset (per lane)
-                // are added in the vector unit: one operation instead of a 64-bit scalar add per load
+                // are added in the vector unit: one operation instead of a 64-bit scalar add per
+                // load.  (Buffer loads that take the row offset as their scalar offset need no add
+                // at all, but measured 45 % slower: the list entries then sit in scalar registers
+                // until their load is issued, and too few list loads stay in flight.)
                 const uint4 e = *reinterpret_cast<const uint4 *>(L[u] + k);
                 r[u][0] = *reinterpret_cast<const uint32_t *>(xb_base + (e.x + word_off));
                 r[u][1] = *reinterpret_cast<const uint32_t *>(xb_base + (e.y + word_off));
@@ -1053,7 +1057,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     const uint32_t ge_init = d.thr >= 65536u ? 0u : ~0u;
 
     // per-wavefront event counts of one launch fit 32 bits (at most 2^30 examples per launch)
-    uint32_t n_fired = 0, n_type1 = 0, n_changes = 0, n_type2 = 0, n_eval = 0, n_draw = 0;
+    uint32_t n_fired = 0, n_type1 = 0, n_changes = 0, n_type2 = 0, n_eval = 0, n_draw = 0, n_listed_blocks = 0;
 
     // Which stored previous outputs o* can differ from the clause's current output: only
     // those not re-evaluated since the include mask last changed.  Kept per clause as two
@@ -1162,6 +1166,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
             }
         }
         n_eval += (uint32_t)(be - bs);
+        n_listed_blocks += (uint32_t)(be - bs);
         // the whole blocks among them are up to date again
         const int fs = max(bs, (i_begin + 63) >> 6), fe = (i_end == q) ? be : min(be, i_end >> 6);
         if (fs < fe) {
@@ -1410,8 +1415,8 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     n_changes += n_changes_v;
     // event counters: 64 interleaved sets, because thousands of wavefronts ending at the
     // same time on one address serialise in the L2 atomic unit (measured: ~1.7 ms per launch)
-    if (lane >= 1 && lane < 8) {
-        const uint32_t v = lane == 1 ? n_fired : lane == 2 ? n_type1 : lane == 3 ? n_changes
+    if (lane < 8) { // slot 4 (trained pairs) is counted by the launch preparation
+        const uint32_t v = lane == 0 ? n_listed_blocks : lane == 1 ? n_fired : lane == 2 ? n_type1 : lane == 3 ? n_changes
                          : lane == 4 ? 0u : lane == 5 ? n_type2 : lane == 6 ? n_eval : n_draw;
         if (v) atomicAdd(&a.counters[(g & (COUNTER_SETS - 1)) * 8 + lane], (unsigned long long)v);
     }
@@ -1453,6 +1458,11 @@ struct tm_handle {
     uint32_t epoch;
     uint64_t pairs_visited; // (clause, example) visits enqueued since the counters were last read
     int last_hip;
+    // kernel timing (measurement aid): event pairs around the launches of the two main kernels
+    bool timing;
+    std::vector<hipEvent_t> ev_pool;  // events created so far, reused
+    size_t ev_used;                   // events of the pool handed out since timing was switched on
+    std::vector<int> ev_kind;         // kind of the k-th recorded pair (events 2k, 2k+1)
 };
 
 namespace {
@@ -1544,6 +1554,24 @@ inline int hip_fail(tm_handle *h, hipError_t e)
     } while (0)
 
 inline unsigned blocks_for(int64_t n, int bs) { return (unsigned)((n + bs - 1) / bs); }
+
+enum { TIMED_TRAIN = 0, TIMED_PRECALC = 1, TIMED_INFER = 2, TIMED_KINDS = 3 };
+
+// Records an event on the stream when kernel timing is on: called before (first = true)
+// and after the launch of a timed kernel.
+int timing_mark(tm_handle *h, int kind, bool first, hipStream_t st)
+{
+    if (!h->timing) return TM_OK;
+    if (h->ev_used == h->ev_pool.size()) {
+        hipEvent_t e;
+        TM_HIP(h, hipEventCreate(&e));
+        h->ev_pool.push_back(e);
+    }
+    TM_HIP(h, hipEventRecord(h->ev_pool[h->ev_used++], st));
+    if (first) h->ev_kind.push_back(kind);
+    return TM_OK;
+}
+
 
 int fill(tm_handle *h, void *p, size_t bytes, uint32_t v, hipStream_t st)
 {
@@ -1639,7 +1667,8 @@ int build_xb(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *XB, hipStream
 // here from the current masks); writes bits and/or the class sums.  With clampT > 0 the
 // sums are clamped.  acc need not be zeroed by the caller.
 int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *lits, int32_t *nlit, uint32_t *bits,
-                       int64_t bits_stride, int32_t *acc, int64_t acc_si, int64_t acc_sc, int clampT, hipStream_t st)
+                       int64_t bits_stride, int32_t *acc, int64_t acc_si, int64_t acc_sc, int clampT, int timed_kind,
+                       hipStream_t st)
 {
     const Dims &d = h->d;
     const int64_t QW = xb_row_words(q);
@@ -1668,9 +1697,13 @@ int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *li
             if (rc) return rc;
         }
     }
+    int rc = timing_mark(h, timed_kind, true, st);
+    if (rc) return rc;
     hipLaunchKernelGGL(k_eval_sparse, dim3((unsigned)ranges, (unsigned)(d.m * S)), dim3(64 * SP_WAVES), 0, st, lits, nlit,
                        h->inc, XB, a);
     TM_HIP(h, hipGetLastError());
+    rc = timing_mark(h, timed_kind, false, st);
+    if (rc) return rc;
     if (acc && S > 1 && clampT > 0) {
         hipLaunchKernelGGL(k_clamp, dim3(blocks_for(q * d.m, 256)), dim3(256), 0, st, acc, q * d.m, clampT);
         TM_HIP(h, hipGetLastError());
@@ -1723,6 +1756,8 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
         TM_HIP(h, hipGetLastError());
         hipLaunchKernelGGL(k_launch_prep<true>, pgrid, dim3(1024), 0, st, pa);
         TM_HIP(h, hipGetLastError());
+        int rc = timing_mark(h, TIMED_TRAIN, true, st);
+        if (rc) return rc;
         if (wpl <= 1) launch_train_t<1>(p, a, full, st);
         else if (wpl <= 2) launch_train_t<2>(p, a, full, st);
         else if (wpl <= 3) launch_train_t<3>(p, a, full, st);
@@ -1735,6 +1770,8 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
         else if (wpl <= 20) launch_train_t<20>(p, a, full, st);
         else return TM_ELIMIT;
         TM_HIP(h, hipGetLastError());
+        rc = timing_mark(h, TIMED_TRAIN, false, st);
+        if (rc) return rc;
     }
     return TM_OK;
 }
@@ -1757,7 +1794,7 @@ int fresh_set(tm_handle *h, bool all_stale, hipStream_t st)
 
 int sync_tallies(tm_handle *h, hipStream_t st)
 {
-    const int rc = launch_eval_sparse(h, h->XB, h->q, h->lits, h->nlit, h->ostar, h->Qw, h->tally, 1, h->qp, 0, st);
+    const int rc = launch_eval_sparse(h, h->XB, h->q, h->lits, h->nlit, h->ostar, h->Qw, h->tally, 1, h->qp, 0, TIMED_PRECALC, st);
     if (rc) return rc;
     return fresh_set(h, false, st); // every stored output is current
 }
@@ -1790,9 +1827,8 @@ int tm_create(const tm_config *cfg, void *state_buf, void *stream, tm_handle **o
     const int rc = check_config(cfg);
     if (rc) return rc;
     if (!state_buf || !out || ((uintptr_t)state_buf & 255)) return TM_EINVAL;
-    tm_handle *h = new (std::nothrow) tm_handle;
+    tm_handle *h = new (std::nothrow) tm_handle(); // every member zero, the vectors empty
     if (!h) return TM_EINVAL;
-    memset(h, 0, sizeof(*h));
     h->cfg = *cfg;
     h->d = make_dims(cfg);
     const uint32_t top = (uint32_t)(127 + h->d.N), bottom = (uint32_t)(128 - h->d.N);
@@ -1822,6 +1858,7 @@ int tm_create(const tm_config *cfg, void *state_buf, void *stream, tm_handle **o
 int tm_destroy(tm_handle *h)
 {
     if (!h) return TM_EINVAL;
+    for (hipEvent_t e : h->ev_pool) (void)hipEventDestroy(e);
     delete h;
     return TM_OK;
 }
@@ -1968,7 +2005,7 @@ int tm_class_sums_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, 
     int32_t *nlit = (int32_t *)(base + align256(xb_bytes(d, q)) + align256((size_t)d.C * LIT_MAX * 4));
     const int rc = build_xb(h, X, q, XB, st);
     if (rc) return rc;
-    return launch_eval_sparse(h, XB, q, lits, nlit, nullptr, 0, sums, d.m, 1, d.T, st);
+    return launch_eval_sparse(h, XB, q, lits, nlit, nullptr, 0, sums, d.m, 1, d.T, TIMED_INFER, st);
 }
 
 int tm_predict_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, int32_t *sums_scratch, void *ws,
@@ -2069,6 +2106,36 @@ int tm_get_epoch(tm_handle *h, uint32_t *epoch)
     return TM_OK;
 }
 
+int tm_kernel_timing(tm_handle *h, int enable)
+{
+    if (!h) return TM_EINVAL;
+    h->timing = enable != 0;
+    h->ev_used = 0;
+    h->ev_kind.clear();
+    return TM_OK;
+}
+
+int tm_read_kernel_timing(tm_handle *h, double *ms, int64_t *launches)
+{
+    if (!h || !ms || !launches) return TM_EINVAL;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    for (int k = 0; k < TIMED_KINDS; ++k) {
+        ms[k] = 0.0;
+        launches[k] = 0;
+    }
+    for (size_t k = 0; k < h->ev_kind.size(); ++k) {
+        if (2 * k + 1 >= h->ev_used) break; // a launch that failed between its two marks
+        float t = 0.f;
+        TM_HIP(h, hipEventSynchronize(h->ev_pool[2 * k + 1]));
+        TM_HIP(h, hipEventElapsedTime(&t, h->ev_pool[2 * k], h->ev_pool[2 * k + 1]));
+        ms[h->ev_kind[k]] += (double)t;
+        launches[h->ev_kind[k]] += 1;
+    }
+    h->ev_used = 0;
+    h->ev_kind.clear();
+    return TM_OK;
+}
+
 int tm_read_counters(tm_handle *h, uint64_t *out, void *stream)
 {
     if (!h || !out) return TM_EINVAL;
@@ -2082,6 +2149,7 @@ int tm_read_counters(tm_handle *h, uint64_t *out, void *stream)
         out[k] = 0;
         for (int c = 0; c < COUNTER_SETS; ++c) out[k] += tmp[c * 8 + k];
     }
+    out[8] = out[0];           // device slot 0: blocks evaluated through literal lists
     out[0] = h->pairs_visited; // every clause visits every example of a pass; known on the host
     h->pairs_visited = 0;
     return fill(h, h->counters, (size_t)COUNTER_SETS * 64, 0u, st);
