@@ -44,13 +44,13 @@ GATE_OPS = PHILOX_OPS + 8                                # one block + clip, err
 # HBM traffic per launch in the timed (steady) epochs of the default workload, from two separate
 # `rocprofv3 --pmc` runs of this program (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch, averaged
 # over the timed launches).  The scale factors come from the same counters read for a plain
-# 1 GiB device copy in the same runs (--calibration-copy): FETCH_SIZE reads 524,310 KiB for
+# 1 GiB device copy in the same runs (--calibration-copy): FETCH_SIZE reads 524,309 KiB for
 # 1,048,576 KiB fetched, WRITE_SIZE reads 1,048,576 KiB for 1,048,576 KiB written.  Summaries are
 # under profiles/.
 MEASURED_TRAFFIC = {
-    "image_like_train": {"fetch_kib": 0.0, "fetch_scale": 2.0, "write_kib": 0.0, "write_scale": 1.0},
+    "image_like_train": {"fetch_kib": 163707.0, "fetch_scale": 2.0, "write_kib": 98381.0, "write_scale": 1.0},
     # k_eval_sparse in tm_sync_tallies
-    "image_like_precalc": {"fetch_kib": 0.0, "fetch_scale": 2.0, "write_kib": 0.0, "write_scale": 1.0},
+    "image_like_precalc": {"fetch_kib": 58644.0, "fetch_scale": 2.0, "write_kib": 160625.0, "write_scale": 1.0},
 }
 
 
