@@ -905,10 +905,10 @@ constexpr int EVAL_PAD = 16; // empty entries after the list: a group may read t
 // plain or negated mask word is non-zero, compacted in LDS: eoff[k] = byte
 // offset of that word's row in XT, emask[k] = {mask of plain literals, mask of
 // negated literals}; padded with EVAL_PAD empty entries.  Rebuilt whenever plane 7
-// changes.  *lit_count (LDS) receives the number of included literals.
+// changes.  n_literals receives the number of included literals (narrow clauses only).
 template <int WPL>
 __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lmask, uint32_t *eoff,
-                                             uint2 *emask, uint32_t *lit_count, int lane, int Wf, int W,
+                                             uint2 *emask, int &n_literals, int lane, int Wf, int W,
                                              uint32_t row_bytes)
 {
 #pragma unroll
@@ -916,10 +916,9 @@ __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lm
         const int lw = r * 64 + lane;
         if (lw < W) lmask[lw] = p[r][7];
     }
-    if (lane == 0) *lit_count = 0u;
     wave_lds_sync();
     int n = 0;
-    uint32_t lits = 0;
+    n_literals = 0;
     for (int f0 = 0; f0 < Wf; f0 += 64) {
         const int fw = f0 + lane;
         const bool ok = fw < Wf;
@@ -932,10 +931,17 @@ __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lm
             eoff[n + pre] = (uint32_t)fw * row_bytes;
             emask[n + pre] = make_uint2(mp, mn);
         }
-        lits += (uint32_t)(__builtin_popcount(mp) + __builtin_popcount(mn));
+        if (WPL <= 4) {
+            // included literals of the clause (only narrow clauses use it): the per-lane counts are
+            // summed bit by bit with ballots - a loop-free wave sum (an atomic on one LDS word is
+            // turned by the compiler into a 64-step scalar loop over the lanes)
+            const uint32_t cnt = (uint32_t)(__builtin_popcount(mp) + __builtin_popcount(mn)); // 0..64
+#pragma unroll
+            for (int bit = 0; bit < 7; ++bit)
+                n_literals += __builtin_popcountll(ballot(((cnt >> bit) & 1u) != 0u)) << bit;
+        }
         n += __builtin_popcountll(b);
     }
-    if (lits) atomicAdd(lit_count, lits); // number of included literals of the clause, summed in LDS
     if (lane < EVAL_PAD) {
         eoff[n + lane] = 0u;
         emask[n + lane] = make_uint2(0u, 0u);
@@ -1037,8 +1043,8 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     uint32_t *lmask = lds + wave * a.lds_wave_words;        // [W] include masks, literal-word order
     uint32_t *eoff = lmask + a.lds_mask_words;              // [Wf + EVAL_PAD] (rounded to 4 words)
     uint2 *emask = reinterpret_cast<uint2 *>(eoff + a.lds_off_words);
-    uint32_t *llist = lmask + a.lds_wave_words - (TRAIN_LIT_MAX + 8); // [TRAIN_LIT_MAX + 4] literal list for the sweeps
-    uint32_t *lit_count = llist + TRAIN_LIT_MAX + 4;                   // number of included literals
+    uint32_t *llist = lmask + a.lds_wave_words - (TRAIN_LIT_MAX + 4); // [TRAIN_LIT_MAX + 4] literal list for the sweeps
+    int n_literals = 0;                                                // included literals of the clause (narrow clauses)
 
     const int c = g / d.n;
     const bool pos = ((g - c * d.n) & 1) != 0; // odd index within the class: positive polarity
@@ -1060,7 +1066,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
         }
         p[r] = t;
     }
-    int nent = build_entries<WPL>(p, lmask, eoff, emask, lit_count, lane, d.Wf, d.W, row_bytes);
+    int nent = build_entries<WPL>(p, lmask, eoff, emask, n_literals, lane, d.Wf, d.W, row_bytes);
 
     // lowest Philox block of the Type I comparator that can matter: bits of the
     // uniform below the lowest set bit of thr never decide u < thr
@@ -1200,7 +1206,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
         // The list pays for runs of blocks: a few blocks, or a list that the last mask change
         // left to be rebuilt for a short run, are cheaper block by block below; so are wide
         // clauses (their registers hold the automata) and untrained ones (hundreds of literals).
-        if (WPL <= 4 && n_blocks >= (n_listed < 0 ? 8 : 3) && (int)*lit_count <= TRAIN_LIT_MAX) {
+        if (WPL <= 4 && n_blocks >= (n_listed < 0 ? 8 : 3) && n_literals <= TRAIN_LIT_MAX) {
             if (n_listed < 0) n_listed = build_literals<WPL>(p, llist, lane, d.Wf, d.W, d.o, (uint32_t)a.QW * 4u);
             if (s1 < e1) sweep_listed(s1, e1);
             if (s2 < to) sweep_listed(s2, to);
@@ -1401,7 +1407,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
             if (ballot(changed != 0u)) { // the conjunction changed: re-evaluate this and the later examples of the block
                 mask_changed = true;
                 n_listed = -1;
-                nent = build_entries<WPL>(p, lmask, eoff, emask, lit_count, lane, d.Wf, d.W, row_bytes);
+                nent = build_entries<WPL>(p, lmask, eoff, emask, n_literals, lane, d.Wf, d.W, row_bytes);
                 const uint64_t nb = eval64(eoff, emask, nent, XT + (cb << 6), lane);
                 const uint64_t keep = (1ull << bl) - 1ull;
                 obits = (obits & keep) | (nb & ~keep);
@@ -1751,7 +1757,7 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     a.q = (int32_t)h->q; a.qp = (int32_t)h->qp; a.Qw = (int32_t)h->Qw; a.epoch = h->epoch;
     a.lds_mask_words = (d.W + 3) & ~3;
     a.lds_off_words = (d.Wf + EVAL_PAD + 3) & ~3;
-    a.lds_wave_words = a.lds_mask_words + a.lds_off_words + 2 * ((d.Wf + EVAL_PAD + 1) & ~1) + TRAIN_LIT_MAX + 8;
+    a.lds_wave_words = a.lds_mask_words + a.lds_off_words + 2 * ((d.Wf + EVAL_PAD + 1) & ~1) + TRAIN_LIT_MAX + 4;
     a.QW = (int)xb_row_words(h->q);
     const bool full = (d.N == 128);
     const int wpl = (d.W + 63) / 64;
