@@ -905,11 +905,10 @@ constexpr int EVAL_PAD = 16; // empty entries after the list: a group may read t
 // plain or negated mask word is non-zero, compacted in LDS: eoff[k] = byte
 // offset of that word's row in XT, emask[k] = {mask of plain literals, mask of
 // negated literals}; padded with EVAL_PAD empty entries.  Rebuilt whenever plane 7
-// changes.  n_literals receives the number of included literals (narrow clauses only).
+// changes.
 template <int WPL>
 __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lmask, uint32_t *eoff,
-                                             uint2 *emask, int &n_literals, int lane, int Wf, int W,
-                                             uint32_t row_bytes)
+                                             uint2 *emask, int lane, int Wf, int W, uint32_t row_bytes)
 {
 #pragma unroll
     for (int r = 0; r < WPL; ++r) {
@@ -918,7 +917,6 @@ __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lm
     }
     wave_lds_sync();
     int n = 0;
-    n_literals = 0;
     for (int f0 = 0; f0 < Wf; f0 += 64) {
         const int fw = f0 + lane;
         const bool ok = fw < Wf;
@@ -930,15 +928,6 @@ __device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lm
         if (nzf) {
             eoff[n + pre] = (uint32_t)fw * row_bytes;
             emask[n + pre] = make_uint2(mp, mn);
-        }
-        if (WPL <= 4) {
-            // included literals of the clause (only narrow clauses use it): the per-lane counts are
-            // summed bit by bit with ballots - a loop-free wave sum (an atomic on one LDS word is
-            // turned by the compiler into a 64-step scalar loop over the lanes)
-            const uint32_t cnt = (uint32_t)(__builtin_popcount(mp) + __builtin_popcount(mn)); // 0..64
-#pragma unroll
-            for (int bit = 0; bit < 7; ++bit)
-                n_literals += __builtin_popcountll(ballot(((cnt >> bit) & 1u) != 0u)) << bit;
         }
         n += __builtin_popcountll(b);
     }
@@ -988,6 +977,22 @@ __device__ __forceinline__ uint64_t eval64(const uint32_t *eoff, const uint2 *em
 // Literals a clause's list in LDS can hold for the sweeps over outdated outputs; clauses
 // with more (untrained ones) are swept block by block with eval64.
 constexpr int TRAIN_LIT_MAX = 64;
+
+// Number of included literals of the clause held in p: the per-lane counts are summed bit by
+// bit with ballots, a loop-free wave sum.  (An atomic add on one LDS word would do, but the
+// compiler expands it into a 64-step scalar loop over the lanes.)
+template <int WPL>
+__device__ __forceinline__ int count_literals(const u32x8 (&p)[WPL], int lane, int W)
+{
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int r = 0; r < WPL; ++r) cnt += (r * 64 + lane < W) ? (uint32_t)__builtin_popcount(p[r][7]) : 0u;
+    int total = 0;
+#pragma unroll
+    for (int bit = 0; bit < 8; ++bit) // cnt <= 32 * WPL <= 128 for the narrow clauses this is used for
+        total += __builtin_popcountll(ballot(((cnt >> bit) & 1u) != 0u)) << bit;
+    return total;
+}
 
 // List of the included literals of the clause held in p (lane = literal word), as byte
 // offsets of their rows in XB, padded to a multiple of 4 with the all-ones row; returns
@@ -1044,7 +1049,6 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     uint32_t *eoff = lmask + a.lds_mask_words;              // [Wf + EVAL_PAD] (rounded to 4 words)
     uint2 *emask = reinterpret_cast<uint2 *>(eoff + a.lds_off_words);
     uint32_t *llist = lmask + a.lds_wave_words - (TRAIN_LIT_MAX + 4); // [TRAIN_LIT_MAX + 4] literal list for the sweeps
-    int n_literals = 0;                                                // included literals of the clause (narrow clauses)
 
     const int c = g / d.n;
     const bool pos = ((g - c * d.n) & 1) != 0; // odd index within the class: positive polarity
@@ -1066,7 +1070,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
         }
         p[r] = t;
     }
-    int nent = build_entries<WPL>(p, lmask, eoff, emask, n_literals, lane, d.Wf, d.W, row_bytes);
+    int nent = build_entries<WPL>(p, lmask, eoff, emask, lane, d.Wf, d.W, row_bytes);
 
     // lowest Philox block of the Type I comparator that can matter: bits of the
     // uniform below the lowest set bit of thr never decide u < thr
@@ -1151,7 +1155,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     // to the next fired gate, most of what an epoch of a trained machine has to evaluate.
     // A trained clause has few literals, so the sweep walks its literal list over the rows
     // of XB, lane = word of 32 examples: 2048 examples per pass and one load per literal.
-    int n_listed = -1;          // literals of the current masks, -1: list not built since the last change
+    int n_listed = -1;          // literals of the current masks (list built if <= TRAIN_LIT_MAX), -1: not counted since the last change
     uint32_t n_changes_v = 0;   // tally changes found by the passes, per lane
     const char *xb_base = reinterpret_cast<const char *>(XB);
     uint32_t *ostar_row = a.ostar + (int64_t)g * a.Qw;
@@ -1206,11 +1210,16 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
         // The list pays for runs of blocks: a few blocks, or a list that the last mask change
         // left to be rebuilt for a short run, are cheaper block by block below; so are wide
         // clauses (their registers hold the automata) and untrained ones (hundreds of literals).
-        if (WPL <= 4 && n_blocks >= (n_listed < 0 ? 8 : 3) && n_literals <= TRAIN_LIT_MAX) {
-            if (n_listed < 0) n_listed = build_literals<WPL>(p, llist, lane, d.Wf, d.W, d.o, (uint32_t)a.QW * 4u);
-            if (s1 < e1) sweep_listed(s1, e1);
-            if (s2 < to) sweep_listed(s2, to);
-            return;
+        if (WPL <= 4 && n_blocks >= (n_listed < 0 ? 8 : 3)) {
+            if (n_listed < 0) {
+                n_listed = count_literals<WPL>(p, lane, d.W);
+                if (n_listed <= TRAIN_LIT_MAX) build_literals<WPL>(p, llist, lane, d.Wf, d.W, d.o, (uint32_t)a.QW * 4u);
+            }
+            if (n_listed <= TRAIN_LIT_MAX) {
+                if (s1 < e1) sweep_listed(s1, e1);
+                if (s2 < to) sweep_listed(s2, to);
+                return;
+            }
         }
         for (int b = next_stale(from); b < to; b = next_stale(b + 1)) { // closing b does not change which later blocks are outdated
             const uint32_t *op = ostar_row + (b << 1);
@@ -1407,7 +1416,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
             if (ballot(changed != 0u)) { // the conjunction changed: re-evaluate this and the later examples of the block
                 mask_changed = true;
                 n_listed = -1;
-                nent = build_entries<WPL>(p, lmask, eoff, emask, n_literals, lane, d.Wf, d.W, row_bytes);
+                nent = build_entries<WPL>(p, lmask, eoff, emask, lane, d.Wf, d.W, row_bytes);
                 const uint64_t nb = eval64(eoff, emask, nent, XT + (cb << 6), lane);
                 const uint64_t keep = (1ull << bl) - 1ull;
                 obits = (obits & keep) | (nb & ~keep);
