@@ -106,6 +106,31 @@ def test_literal_list_lengths_and_dense_clauses(q, device):
     assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ora.clause_outputs(X).T)
 
 
+@pytest.mark.parametrize("n", [4080, 4082, 9000])
+def test_vote_counters_at_capacity(n, device):
+    """Every positive clause of class 0 is satisfied by every example and no negative one is:
+    the bit-sliced vote counters of the literal-list kernel hold their largest counts (255
+    clauses per wavefront at n = 4080; more clauses split a class over several workgroups)."""
+    m, o, N, T, q = 2, 8, 128, 3000, 100
+    print("vote counters", n, flush=True)
+    rng = np.random.default_rng(n)
+    ora, gpu = make_pair(m, n, o, N, T, 4.0, 5)
+    st = np.ones((ora.C, ora.L), dtype=np.int32)
+    st[0:n:2, 0] = 2 * N          # negative clauses of class 0: x0 AND NOT x0
+    st[0:n:2, o] = 2 * N
+    st[n + 1:2 * n:4, 1] = 2 * N  # some positive clauses of class 1: x1
+    ora.state[:] = st
+    push_state(gpu, ora.state)
+    X, y = rand_problem(rng, q, o, m)
+    Xd = dev_bits(gpu, X)
+    want = ora.class_sums(X)
+    assert want[:, 0].max() == min(T, n // 2)
+    for lists in (True, False):
+        assert np.array_equal(gpu.class_sums(Xd, lists=lists).cpu().numpy(), want)
+    gpu.bind_train(Xd, dev_i32(gpu, y))
+    assert np.array_equal(gpu.tallies().cpu().numpy(), ora.class_sums(X, clamp=False))
+
+
 def test_class_sums_are_clamped(device):
     ora, gpu = make_pair(2, 64, 20, 128, 5, 3.0, 3)
     ora.state[:] = 1
