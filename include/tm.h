@@ -108,6 +108,13 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
  * Advances the handle's epoch counter (part of the random counter) by one. */
 int tm_fit_epoch(tm_handle *h, void *stream);
 
+/* Algorithm 1 on one batch: the examples i0 .. i0+cnt-1 of the bound set (the
+ * paper's batch size b = cnt), gated on the live tallies like tm_fit_epoch.
+ * Uses the current epoch counter without advancing it (tm_set_epoch), so that an
+ * epoch can be walked in batches with tm_sync_tallies or other work in between:
+ * how often the tallies are recomputed is the caller's choice. */
+int tm_fit_batch(tm_handle *h, int64_t i0, int64_t cnt, void *stream);
+
 /* Eq. 3 per class, clamped to [-T, T]: sums device int32 [q][m].
  * X need not be the bound training set.  q may be 0. */
 int tm_class_sums(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, void *stream);

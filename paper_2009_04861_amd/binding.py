@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG, "libtm_hip.so")
 TM_OK, TM_EINVAL, TM_ESTATE, TM_EHIP, TM_ELIMIT = 0, -1, -2, -3, -4
 
 EXPORTS = [
-    "tm_state_bytes", "tm_train_ws_bytes", "tm_create", "tm_destroy", "tm_bind_train", "tm_fit_epoch",
+    "tm_state_bytes", "tm_train_ws_bytes", "tm_create", "tm_destroy", "tm_bind_train", "tm_fit_epoch", "tm_fit_batch",
     "tm_class_sums", "tm_predict", "tm_infer_ws_bytes", "tm_class_sums_ws", "tm_predict_ws", "tm_get_ta_state", "tm_set_ta_state", "tm_clause_outputs",
     "tm_sync_tallies", "tm_get_tallies", "tm_get_prev_outputs", "tm_feedback_step", "tm_train_chunk", "tm_set_epoch",
     "tm_get_epoch", "tm_read_counters", "tm_kernel_timing", "tm_read_kernel_timing", "tm_strerror", "tm_last_hip_error",
@@ -110,6 +110,10 @@ def tm_bind_train(h, X, y, ws):
 
 def tm_fit_epoch(h):
     _check(lib().tm_fit_epoch(h, _stream()), "tm_fit_epoch")
+
+
+def tm_fit_batch(h, i0, cnt):
+    _check(lib().tm_fit_batch(h, ctypes.c_int64(i0), ctypes.c_int64(cnt), _stream()), "tm_fit_batch")
 
 
 def tm_class_sums(h, X, sums):
@@ -254,6 +258,10 @@ class TsetlinMachine:
     def fit_epoch(self):
         with torch.cuda.device(self.dev):
             tm_fit_epoch(self.h)
+
+    def fit_batch(self, i0, cnt):
+        with torch.cuda.device(self.dev):
+            tm_fit_batch(self.h, i0, cnt)
 
     def feedback_step(self, snapshot, i0, cnt):
         with torch.cuda.device(self.dev):

@@ -1966,6 +1966,21 @@ int tm_fit_epoch(tm_handle *h, void *stream)
     return TM_OK;
 }
 
+int tm_fit_batch(tm_handle *h, int64_t i0, int64_t cnt, void *stream)
+{
+    if (!h || i0 < 0 || cnt < 0) return TM_EINVAL;
+    if (!h->bound) return TM_ESTATE;
+    if (i0 > h->q) return TM_EINVAL;
+    if (h->epoch >= (1u << 24)) return TM_ELIMIT;
+    hipStream_t st = (hipStream_t)stream;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    const int64_t i_end = (cnt > h->q - i0) ? h->q : i0 + cnt;
+    int rc = run_negcls(h, st);
+    if (rc) return rc;
+    if (i_end <= i0) return TM_OK;
+    return launch_train(h, nullptr, i0, i_end, st);
+}
+
 int tm_feedback_step(tm_handle *h, const int32_t *tally_snapshot, int64_t i0, int64_t cnt, void *stream)
 {
     if (!h || !tally_snapshot || i0 < 0 || cnt < 0) return TM_EINVAL;

@@ -340,6 +340,40 @@ def test_async_epoch_invariants(shape, device):
     assert c["pairs"] == 4 * q * ora.C and 0 < c["fired"] < c["pairs"]
 
 
+def test_epochs_walked_in_batches(device):
+    """Algorithm 1 batch by batch (tm_fit_batch, b = 250) with the tallies recomputed after every
+    batch: the bookkeeping invariants hold after every batch, the epoch counter is the caller's,
+    and the noisy-XOR machine learns as it does with whole-epoch passes."""
+    hp = synth.WORKLOADS["noisy_xor"]
+    Xtr, ytr, Xte, yte = synth.noisy_xor(2000, 2000)
+    ora, gpu = make_pair(seed=9, **hp)
+    m, n, q, b = hp["m"], hp["n"], len(ytr), 250
+    Xd = dev_bits(gpu, Xtr)
+    gpu.bind_train(Xd, dev_i32(gpu, ytr))
+    Xte_d = dev_bits(gpu, Xte)
+    sign = np.where(np.arange(ora.C) % n % 2 == 1, 1, -1)
+    gpu.counters()
+    accs = []
+    for ep in range(40):
+        B.tm_set_epoch(gpu.h, ep)
+        for i0 in range(0, q, b):
+            gpu.fit_batch(i0, b)
+            if ep < 3:
+                ostar = bits_to_u8(gpu.prev_outputs(), q).astype(np.int64)
+                want = np.stack([(ostar[c * n:(c + 1) * n] * sign[c * n:(c + 1) * n, None]).sum(0) for c in range(m)], 1)
+                assert np.array_equal(gpu.tallies().cpu().numpy(), want)
+            gpu.sync_tallies()
+        assert B.tm_get_epoch(gpu.h) == ep
+        if ep >= 30:
+            accs.append((gpu.predict(Xte_d).cpu().numpy() == yte).mean())
+    assert gpu.counters()["pairs"] == 40 * q * ora.C
+    print("accuracy with batches of %d: %.4f" % (b, np.mean(accs)), flush=True)
+    assert np.mean(accs) > 0.85     # 40 % label noise, 2000 examples: whole-epoch passes reach about 0.93 too
+    with pytest.raises(B.TMError) as e:
+        gpu.fit_batch(q + 1, 10)
+    assert e.value.code == B.TM_EINVAL
+
+
 def test_error_codes(device):
     gpu = B.TsetlinMachine(3, 4, 20, 10, 5, 3.0, 1)
     with pytest.raises(B.TMError) as e:
