@@ -181,6 +181,24 @@ __global__ void k_argmax(const int32_t *sums, int32_t *pred, int64_t q, int m)
     pred[i] = best;
 }
 
+// both of the above in one pass over the unclamped sums
+__global__ void k_clamp_argmax(int32_t *sums, int32_t *pred, int64_t q, int m, int T)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= q) return;
+    int best = 0;
+    int32_t bv = 0;
+    for (int c = 0; c < m; ++c) {
+        const int32_t v = min(max(sums[i * m + c], -T), T);
+        sums[i * m + c] = v;
+        if (c == 0 || v > bv) {
+            bv = v;
+            best = c;
+        }
+    }
+    pred[i] = best;
+}
+
 // out[i][c] = tally[c][i]
 __global__ void k_tally_out(const int32_t *tally, int32_t *out, int64_t q, int64_t qp, int m)
 {
@@ -644,12 +662,14 @@ constexpr int SP_PLANES = 8;   // bit planes of a wavefront's vote counter: at m
 // XB from row-major X: one workgroup of 4 wavefronts per 64 examples, each wavefront a
 // contiguous share of the feature words; the 64 ballots of bit b of a word are two words
 // of row 32 fw + b, their complement two words of row o + 32 fw + b.  Examples from q up
-// to 32 QW read as feature 0 (no clause output is taken from them).
+// to 32 QW read as feature 0 (no clause output is taken from them).  Row 2o is set to ones.
 __global__ __launch_bounds__(256) void k_transpose_bits(const uint32_t *__restrict__ X, uint32_t *__restrict__ XB,
                                                         int64_t q, int Wf, int o, int QW)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t i = (int64_t)blockIdx.x * 64 + lane;
+    if (threadIdx.x == 0) // this block's two words of the all-ones row
+        *reinterpret_cast<uint2 *>(XB + (int64_t)2 * o * QW + (int64_t)blockIdx.x * 2) = make_uint2(~0u, ~0u);
     const int per = (Wf + 3) / 4;
     const int f_end = min(Wf, (wave + 1) * per);
     for (int fw = wave * per; fw < f_end; ++fw) {
@@ -676,11 +696,13 @@ __global__ __launch_bounds__(256) void k_transpose_bits(const uint32_t *__restri
 // step.  nlit[g] = number of included literals (may exceed LIT_MAX).
 __global__ __launch_bounds__(256) void k_literal_lists(const uint32_t *__restrict__ inc, uint32_t *__restrict__ lits,
                                                        int32_t *__restrict__ nlit, int C, int Wf, int W, int o,
-                                                       uint32_t row_bytes)
+                                                       uint32_t row_bytes, int32_t *fresh, int qp)
 {
     const int lane = threadIdx.x & 63;
     const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (g >= C) return;
+    // ahead of a tally pre-calculation: every stored output of the clause will be current
+    if (fresh && lane == 0) *reinterpret_cast<int4 *>(fresh + (int64_t)g * 4) = make_int4(0, 0, qp, 0);
     uint32_t *L = lits + (int64_t)g * LIT_MAX;
     int base = 0;
     for (int w0 = 0; w0 < W; w0 += 64) {
@@ -1680,27 +1702,27 @@ void launch_train_t(const TrainPtrs &p, const TrainArgs &a, bool full, hipStream
     else hipLaunchKernelGGL((k_train<WPL, false>), grid, block, lds, st, p.X, p.XT, p.XB, p.gate, p.ngate, a);
 }
 
-// XB (rows of bits over the examples) of q examples given row-major, and its all-ones row.
+// XB (rows of bits over the examples, and the all-ones row) of q examples given row-major.
 int build_xb(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *XB, hipStream_t st)
 {
     const Dims &d = h->d;
     const int64_t QW = xb_row_words(q);
     hipLaunchKernelGGL(k_transpose_bits, dim3((unsigned)(QW / 2)), dim3(256), 0, st, X, XB, q, d.Wf, d.o, (int)QW);
     TM_HIP(h, hipGetLastError());
-    return fill(h, XB + (int64_t)2 * d.o * QW, (size_t)QW * 4, ~0u, st);
+    return TM_OK;
 }
 
 // Evaluation of all clauses on the q examples behind XB from their literal lists (rebuilt
 // here from the current masks); writes bits and/or the class sums.  With clampT > 0 the
 // sums are clamped.  acc need not be zeroed by the caller.
 int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *lits, int32_t *nlit, uint32_t *bits,
-                       int64_t bits_stride, int32_t *acc, int64_t acc_si, int64_t acc_sc, int clampT, int timed_kind,
-                       hipStream_t st)
+                       int64_t bits_stride, int32_t *acc, int64_t acc_si, int64_t acc_sc, int clampT, int32_t *pred,
+                       int32_t *fresh, int timed_kind, hipStream_t st)
 {
     const Dims &d = h->d;
     const int64_t QW = xb_row_words(q);
     hipLaunchKernelGGL(k_literal_lists, dim3(blocks_for(d.C, 4)), dim3(256), 0, st, h->inc, lits, nlit, d.C, d.Wf, d.W,
-                       d.o, (uint32_t)(QW * 4));
+                       d.o, (uint32_t)(QW * 4), fresh, (int)h->qp);
     TM_HIP(h, hipGetLastError());
     SparseArgs a;
     a.bits = bits; a.bits_stride = bits_stride; a.acc = acc; a.acc_si = acc_si; a.acc_sc = acc_sc;
@@ -1734,10 +1756,14 @@ int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *li
     TM_HIP(h, hipGetLastError());
     rc = timing_mark(h, timed_kind, false, st);
     if (rc) return rc;
-    if (acc && S > 1 && clampT > 0) {
+    // what is left: clamp the added-up sums, pick the class
+    if (acc && S > 1 && clampT > 0 && pred)
+        hipLaunchKernelGGL(k_clamp_argmax, dim3(blocks_for(q, 256)), dim3(256), 0, st, acc, pred, q, d.m, clampT);
+    else if (acc && S > 1 && clampT > 0)
         hipLaunchKernelGGL(k_clamp, dim3(blocks_for(q * d.m, 256)), dim3(256), 0, st, acc, q * d.m, clampT);
-        TM_HIP(h, hipGetLastError());
-    }
+    else if (pred)
+        hipLaunchKernelGGL(k_argmax, dim3(blocks_for(q, 256)), dim3(256), 0, st, acc, pred, q, d.m);
+    TM_HIP(h, hipGetLastError());
     return TM_OK;
 }
 
@@ -1824,9 +1850,9 @@ int fresh_set(tm_handle *h, bool all_stale, hipStream_t st)
 
 int sync_tallies(tm_handle *h, hipStream_t st)
 {
-    const int rc = launch_eval_sparse(h, h->XB, h->q, h->lits, h->nlit, h->ostar, h->Qw, h->tally, 1, h->qp, 0, TIMED_PRECALC, st);
-    if (rc) return rc;
-    return fresh_set(h, false, st); // every stored output is current
+    const int rc = launch_eval_sparse(h, h->XB, h->q, h->lits, h->nlit, h->ostar, h->Qw, h->tally, 1, h->qp, 0, nullptr,
+                                      h->fresh /* every stored output is current afterwards */, TIMED_PRECALC, st);
+    return rc;
 }
 
 } // namespace
@@ -2035,7 +2061,8 @@ int tm_infer_ws_bytes(const tm_config *cfg, int64_t q, size_t *out)
     return TM_OK;
 }
 
-int tm_class_sums_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, void *ws, void *stream)
+// class sums (and, with pred, the decision) of q examples through literal lists; ws as tm_infer_ws_bytes
+static int infer_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, int32_t *pred, void *ws, void *stream)
 {
     if (!h || q < 0) return TM_EINVAL;
     if (q == 0) return TM_OK;
@@ -2050,21 +2077,19 @@ int tm_class_sums_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, 
     int32_t *nlit = (int32_t *)(base + align256(xb_bytes(d, q)) + align256((size_t)d.C * LIT_MAX * 4));
     const int rc = build_xb(h, X, q, XB, st);
     if (rc) return rc;
-    return launch_eval_sparse(h, XB, q, lits, nlit, nullptr, 0, sums, d.m, 1, d.T, TIMED_INFER, st);
+    return launch_eval_sparse(h, XB, q, lits, nlit, nullptr, 0, sums, d.m, 1, d.T, pred, nullptr, TIMED_INFER, st);
+}
+
+int tm_class_sums_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, void *ws, void *stream)
+{
+    return infer_ws(h, X, q, sums, nullptr, ws, stream);
 }
 
 int tm_predict_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, int32_t *sums_scratch, void *ws,
                   void *stream)
 {
-    if (!h || q < 0) return TM_EINVAL;
-    if (q == 0) return TM_OK;
-    if (!pred || !sums_scratch) return TM_EINVAL;
-    const int rc = tm_class_sums_ws(h, X, q, sums_scratch, ws, stream);
-    if (rc) return rc;
-    hipLaunchKernelGGL(k_argmax, dim3(blocks_for(q, 256)), dim3(256), 0, (hipStream_t)stream, sums_scratch, pred, q,
-                       h->d.m);
-    TM_HIP(h, hipGetLastError());
-    return TM_OK;
+    if (q > 0 && !pred) return TM_EINVAL;
+    return infer_ws(h, X, q, sums_scratch, pred, ws, stream);
 }
 
 int tm_get_ta_state(tm_handle *h, uint8_t *out, void *stream)
