@@ -318,7 +318,8 @@ def main():
     # Literal-list evaluation kernel in the tally pre-calculation.  Algorithmic HBM bytes: every
     # literal row once, the literal lists, previous-output bits and tallies out.  Algorithmic
     # lane-ops: per clause and word of 32 examples one AND per literal and about 3 for the vote
-    # count.  Neither is what binds it (L1 throughput and instruction issue).
+    # count.  Neither is what binds it: the kernel runs at the rate at which a CU can issue
+    # 4-byte-per-lane loads (about 9.5 clocks each), `l1_bytes_per_launch` is what passes through.
     pre_ms, n_pre = kt["precalc"]
     pre_launch_ms = pre_ms / max(1, n_pre)
     words = (q + 31) // 32
