@@ -251,13 +251,14 @@ def main():
     ops_nominal = train_kernel_ops(cnt, W, lits, entries, nominal=True) / max(1, n_train)
     achieved = ops / (launch_ms * 1e-3) / 1e12
     # algorithmic HBM bytes of one training launch: TA planes in + out and include masks out for
-    # every clause, and the launch's share of the examples (row-major for feedback, word-major
-    # and literal rows for evaluation), previous-output bits in + out, tallies in + out, labels
+    # every clause, the launch's share of the examples (row-major for feedback, word-major and
+    # literal rows for evaluation), tallies in + out, labels, and the previous-output bits of the
+    # blocks that were evaluated, in + out
     chunk = B.tm_train_chunk(tm.h)
     share = min(1.0, chunk / q)
     hbm_bytes = (2 * C * W * 32 + C * W * 4
-                 + share * (2 * q * tm.Wf * 4 + 2 * tm.o * q / 8 + 2 * C * ((q + 63) // 64) * 8
-                            + tm.m * q * 4 * 2 + q * 8))
+                 + share * (2 * q * tm.Wf * 4 + 2 * tm.o * q / 8 + tm.m * q * 4 * 2 + q * 8)
+                 + 2 * 8 * cnt["blocks_evaluated"] / max(1, n_train))
     headline = args.workload == "image_like" and not (args.small or args.clauses_per_class or args.q_train)
     traffic = None
     if headline and MEASURED_TRAFFIC["image_like_train"]["fetch_kib"] > 0:
