@@ -46,6 +46,11 @@ def test_sizes_and_validation_are_host_only():
             + C * 16 + C * 4)
     assert ws >= need
     assert ws < 1.01 * need + 8192
+    # inference workspace: literal rows of the examples + literal lists + their lengths
+    iw = B.tm_infer_ws_bytes(cfg, 10000)
+    need_i = 1569 * ((10000 + 2047) // 2048) * 64 * 4 + C * 128 * 4 + C * 4
+    assert need_i <= iw < need_i + 1024
+    assert B.tm_infer_ws_bytes(cfg, 0) >= C * 128 * 4
     bad = [dict(m=1), dict(n=3), dict(n=0), dict(o=0), dict(N=0), dict(N=129), dict(T=0), dict(s=0.5)]
     for kw in bad:
         a = dict(m=2, n=4, o=8, N=10, T=5, s=3.0)
