@@ -1,0 +1,583 @@
+// The training kernel: Algorithm 1, one wavefront per clause.
+// Part of the one translation unit tm_kernels.hip (included there, in this order).
+#ifndef TM_KERNELS_TRAIN_HPP_
+#define TM_KERNELS_TRAIN_HPP_
+
+namespace tsetlin {
+
+// ------------------------------------------------------------------------
+// k_train: Algorithm 1, one wavefront per clause
+// ------------------------------------------------------------------------
+
+struct TrainArgs {
+    Dims d;
+    SatConst sat;
+    uint32_t *planes;
+    uint32_t *inc;
+    int32_t *tally;
+    const int32_t *vhat; // [q][m] snapshot the gate reads instead of the live tally, or null
+    uint32_t *ostar;
+    int32_t *fresh; // [C][4] per clause: examples whose stored output may be outdated lie in [plo,phi) or [slo,qp)
+    const int32_t *order; // [C] clause handled by each wavefront of the launch
+    unsigned long long *counters;
+    int32_t q, qp, Qw, i_begin, i_end; // example counts fit 31 bits (checked at bind)
+    uint32_t epoch;
+    int lds_mask_words; // W rounded up to a multiple of 4
+    int lds_off_words;  // Wf + EVAL_PAD rounded up to a multiple of 4
+    int lds_wave_words; // LDS words per wavefront
+    int QW;             // words per row of XB
+};
+
+constexpr int EVAL_PAD = 16; // empty entries after the list: a group may read that far past its end
+
+// The clause as the evaluation loop wants it: one entry per feature word whose
+// plain or negated mask word is non-zero, compacted in LDS: eoff[k] = byte
+// offset of that word's row in XT, emask[k] = {mask of plain literals, mask of
+// negated literals}; padded with EVAL_PAD empty entries.  Rebuilt whenever plane 7
+// changes.
+template <int WPL>
+__device__ __forceinline__ int build_entries(const u32x8 (&p)[WPL], uint32_t *lmask, uint32_t *eoff,
+                                             uint2 *emask, int lane, int Wf, int W, uint32_t row_bytes)
+{
+#pragma unroll
+    for (int r = 0; r < WPL; ++r) {
+        const int lw = r * 64 + lane;
+        if (lw < W) lmask[lw] = p[r][7];
+    }
+    wave_lds_sync();
+    int n = 0;
+    for (int f0 = 0; f0 < Wf; f0 += 64) {
+        const int fw = f0 + lane;
+        const bool ok = fw < Wf;
+        const uint32_t mp = ok ? lmask[fw] : 0u;
+        const uint32_t mn = ok ? lmask[Wf + fw] : 0u;
+        const bool nzf = (mp | mn) != 0u;
+        const uint64_t b = ballot(nzf);
+        const int pre = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, 0u));
+        if (nzf) {
+            eoff[n + pre] = (uint32_t)fw * row_bytes;
+            emask[n + pre] = make_uint2(mp, mn);
+        }
+        n += __builtin_popcountll(b);
+    }
+    if (lane < EVAL_PAD) {
+        eoff[n + lane] = 0u;
+        emask[n + lane] = make_uint2(0u, 0u);
+    }
+    wave_lds_sync();
+    return n;
+}
+
+// Clause outputs for 64 examples, lane = example: bit l of the result is
+// C(X_{i0+l}).  xt_block points at XT[0][i0].  An entry costs one coalesced
+// 256-byte load, an LDS broadcast of its masks and two bit operations.
+// Entries are taken EVAL_GROUP at a time (that many loads in flight; 8 and 24
+// measured slower); a dense (young) clause violates all 64 examples within the
+// first group and the loop stops.
+constexpr int EVAL_GROUP = 16;
+
+__device__ __forceinline__ uint64_t eval64(const uint32_t *eoff, const uint2 *emask, int nent,
+                                           const uint32_t *__restrict__ xt_block, int lane)
+{
+    uint32_t viol = 0;
+    const char *base = reinterpret_cast<const char *>(xt_block);
+    const uint32_t lane4 = (uint32_t)lane * 4u;
+    for (int k = 0; k < nent; k += EVAL_GROUP) {
+        uint32_t off[EVAL_GROUP], x[EVAL_GROUP];
+#pragma unroll
+        for (int j = 0; j < EVAL_GROUP; j += 4) {
+            const uint4 o = *reinterpret_cast<const uint4 *>(eoff + k + j);
+            off[j] = o.x; off[j + 1] = o.y; off[j + 2] = o.z; off[j + 3] = o.w;
+        }
+#pragma unroll
+        for (int j = 0; j < EVAL_GROUP; ++j) x[j] = *reinterpret_cast<const uint32_t *>(base + (off[j] + lane4));
+        const uint4 *mq = reinterpret_cast<const uint4 *>(emask + k);
+#pragma unroll
+        for (int j = 0; j < EVAL_GROUP / 2; ++j) {
+            const uint4 m = mq[j]; // {plain, negated} masks of entries 2j and 2j+1
+            // a plain literal is violated where x = 0, a negated one where x = 1
+            viol |= bitselect(x[2 * j], m.y, m.x) | bitselect(x[2 * j + 1], m.w, m.z);
+        }
+        if (ballot(viol == 0u) == 0) break;
+    }
+    return ballot(viol == 0u);
+}
+
+// Literals a clause's list in LDS can hold for the sweeps over outdated outputs; clauses
+// with more (untrained ones) are swept block by block with eval64.
+constexpr int TRAIN_LIT_MAX = 64;
+
+// Number of included literals of the clause held in p: the per-lane counts are summed bit by
+// bit with ballots, a loop-free wave sum.  (An atomic add on one LDS word would do, but the
+// compiler expands it into a 64-step scalar loop over the lanes.)
+template <int WPL>
+__device__ __forceinline__ int count_literals(const u32x8 (&p)[WPL], int lane, int W)
+{
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int r = 0; r < WPL; ++r) cnt += (r * 64 + lane < W) ? (uint32_t)__builtin_popcount(p[r][7]) : 0u;
+    int total = 0;
+#pragma unroll
+    for (int bit = 0; bit < 8; ++bit) // cnt <= 32 * WPL <= 128 for the narrow clauses this is used for
+        total += __builtin_popcountll(ballot(((cnt >> bit) & 1u) != 0u)) << bit;
+    return total;
+}
+
+// List of the included literals of the clause held in p (lane = literal word), as byte
+// offsets of their rows in XB, padded to a multiple of 4 with the all-ones row; returns
+// the number of included literals.  Only called for clauses with at most TRAIN_LIT_MAX.
+// The order of the list does not matter (the output is their conjunction): literals are
+// taken bit position by bit position, each position compacted over the lanes by ballot.
+template <int WPL>
+__device__ __forceinline__ int build_literals(const u32x8 (&p)[WPL], uint32_t *llist, int lane, int Wf, int W, int o,
+                                              uint32_t xb_row_bytes)
+{
+    int base = 0;
+#pragma unroll
+    for (int r = 0; r < WPL; ++r) {
+        const int lw = r * 64 + lane;
+        const uint32_t m = lw < W ? p[r][7] : 0u;
+        if (ballot(m != 0u) == 0) continue;
+        const uint32_t k0 = lw >= Wf ? (uint32_t)o + (uint32_t)(lw - Wf) * 32u : (uint32_t)lw * 32u; // literal of bit 0
+        for (int b = 0; b < 32; ++b) {
+            const bool set = ((m >> b) & 1u) != 0u;
+            const uint64_t bal = ballot(set);
+            if (bal == 0) continue;
+            const int pos = base + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+            if (set && pos < TRAIN_LIT_MAX) llist[pos] = (k0 + (uint32_t)b) * xb_row_bytes;
+            base += __builtin_popcountll(bal);
+        }
+    }
+    if (lane < 4) llist[min(base, TRAIN_LIT_MAX) + lane] = 2u * (uint32_t)o * xb_row_bytes;
+    wave_lds_sync();
+    return base;
+}
+
+constexpr int TRAIN_WAVES = 4; // clauses (wavefronts) per workgroup of the training kernel
+
+// One wavefront = one clause of class c.  The examples whose gate can open for this
+// clause are those of the gate list of c for this launch (label c: trained towards 1;
+// drawn negative class c: trained towards 0); their gates are drawn 64 at a time, lane =
+// list entry.  Blocks of 64 consecutive examples are evaluated (lane = example) only
+// when a gate in them fired or their stored outputs may be outdated; all other blocks
+// of the pass are never touched.
+template <int WPL, bool FULL>
+__global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
+                                                            const uint32_t *__restrict__ XB,
+                                                            const int32_t *__restrict__ gate,
+                                                            const int32_t *__restrict__ ngate, const TrainArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    const Dims &d = a.d;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int slot = blockIdx.x * TRAIN_WAVES + wave;
+    if (slot >= d.C) return; // whole wavefront; the kernel has no workgroup-wide barrier
+    const int g = __builtin_amdgcn_readfirstlane(a.order[slot]);
+    uint32_t *lmask = lds + wave * a.lds_wave_words;        // [W] include masks, literal-word order
+    uint32_t *eoff = lmask + a.lds_mask_words;              // [Wf + EVAL_PAD] (rounded to 4 words)
+    uint2 *emask = reinterpret_cast<uint2 *>(eoff + a.lds_off_words);
+    uint32_t *llist = lmask + a.lds_wave_words - (TRAIN_LIT_MAX + 4); // [TRAIN_LIT_MAX + 4] literal list for the sweeps
+
+    const int c = g / d.n;
+    const bool pos = ((g - c * d.n) & 1) != 0; // odd index within the class: positive polarity
+    const int sign = pos ? 1 : -1;
+    const int T = d.T;
+    const uint32_t row_bytes = (uint32_t)a.qp * 4u;
+    const int i_begin = a.i_begin, i_end = a.i_end, q = a.q;
+
+    u32x8 p[WPL];
+#pragma unroll
+    for (int r = 0; r < WPL; ++r) {
+        const int lw = r * 64 + lane;
+        u32x8 t = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+        if (lw < d.W) {
+            const uint4 *src = reinterpret_cast<const uint4 *>(a.planes + ((int64_t)g * d.W + lw) * 8);
+            const uint4 v0 = src[0], v1 = src[1];
+            t[0] = v0.x; t[1] = v0.y; t[2] = v0.z; t[3] = v0.w;
+            t[4] = v1.x; t[5] = v1.y; t[6] = v1.z; t[7] = v1.w;
+        }
+        p[r] = t;
+    }
+    int nent = build_entries<WPL>(p, lmask, eoff, emask, lane, d.Wf, d.W, row_bytes);
+
+    // lowest Philox block of the Type I comparator that can matter: bits of the
+    // uniform below the lowest set bit of thr never decide u < thr
+    const int tz = d.thr ? __builtin_ctz(d.thr) : 16;
+    const int first_blk = min(tz >> 2, 4);
+    const uint32_t ge_init = d.thr >= 65536u ? 0u : ~0u;
+
+    // per-wavefront event counts of one launch fit 32 bits (at most 2^30 examples per launch)
+    uint32_t n_fired = 0, n_type1 = 0, n_changes = 0, n_type2 = 0, n_eval = 0, n_draw = 0, n_listed_blocks = 0;
+
+    // Which stored previous outputs o* can differ from the clause's current output: only
+    // those not re-evaluated since the include mask last changed.  Kept per clause as two
+    // example ranges (multiples of 64), a prefix part [plo, phi) and a suffix [slo, qp); a
+    // block outside both needs no evaluation and no refresh unless one of its gates fires
+    // (the result is the same as refreshing every visited pair: o != o* would be false).
+    int plo, phi, slo;
+    {
+        const int4 f = *reinterpret_cast<const int4 *>(a.fresh + (int64_t)g * 4);
+        plo = __builtin_amdgcn_readfirstlane(f.x);
+        phi = __builtin_amdgcn_readfirstlane(f.y);
+        slo = __builtin_amdgcn_readfirstlane(f.z);
+    }
+    auto next_stale = [&](int b) { // first block index >= b that may hold outdated outputs
+        int r = max(b, slo >> 6);
+        if (plo < phi && b < ((phi + 63) >> 6)) r = min(r, max(b, plo >> 6));
+        return r;
+    };
+
+    // the gate list of this class for this launch
+    const int32_t *list = gate + (int64_t)c * a.qp;
+    const int k_lo = 0, k_hi = ngate[c];
+    const int32_t *tally_c = a.tally + (int64_t)c * a.qp;
+
+    // state of the block of 64 examples that is currently open (cb < 0: none)
+    const int end_block = (i_end + 63) >> 6;
+    int cb = -1, next_block = i_begin >> 6;
+    uint64_t obits = 0, ost = 0, rmask = 0;
+    bool mask_changed = false;
+
+    auto range_mask = [&](int b0) { return ballot(b0 + lane >= i_begin && b0 + lane < i_end); };
+    auto pack64 = [&](uint32_t lo, uint32_t hi) {
+        return (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)lo) |
+               ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)hi) << 32);
+    };
+    // Refresh of tally and previous-output bits (last lines of Algorithm 1) for the 64
+    // examples of block b at once: ob = outputs with the current masks, os = stored ones,
+    // rm = examples of the block that belong to this launch.
+    auto refresh_block = [&](int b, uint64_t ob, uint64_t os, uint64_t rm) {
+        const int b0 = b << 6;
+        const uint64_t diff = (ob ^ os) & rm;
+        if (diff) {
+            if ((diff >> lane) & 1ull) {
+                const int delta = ((ob >> lane) & 1ull) ? sign : -sign;
+                atomicAdd(&a.tally[(int64_t)c * a.qp + b0 + lane], delta);
+            }
+            const uint64_t nw = os ^ diff;
+            if (lane == 0) {
+                uint32_t *op = a.ostar + (int64_t)g * a.Qw + (b0 >> 5);
+                op[0] = (uint32_t)nw;
+                op[1] = (uint32_t)(nw >> 32);
+            }
+            n_changes += __builtin_popcountll(diff);
+        }
+    };
+    // ... followed by the bookkeeping of which stored outputs may be outdated
+    auto close_block = [&](int b, uint64_t ob, uint64_t os, uint64_t rm, bool changed) {
+        refresh_block(b, ob, os, rm);
+        const int b0 = b << 6, b1 = b0 + 64;
+        const bool whole = b0 >= i_begin && (b1 <= i_end || i_end == q);
+        if (whole) { // this block is up to date again
+            if (b0 <= plo) plo = max(plo, b1);
+            if (b0 <= slo) slo = max(slo, b1);
+        }
+        if (changed) { // everything not visited after the change is outdated now
+            plo = 0;
+            phi = b1;
+            slo = b1;
+        }
+    };
+    // Refresh of every block in [from, to) that may hold outdated outputs; no gate fired in
+    // them, so the masks stay as they are.  After a mask change these are all the blocks up
+    // to the next fired gate, most of what an epoch of a trained machine has to evaluate.
+    // A trained clause has few literals, so the sweep walks its literal list over the rows
+    // of XB, lane = word of 32 examples: 2048 examples per pass and one load per literal.
+    int n_listed = -1;          // literals of the current masks (list built if <= TRAIN_LIT_MAX), -1: not counted since the last change
+    uint32_t n_changes_v = 0;   // tally changes found by the passes, per lane
+    const char *xb_base = reinterpret_cast<const char *>(XB);
+    uint32_t *ostar_row = a.ostar + (int64_t)g * a.Qw;
+    auto sweep_listed = [&](int bs, int be) { // blocks [bs, be), all of them possibly outdated
+        for (int w0 = 2 * bs; w0 < 2 * be; w0 += 64) {
+            const int w = w0 + lane;
+            const bool act = w < 2 * be;
+            const int e0 = w << 5;
+            const int lo = min(max(i_begin - e0, 0), 32), hi = min(max(i_end - e0, 0), 32);
+            uint32_t rm = 0u; // examples of the word that belong to this launch
+            if (act && hi > lo) rm = (hi == 32 ? ~0u : (1u << hi) - 1u) & ~((1u << lo) - 1u);
+            const uint32_t woff = act ? (uint32_t)w * 4u : 0u;
+            const uint32_t ost = act ? ostar_row[w] : 0u;
+            uint32_t accv = rm;
+            for (int k = 0; k < n_listed; k += 4) {
+                const uint4 e = *reinterpret_cast<const uint4 *>(llist + k);
+                const uint32_t x0 = *reinterpret_cast<const uint32_t *>(xb_base + (e.x + woff));
+                const uint32_t x1 = *reinterpret_cast<const uint32_t *>(xb_base + (e.y + woff));
+                const uint32_t x2 = *reinterpret_cast<const uint32_t *>(xb_base + (e.z + woff));
+                const uint32_t x3 = *reinterpret_cast<const uint32_t *>(xb_base + (e.w + woff));
+                accv &= x0 & x1 & x2 & x3;
+            }
+            uint32_t diff = (accv ^ ost) & rm;
+            if (diff) ostar_row[w] = ost ^ diff;
+            n_changes_v += (uint32_t)__builtin_popcount(diff);
+            while (diff) { // one tally correction per changed example
+                const int bit = __builtin_ctz(diff);
+                diff &= diff - 1u;
+                atomicAdd(&a.tally[(int64_t)c * a.qp + e0 + bit], ((accv >> bit) & 1u) ? sign : -sign);
+            }
+        }
+        n_eval += (uint32_t)(be - bs);
+        n_listed_blocks += (uint32_t)(be - bs);
+        // the whole blocks among them are up to date again
+        const int fs = max(bs, (i_begin + 63) >> 6), fe = (i_end == q) ? be : min(be, i_end >> 6);
+        if (fs < fe) {
+            const int b0 = fs << 6, b1 = fe << 6;
+            if (b0 <= plo) plo = max(plo, b1);
+            if (b0 <= slo) slo = max(slo, b1);
+        }
+    };
+    auto sweep = [&](int from, int to) {
+        if (next_stale(from) >= to) return;
+        // the outdated blocks are those of [plo, phi) and of [slo, qp), in this order
+        int s1 = from, e1 = from;
+        if (plo < phi) {
+            s1 = max(from, plo >> 6);
+            e1 = max(s1, min(to, (phi + 63) >> 6));
+        }
+        const int s2 = max(max(from, slo >> 6), e1);
+        const int n_blocks = (e1 - s1) + max(to - s2, 0);
+        // The list pays for runs of blocks: a few blocks, or a list that the last mask change
+        // left to be rebuilt for a short run, are cheaper block by block below; so are wide
+        // clauses (their registers hold the automata) and untrained ones (hundreds of literals).
+        if (WPL <= 4 && n_blocks >= (n_listed < 0 ? 8 : 3)) {
+            if (n_listed < 0) {
+                n_listed = count_literals<WPL>(p, lane, d.W);
+                if (n_listed <= TRAIN_LIT_MAX) build_literals<WPL>(p, llist, lane, d.Wf, d.W, d.o, (uint32_t)a.QW * 4u);
+            }
+            if (n_listed <= TRAIN_LIT_MAX) {
+                if (s1 < e1) sweep_listed(s1, e1);
+                if (s2 < to) sweep_listed(s2, to);
+                return;
+            }
+        }
+        for (int b = next_stale(from); b < to; b = next_stale(b + 1)) { // closing b does not change which later blocks are outdated
+            const uint32_t *op = ostar_row + (b << 1);
+            const uint32_t o0 = op[0], o1 = op[1];
+            const uint64_t ob = eval64(eoff, emask, nent, XT + (b << 6), lane);
+            close_block(b, ob, pack64(o0, o1), range_mask(b << 6), false);
+            ++n_eval;
+        }
+    };
+
+    // Candidate data are fetched ahead: entry words two candidate blocks ahead, tallies (which
+    // need the entry's example index) one block ahead.  Reading a tally early is within the
+    // method's premise of outdated tallies.
+    auto load_ent = [&](int k0) { // packed (example << 1 | target), or -1 beyond the range
+        const int k = k0 + lane;
+        return k < k_hi ? list[k] : -1;
+    };
+    auto load_v = [&](int ent) {
+        if (ent < 0) return 0;
+        const int i = ent >> 1;
+        return a.vhat ? a.vhat[(int64_t)i * d.m + c]
+                      : __hip_atomic_load(&tally_c[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    int ent_cur = load_ent(k_lo);
+    int v_cur = load_v(ent_cur);
+    int ent_nxt = load_ent(k_lo + 64);
+
+    for (int k0 = k_lo;; k0 += 64) {
+        const bool last = k0 >= k_hi; // all candidates done: one more round sweeps the remaining blocks
+        uint64_t fmask = 0, tmask = 0;
+        int iv = 0;
+        if (!last) {
+            const int ent = ent_cur, v = v_cur;
+            ent_cur = ent_nxt;
+            v_cur = load_v(ent_cur);
+            ent_nxt = load_ent(k0 + 128);
+            const bool valid = ent >= 0;
+            iv = ent >> 1;
+            const bool target = (ent & 1) != 0;
+            bool fire = false, open = false;
+            if (valid) {
+                const int vc = min(max(v, -T), T);
+                const int e = target ? T - vc : T + vc; // Algorithm 1: error of the recorded vote sum
+                open = e > 0;
+                if (open) {
+                    const U4 r = draw(d.key, STREAM_GATE, 0, (uint32_t)g, (uint64_t)(uint32_t)iv, a.epoch);
+                    fire = (uint64_t)r.x * (uint64_t)(2 * (int64_t)T) < ((uint64_t)e << 32);
+                }
+            }
+            fmask = ballot(fire);
+            tmask = ballot(target);
+            n_draw += __builtin_popcountll(ballot(open));
+            n_fired += __builtin_popcountll(fmask);
+        }
+
+        // words of a fired example in lane = literal-word layout.  Slot geometry (which half,
+        // which bits exist) is recomputed from a laundered index wherever it is needed: it is
+        // example-independent, and the compiler would otherwise keep it in VGPRs for every slot.
+        auto load_row = [&](int ii, uint32_t (&dst)[WPL]) {
+            const uint32_t *xrow = X + (int64_t)ii * d.Wf;
+#pragma unroll
+            for (int r = 0; r < WPL; ++r) {
+                uint32_t lw = (uint32_t)(r * 64 + lane);
+                asm volatile("" : "+v"(lw));
+                const bool act = lw < (uint32_t)d.W;
+                const uint32_t fw = act ? (lw >= (uint32_t)d.Wf ? lw - (uint32_t)d.Wf : lw) : 0u;
+                dst[r] = xrow[fw];
+            }
+        };
+        // the row of the next fired example is requested while the current one is processed
+        uint32_t xnext[WPL];
+        if (fmask) load_row(__builtin_amdgcn_readlane(iv, __builtin_ctzll(fmask)), xnext);
+
+        for (;;) {
+            // next event: a fired candidate, or (after the last candidate) the end of the range
+            const bool have = fmask != 0;
+            int l = 0, ii = 0, B;
+            if (have) {
+                l = __builtin_ctzll(fmask);
+                fmask &= fmask - 1;
+                ii = __builtin_amdgcn_readlane(iv, l);
+                B = ii >> 6;
+            } else if (last) {
+                B = end_block;
+            } else {
+                break;
+            }
+
+            // bring block B up: close the open block, refresh the outdated blocks in between
+            if (cb != B) {
+                if (cb >= 0) {
+                    close_block(cb, obits, ost, rmask, mask_changed);
+                    next_block = cb + 1;
+                    cb = -1;
+                }
+                const int lim = min(B, end_block);
+                sweep(next_block, lim);
+                next_block = max(next_block, lim);
+                if (B < end_block) {
+                    // open block B: previous outputs, range mask, evaluation with the current masks
+                    cb = B;
+                    const int b0 = B << 6;
+                    const uint32_t *op = a.ostar + (int64_t)g * a.Qw + (b0 >> 5);
+                    const uint32_t o0 = op[0], o1 = op[1];
+                    rmask = range_mask(b0);
+                    obits = eval64(eoff, emask, nent, XT + b0, lane);
+                    ost = pack64(o0, o1);
+                    mask_changed = false;
+                    ++n_eval;
+                }
+            }
+            if (!have) break; // the range is finished
+
+            const int bl = ii & 63;                  // position of the example in the open block
+            const bool tgt = (tmask >> l) & 1;
+            const bool Cout = (obits >> bl) & 1;     // clause output on the state before the update
+            uint32_t changed = 0;
+            uint32_t xw[WPL];
+#pragma unroll
+            for (int r = 0; r < WPL; ++r) xw[r] = xnext[r];
+            if (fmask) load_row(__builtin_amdgcn_readlane(iv, __builtin_ctzll(fmask)), xnext);
+            auto literal = [&](uint32_t lw, uint32_t x, uint32_t &valid) {
+                const bool act = lw < (uint32_t)d.W;
+                const bool neg = lw >= (uint32_t)d.Wf;
+                const uint32_t fw = neg ? lw - (uint32_t)d.Wf : lw;
+                valid = act ? (fw == (uint32_t)d.Wf - 1u ? d.tailmask : ~0u) : 0u;
+                return (x ^ (neg ? ~0u : 0u)) & valid; // 0 on padding bits and idle lanes
+            };
+            if (tgt != pos) {
+                // Type II feedback (Table 2): where the clause is 1 and the literal 0, push Exclude towards Include
+                if (Cout) {
+                    ++n_type2;
+#pragma unroll
+                    for (int r = 0; r < WPL; ++r) {
+                        uint32_t lw = (uint32_t)(r * 64 + lane);
+                        asm volatile("" : "+v"(lw));
+                        uint32_t valid;
+                        const uint32_t lit = literal(lw, xw[r], valid);
+                        uint32_t sp[8];
+                        get_slot(p[r], sp);
+                        const uint32_t old7 = sp[7];
+                        const uint32_t m = ~lit & ~old7 & valid; // excluded automata (below the top bit) cannot overflow
+                        ripple_inc(sp, m);
+                        changed |= sp[7] ^ old7;
+                        put_slot(p[r], sp);
+                    }
+                }
+            } else {
+                // Type I feedback (Table 1)
+                ++n_type1;
+#pragma unroll
+                for (int r = 0; r < WPL; ++r) {
+                    // The literal-word index is laundered through an empty asm so that the
+                    // compiler does not hoist the example-independent first Philox round of
+                    // every slot and block out of the example loop (dozens of live VGPRs per slot).
+                    uint32_t lw = (uint32_t)(r * 64 + lane);
+                    asm volatile("" : "+v"(lw));
+                    // bit-sliced comparison of 32 16-bit uniforms with thr, least significant bit first:
+                    // ge = [u >= thr]; bit b of literal j's uniform is bit j of random word b;
+                    // thr bit 1: ge &= w, thr bit 0: ge |= w, i.e. majority(w, ge, ~thr bit)
+                    uint32_t ge = ge_init;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        if (t >= first_blk) {
+                            const U4 R = draw(d.key, STREAM_TYPE1, 4u * lw + (uint32_t)t, (uint32_t)g,
+                                              (uint64_t)(uint32_t)ii, a.epoch);
+                            const uint32_t w[4] = {R.x, R.y, R.z, R.w};
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                const uint32_t K = ((d.thr >> (4 * t + k)) & 1u) ? 0u : ~0u;
+                                ge = majority3(w[k], ge, K);
+                            }
+                        }
+                    }
+                    uint32_t valid;
+                    const uint32_t lit = literal(lw, xw[r], valid);
+                    uint32_t sp[8];
+                    get_slot(p[r], sp);
+                    const uint32_t old7 = sp[7];
+                    if (Cout) { // strong: literals that are 1 move towards Include with probability (s-1)/s (1 if boosted)
+                        const uint32_t m = lit & (ge | d.boost) & ~at_value<FULL>(sp, a.sat.kmax, true);
+                        ripple_inc(sp, m);
+                    }
+                    // weak: everything else moves towards Exclude with probability 1/s
+                    const uint32_t wk = (Cout ? ~lit : ~0u) & ~ge & valid & ~at_value<FULL>(sp, a.sat.kmin, false);
+                    ripple_dec(sp, wk);
+                    changed |= sp[7] ^ old7;
+                    put_slot(p[r], sp);
+                    // keep the slots apart in the instruction schedule: interleaving them
+                    // multiplies the live registers by the number of slots
+                    if (WPL > 2) __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if (ballot(changed != 0u)) { // the conjunction changed: re-evaluate this and the later examples of the block
+                mask_changed = true;
+                n_listed = -1;
+                nent = build_entries<WPL>(p, lmask, eoff, emask, lane, d.Wf, d.W, row_bytes);
+                const uint64_t nb = eval64(eoff, emask, nent, XT + (cb << 6), lane);
+                const uint64_t keep = (1ull << bl) - 1ull;
+                obits = (obits & keep) | (nb & ~keep);
+            }
+        }
+        if (last) break;
+    }
+    if (plo >= phi) plo = phi = 0;
+    if (lane == 0) *reinterpret_cast<int4 *>(a.fresh + (int64_t)g * 4) = make_int4(plo, phi, slo, 0);
+
+#pragma unroll
+    for (int r = 0; r < WPL; ++r) {
+        const int lw = r * 64 + lane;
+        if (lw < d.W) {
+            uint4 *dst = reinterpret_cast<uint4 *>(a.planes + ((int64_t)g * d.W + lw) * 8);
+            const u32x8 t = p[r];
+            dst[0] = make_uint4(t[0], t[1], t[2], t[3]);
+            dst[1] = make_uint4(t[4], t[5], t[6], t[7]);
+            a.inc[(int64_t)g * d.W + lw] = t[7];
+        }
+    }
+    for (int sh = 32; sh > 0; sh >>= 1) n_changes_v += __shfl_xor(n_changes_v, sh, 64);
+    n_changes += n_changes_v;
+    // event counters: 64 interleaved sets, because thousands of wavefronts ending at the
+    // same time on one address serialise in the L2 atomic unit (measured: ~1.7 ms per launch)
+    if (lane < 8) { // slot 4 (trained pairs) is counted by the launch preparation
+        const uint32_t v = lane == 0 ? n_listed_blocks : lane == 1 ? n_fired : lane == 2 ? n_type1 : lane == 3 ? n_changes
+                         : lane == 4 ? 0u : lane == 5 ? n_type2 : lane == 6 ? n_eval : n_draw;
+        if (v) atomicAdd(&a.counters[(g & (COUNTER_SETS - 1)) * 8 + lane], (unsigned long long)v);
+    }
+}
+
+} // namespace tsetlin
+
+#endif
