@@ -134,7 +134,9 @@ int tm_infer_ws_bytes(const tm_config *cfg, int64_t q, size_t *out);
  * byte aligned, contents need not be kept between calls).  Same results.  Eq. 1
  * is a conjunction over the INCLUDED literals only, so each clause is evaluated
  * from the list of its included literals instead of from its 2o mask bits; on a
- * trained machine that is a few dozen literals per clause.  TM_ELIMIT when
+ * trained machine that is a few dozen literals per clause (the lists hold
+ * 128 to 1,024 literals depending on o; longer clauses are finished from
+ * their masks).  TM_ELIMIT when
  * (2o + 1) * 64 * ceil(q / 2048) * 4 bytes reach 4 GiB: split q. */
 int tm_class_sums_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, void *ws, void *stream);
 int tm_predict_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, int32_t *sums_scratch, void *ws,

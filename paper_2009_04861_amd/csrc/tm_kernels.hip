@@ -10,7 +10,7 @@
 //                  ostar  uint32 [C][Qw]    previous clause outputs, 1 bit per (clause, example), Qw = qp/32
 //                  XT     uint32 [Wf][qp]   transposed features (word-major) for lane = example evaluation
 //                  XB     uint32 [2o+1][QW] literals as bit rows over the examples (row 2o all ones), QW = 64*ceil(q/2048)
-//                  lits   uint32 [C][128]   literal lists of the clauses, nlit int32 [C] their lengths
+//                  lits   uint32 [C][cap]   literal lists of the clauses (cap = 128..1024), nlit int32 [C] their lengths
 //                  negcls int32  [qp]       class trained towards 0 for each example, this epoch
 //                  gate   int32  [m][qp]    per class and launch: ascending list of (example << 1 | target) whose gate can open
 //                  fresh  int32  [C][4]     per clause: example ranges whose stored outputs may be outdated
@@ -80,7 +80,7 @@ struct tm_handle {
     uint32_t *XT;
     int32_t *negcls;
     uint32_t *XB;   // [2o+1][QW] literal rows of the bound data
-    uint32_t *lits; // [C][LIT_MAX]
+    uint32_t *lits; // [C][lit_cap(d)]
     int32_t *nlit;  // [C]
     int32_t *gate;  // [m][qp] gate lists of the current launch
     int32_t *ngate; // [m]
@@ -147,6 +147,14 @@ inline size_t xb_bytes(const Dims &d, int64_t q) { return (size_t)(2 * d.o + 1) 
 // segments of the launch preparation: of the longest range of examples, or of the clauses
 inline int64_t prep_segments(const Dims &d, int64_t qp) { return (std::max<int64_t>(qp, d.C) + PREP_SEG - 1) / PREP_SEG; }
 
+// Entries per literal list: a sixteenth of the literals, within [128, 1024], a multiple of 64.
+// Trained clauses include far fewer; what does not fit is finished from the include masks.
+inline int lit_cap(const Dims &d)
+{
+    const int want = ((2 * d.o / 16) + 63) & ~63;
+    return std::min(LIT_CAP_MAX, std::max(LIT_CAP_MIN, want));
+}
+
 struct WsLayout {
     size_t tally, ostar, xt, xb, lits, nlit, negcls, gate, ngate, fresh, order, seg_cnt, counters, flag, total;
 };
@@ -161,7 +169,7 @@ WsLayout ws_layout(const Dims &d, int64_t q)
     L.ostar = off; off += align256((size_t)d.C * Qw * 4);
     L.xt = off; off += align256((size_t)d.Wf * qp * 4);
     L.xb = off; off += align256(xb_bytes(d, q));
-    L.lits = off; off += align256((size_t)d.C * LIT_MAX * 4);
+    L.lits = off; off += align256((size_t)d.C * lit_cap(d) * 4);
     L.nlit = off; off += align256((size_t)d.C * 4);
     L.negcls = off; off += align256((size_t)qp * 4);
     L.gate = off; off += align256((size_t)d.m * qp * 4);
@@ -307,11 +315,11 @@ int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *li
     const Dims &d = h->d;
     const int64_t QW = xb_row_words(q);
     hipLaunchKernelGGL(k_literal_lists, dim3(blocks_for(d.C, 4)), dim3(256), 0, st, h->inc, lits, nlit, d.C, d.Wf, d.W,
-                       d.o, (uint32_t)(QW * 4), fresh, (int)h->qp);
+                       d.o, lit_cap(d), (uint32_t)(QW * 4), fresh, (int)h->qp);
     TM_HIP(h, hipGetLastError());
     SparseArgs a;
     a.bits = bits; a.bits_stride = bits_stride; a.acc = acc; a.acc_si = acc_si; a.acc_sc = acc_sc;
-    a.q = q; a.QW = (int)QW; a.QWq = (int)((q + 31) / 32); a.n = d.n; a.m = d.m; a.o = d.o; a.Wf = d.Wf; a.W = d.W;
+    a.q = q; a.QW = (int)QW; a.QWq = (int)((q + 31) / 32); a.n = d.n; a.m = d.m; a.o = d.o; a.Wf = d.Wf; a.W = d.W; a.lit_cap = lit_cap(d);
     // enough workgroups to fill the chip (16 wavefronts each), at most 255 clauses per wavefront,
     // at least 16 clauses per workgroup
     const int64_t ranges = QW / 64;
@@ -642,7 +650,7 @@ int tm_infer_ws_bytes(const tm_config *cfg, int64_t q, size_t *out)
     if (rc) return rc;
     if (!out || q < 0) return TM_EINVAL;
     const Dims d = make_dims(cfg);
-    *out = align256(xb_bytes(d, q)) + align256((size_t)d.C * LIT_MAX * 4) + align256((size_t)d.C * 4);
+    *out = align256(xb_bytes(d, q)) + align256((size_t)d.C * lit_cap(d) * 4) + align256((size_t)d.C * 4);
     return TM_OK;
 }
 
@@ -659,7 +667,7 @@ static int infer_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, i
     char *base = (char *)ws;
     uint32_t *XB = (uint32_t *)base;
     uint32_t *lits = (uint32_t *)(base + align256(xb_bytes(d, q)));
-    int32_t *nlit = (int32_t *)(base + align256(xb_bytes(d, q)) + align256((size_t)d.C * LIT_MAX * 4));
+    int32_t *nlit = (int32_t *)(base + align256(xb_bytes(d, q)) + align256((size_t)d.C * lit_cap(d) * 4));
     const int rc = build_xb(h, X, q, XB, st);
     if (rc) return rc;
     return launch_eval_sparse(h, XB, q, lits, nlit, nullptr, 0, sums, d.m, 1, d.T, pred, nullptr, TIMED_INFER, st);

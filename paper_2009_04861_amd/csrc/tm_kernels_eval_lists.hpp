@@ -20,7 +20,7 @@ namespace tsetlin {
 // clauses by their literals.  An untrained clause includes about half of all literals,
 // but then some literal is false on every example after a few loads and the loop stops.
 
-constexpr int LIT_MAX = 128;   // listed literals per clause; clauses with more are finished from their masks
+constexpr int LIT_CAP_MIN = 128, LIT_CAP_MAX = 1024; // bounds of the list capacity (entries per clause)
 constexpr int SP_WAVES = 16;   // wavefronts per workgroup of k_eval_sparse
 constexpr int SP_PLANES = 8;   // bit planes of a wavefront's vote counter: at most 255 clauses per wavefront
 
@@ -56,19 +56,21 @@ __global__ __launch_bounds__(256) void k_transpose_bits(const uint32_t *__restri
 }
 
 // Literal list of every clause, one wavefront per clause: entry = byte offset of the
-// literal's row in XB; the first LIT_MAX included literals in literal order, the rest of
-// the LIT_MAX slots filled with the all-ones row so that several clauses can be walked in
-// step.  nlit[g] = number of included literals (may exceed LIT_MAX).
+// literal's row in XB; the first `cap` included literals in literal order (cap = list
+// capacity, a multiple of 4 chosen from the number of features), the rest of the cap
+// slots filled with the all-ones row so that several clauses can be walked in step.
+// nlit[g] = number of included literals (may exceed cap; such clauses are finished from
+// their masks).
 __global__ __launch_bounds__(256) void k_literal_lists(const uint32_t *__restrict__ inc, uint32_t *__restrict__ lits,
                                                        int32_t *__restrict__ nlit, int C, int Wf, int W, int o,
-                                                       uint32_t row_bytes, int32_t *fresh, int qp)
+                                                       int cap, uint32_t row_bytes, int32_t *fresh, int qp)
 {
     const int lane = threadIdx.x & 63;
     const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (g >= C) return;
     // ahead of a tally pre-calculation: every stored output of the clause will be current
     if (fresh && lane == 0) *reinterpret_cast<int4 *>(fresh + (int64_t)g * 4) = make_int4(0, 0, qp, 0);
-    uint32_t *L = lits + (int64_t)g * LIT_MAX;
+    uint32_t *L = lits + (int64_t)g * cap;
     int base = 0;
     for (int w0 = 0; w0 < W; w0 += 64) {
         const int lw = w0 + lane;
@@ -85,12 +87,12 @@ __global__ __launch_bounds__(256) void k_literal_lists(const uint32_t *__restric
         while (m) {
             const int b = __builtin_ctz(m);
             m &= m - 1u;
-            if (pos < LIT_MAX) L[pos] = (k0 + (uint32_t)b) * row_bytes;
+            if (pos < cap) L[pos] = (k0 + (uint32_t)b) * row_bytes;
             ++pos;
         }
         base += __shfl(incl, 63, 64);
     }
-    for (int t = min(base, LIT_MAX) + lane; t < LIT_MAX; t += 64) L[t] = 2u * (uint32_t)o * row_bytes;
+    for (int t = min(base, cap) + lane; t < cap; t += 64) L[t] = 2u * (uint32_t)o * row_bytes;
     if (lane == 0) nlit[g] = base;
 }
 
@@ -102,13 +104,14 @@ struct SparseArgs {
     int64_t q;
     int QW, QWq;         // words per row of XB; words that hold examples (ceil(q/32))
     int n, m, o, Wf, W;
+    int lit_cap;         // entries per literal list
     int ranges, by_xcd;  // ranges of 2048 examples; workgroup -> (range, class, share) mapping
     int S, chunk;        // clauses of a class are split over S workgroups, `chunk` (a multiple of 16) each
     int T;               // > 0: the sums are clamped to [-T, T] (only with S = 1)
 };
 
 // Output of clause g on the 32 examples of this lane's word, taken from its include masks
-// (for the rare clause that has more than LIT_MAX literals and is still satisfied somewhere
+// (for the rare clause that has more literals than its list holds and is still satisfied somewhere
 // after the listed ones); `valid` masks examples >= q.
 __device__ __forceinline__ uint32_t clause_from_masks(const uint32_t *__restrict__ inc, const char *xb_lane, int g,
                                                       uint32_t valid, const SparseArgs &a)
@@ -189,10 +192,10 @@ __global__ __launch_bounds__(64 * SP_WAVES) void k_eval_sparse(const uint32_t *_
             const int j = j0 + u * SP_WAVES;
             const bool ok = j < j_hi;
             const int g = c * a.n + (ok ? j : j_lo);
-            L[u] = lits + (int64_t)g * LIT_MAX;
+            L[u] = lits + (int64_t)g * a.lit_cap;
             nl[u] = ok ? nlit[g] : 0;
             x[u] = ok ? valid : 0u;
-            longest = max(longest, min(nl[u], LIT_MAX));
+            longest = max(longest, min(nl[u], a.lit_cap));
         }
         for (int k = 0; k < longest; k += 4) {
             uint32_t r[8][4];
@@ -222,7 +225,7 @@ __global__ __launch_bounds__(64 * SP_WAVES) void k_eval_sparse(const uint32_t *_
             const int j = j0 + u * SP_WAVES;
             if (j < j_hi) {
                 const int g = c * a.n + j;
-                if (nl[u] > LIT_MAX && ballot(x[u] != 0u) != 0) x[u] = clause_from_masks(inc, xb_lane, g, valid, a);
+                if (nl[u] > a.lit_cap && ballot(x[u] != 0u) != 0) x[u] = clause_from_masks(inc, xb_lane, g, valid, a);
                 if (a.bits && word < a.bits_stride) a.bits[(int64_t)g * a.bits_stride + word] = x[u];
             }
         }
