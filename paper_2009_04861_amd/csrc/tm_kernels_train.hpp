@@ -510,15 +510,25 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
                     // ge = [u >= thr]; bit b of literal j's uniform is bit j of random word b;
                     // thr bit 1: ge &= w, thr bit 0: ge |= w, i.e. majority(w, ge, ~thr bit)
                     uint32_t ge = ge_init;
+                    RngKey key = d.key;
+                    uint32_t thr = d.thr;
+                    if (WPL <= 2) asm volatile("" : "+s"(key.seed_lo), "+s"(key.seed_hi), "+s"(thr));
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
                         if (t >= first_blk) {
-                            const U4 R = draw(d.key, STREAM_TYPE1, 4u * lw + (uint32_t)t, (uint32_t)g,
+                            // With one or two slots, key and threshold are laundered as well (above):
+                            // their derived constants (20 round keys, 16 comparator masks) are then
+                            // computed by scalar instructions per slot instead of being kept for the
+                            // whole kernel - kept, they overflow the scalar registers and come back
+                            // through readlane, a vector instruction each, in the loop that is bound by
+                            // vector issue (-5 % per epoch of an untrained machine).  With many slots the
+                            // scalar work per slot costs more than the spills (measured +8 .. +20 %).
+                            const U4 R = draw(key, STREAM_TYPE1, 4u * lw + (uint32_t)t, (uint32_t)g,
                                               (uint64_t)(uint32_t)ii, a.epoch);
                             const uint32_t w[4] = {R.x, R.y, R.z, R.w};
 #pragma unroll
                             for (int k = 0; k < 4; ++k) {
-                                const uint32_t K = ((d.thr >> (4 * t + k)) & 1u) ? 0u : ~0u;
+                                const uint32_t K = ((thr >> (4 * t + k)) & 1u) ? 0u : ~0u;
                                 ge = majority3(w[k], ge, K);
                             }
                         }
