@@ -256,6 +256,44 @@ def test_set_state_after_bind_then_step_refreshes_everything(device):
         assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar)
 
 
+@pytest.mark.parametrize("o", [100, 2500, 5000])
+def test_long_runs_of_outdated_blocks_are_swept_through_literal_lists(o, device):
+    """Sparse clauses pushed after bind leave every stored output outdated; few gates can open,
+    so the passes refresh long runs of blocks, 2048 examples at a time through the clause's
+    literal list (clauses of up to 4 register slots per lane; o = 5000 keeps to the block-by-block path).  Ranges start and
+    end inside blocks and words; 5,000 examples span two segments of the launch preparation."""
+    m, n, N, T, s = 3, 6, 64, 2, 4.0
+    print("list sweeps", o, flush=True)
+    rng = np.random.default_rng(o)
+    q = 5000
+    ora, gpu = make_pair(m, n, o, N, T, s, 5)
+    X, y = rand_problem(rng, q, o, m)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    ora.state[:] = sparse_random_state(rng, ora.C, ora.L, N, 2.5 / o)
+    ora.state[0, :] = 1                                        # an empty clause
+    ora.state[1, :70] = 2 * N                                  # 70 literals: more than the list in LDS holds
+    push_state(gpu, ora.state)
+    gpu.counters()
+    # snapshot that closes every gate (+T for the label, -T elsewhere) except on 2 % of the examples
+    snap = np.full((q, m), -T, dtype=np.int32)
+    snap[np.arange(q), y] = T
+    snap[rng.random(q) < 0.02] = 0
+    fired = 0
+    for ep, (i0, cnt) in enumerate([(1234, 3000), (0, q), (4097, 903), (0, q)]):
+        B.tm_set_epoch(gpu.h, ep)
+        gpu.feedback_step(dev_i32(gpu, snap), i0, cnt)
+        fired += ora.feedback_step(X, y, snap, tally, ostar, ep, i0, cnt)
+        assert np.array_equal(gpu_state_as_oracle(gpu), ora.state), ep
+        assert np.array_equal(gpu.tallies().cpu().numpy(), tally), ep
+        assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar), ep
+    c = gpu.counters()
+    print("fired %d, blocks evaluated %d, of them through lists %d" % (fired, c["blocks_evaluated"], c["blocks_listed"]),
+          flush=True)
+    assert fired > 20 and c["fired"] == fired
+    assert (c["blocks_listed"] > 0) == (o <= 4096)
+
+
 def test_quiet_epochs_skip_evaluation_but_change_nothing(device):
     # T = 1 closes almost every gate once the sums reach the margin: most blocks are skipped
     m, n, o, N, T, s = 2, 20, 30, 50, 1, 3.0
