@@ -412,6 +412,43 @@ def test_epochs_walked_in_batches(device):
     assert e.value.code == B.TM_EINVAL
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_random_small_configurations(case, device):
+    """Random corners of the parameter space (one feature, two clauses, one example, one state
+    per action, s = 1, margins beyond the clause count, ...): initial state, pre-calculation, two
+    frozen passes, inference, all against the oracle."""
+    rng = np.random.default_rng(1000 + case)
+    m = int(rng.choice([2, 2, 3, 5, 11]))
+    n = int(rng.choice([2, 2, 4, 6, 18, 34]))
+    o = int(rng.choice([1, 2, 31, 32, 33, 64, 65, 200]))
+    N = int(rng.choice([1, 2, 7, 128]))
+    T = int(rng.choice([1, 2, n, 3 * n]))
+    s = float(rng.choice([1.0, 1.5, 3.0, 50.0]))
+    q = int(rng.choice([1, 2, 63, 64, 65, 129, 400]))
+    print("random configuration", case, (m, n, o, N, T, s, q), flush=True)
+    ora, gpu = make_pair(m, n, o, N, T, s, 40 + case)
+    assert np.array_equal(gpu_state_as_oracle(gpu), ora.state)
+    X, y = rand_problem(rng, q, o, m, density=float(rng.choice([0.1, 0.5, 0.9])))
+    Xd = dev_bits(gpu, X)
+    gpu.bind_train(Xd, dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    assert np.array_equal(gpu.tallies().cpu().numpy(), tally)
+    assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar)
+    for ep in range(2):
+        B.tm_set_epoch(gpu.h, ep)
+        run_frozen(ora, gpu, X, y, ep, 0, q, tally, ostar)
+        assert np.array_equal(gpu_state_as_oracle(gpu), ora.state), ep
+        assert np.array_equal(gpu.tallies().cpu().numpy(), tally), ep
+        assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar), ep
+    for lists in (True, False):
+        assert np.array_equal(gpu.class_sums(Xd, lists=lists).cpu().numpy(), ora.class_sums(X))
+        assert np.array_equal(gpu.predict(Xd, lists=lists).cpu().numpy(), ora.predict(X))
+    gpu.fit_epoch()
+    gpu.sync_tallies()
+    ora.state[:] = gpu_state_as_oracle(gpu)
+    assert np.array_equal(gpu.tallies().cpu().numpy(), ora.class_sums(X, clamp=False))
+
+
 def test_error_codes(device):
     gpu = B.TsetlinMachine(3, 4, 20, 10, 5, 3.0, 1)
     with pytest.raises(B.TMError) as e:
