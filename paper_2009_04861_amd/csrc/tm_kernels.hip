@@ -385,7 +385,7 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     a.q = (int32_t)h->q; a.qp = (int32_t)h->qp; a.Qw = (int32_t)h->Qw; a.epoch = h->epoch;
     a.lds_mask_words = (d.W + 3) & ~3;
     a.lds_off_words = (d.Wf + EVAL_PAD + 3) & ~3;
-    a.lds_wave_words = a.lds_mask_words + a.lds_off_words + 2 * ((d.Wf + EVAL_PAD + 1) & ~1) + TRAIN_LIT_MAX + 4;
+    a.lds_wave_words = a.lds_mask_words + a.lds_off_words + 2 * ((d.Wf + EVAL_PAD + 1) & ~1) + TRAIN_LIT_MAX + 8;
     a.QW = (int)xb_row_words(h->q);
     const bool full = (d.N == 128);
     const int wpl = (d.W + 63) / 64;

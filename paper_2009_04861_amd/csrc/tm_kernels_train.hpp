@@ -124,7 +124,7 @@ __device__ __forceinline__ int count_literals(const u32x8 (&p)[WPL], int lane, i
 }
 
 // List of the included literals of the clause held in p (lane = literal word), as byte
-// offsets of their rows in XB, padded to a multiple of 4 with the all-ones row; returns
+// offsets of their rows in XB, padded to a multiple of 8 with the all-ones row; returns
 // the number of included literals.  Only called for clauses with at most TRAIN_LIT_MAX.
 // The order of the list does not matter (the output is their conjunction): literals are
 // taken bit position by bit position, each position compacted over the lanes by ballot.
@@ -148,7 +148,7 @@ __device__ __forceinline__ int build_literals(const u32x8 (&p)[WPL], uint32_t *l
             base += __builtin_popcountll(bal);
         }
     }
-    if (lane < 4) llist[min(base, TRAIN_LIT_MAX) + lane] = 2u * (uint32_t)o * xb_row_bytes;
+    if (lane < 8) llist[min(base, TRAIN_LIT_MAX) + lane] = 2u * (uint32_t)o * xb_row_bytes;
     wave_lds_sync();
     return base;
 }
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     uint32_t *lmask = lds + wave * a.lds_wave_words;        // [W] include masks, literal-word order
     uint32_t *eoff = lmask + a.lds_mask_words;              // [Wf + EVAL_PAD] (rounded to 4 words)
     uint2 *emask = reinterpret_cast<uint2 *>(eoff + a.lds_off_words);
-    uint32_t *llist = lmask + a.lds_wave_words - (TRAIN_LIT_MAX + 4); // [TRAIN_LIT_MAX + 4] literal list for the sweeps
+    uint32_t *llist = lmask + a.lds_wave_words - (TRAIN_LIT_MAX + 8); // [TRAIN_LIT_MAX + 8] literal list for the sweeps
 
     const int c = g / d.n;
     const bool pos = ((g - c * d.n) & 1) != 0; // odd index within the class: positive polarity
@@ -299,13 +299,17 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
             const uint32_t woff = act ? (uint32_t)w * 4u : 0u;
             const uint32_t ost = act ? ostar_row[w] : 0u;
             uint32_t accv = rm;
-            for (int k = 0; k < n_listed; k += 4) {
-                const uint4 e = *reinterpret_cast<const uint4 *>(llist + k);
+            for (int k = 0; k < n_listed; k += 8) { // eight literals per round (the list is padded to a multiple of 8)
+                const uint4 e = *reinterpret_cast<const uint4 *>(llist + k), e2 = *reinterpret_cast<const uint4 *>(llist + k + 4);
                 const uint32_t x0 = *reinterpret_cast<const uint32_t *>(xb_base + (e.x + woff));
                 const uint32_t x1 = *reinterpret_cast<const uint32_t *>(xb_base + (e.y + woff));
                 const uint32_t x2 = *reinterpret_cast<const uint32_t *>(xb_base + (e.z + woff));
                 const uint32_t x3 = *reinterpret_cast<const uint32_t *>(xb_base + (e.w + woff));
-                accv &= x0 & x1 & x2 & x3;
+                const uint32_t x4 = *reinterpret_cast<const uint32_t *>(xb_base + (e2.x + woff));
+                const uint32_t x5 = *reinterpret_cast<const uint32_t *>(xb_base + (e2.y + woff));
+                const uint32_t x6 = *reinterpret_cast<const uint32_t *>(xb_base + (e2.z + woff));
+                const uint32_t x7 = *reinterpret_cast<const uint32_t *>(xb_base + (e2.w + woff));
+                accv &= x0 & x1 & x2 & x3 & x4 & x5 & x6 & x7;
             }
             uint32_t diff = (accv ^ ost) & rm;
             if (diff) ostar_row[w] = ost ^ diff;
