@@ -14,7 +14,7 @@
  *
  * Data conventions of this file
  *   X      uint8  [q][o]        feature values 0/1
- *   y      int32  [q]           class label 0..m-1
+ *   y      int32  [q]           class label 0..m-1 (regression mode: target 0..T)
  *   state  int32  [m*n][2o]     TA state 1..2N.  Literal k<o is x_k, literal
  *                               o+k is NOT x_k (Section 2.1, literal set L).
  *   clause g = c*n + j belongs to class c; it has positive polarity iff j is
@@ -33,6 +33,20 @@
  *   - The tally refresh of Algorithm 1 (its last five lines) is done for every
  *     visited (clause, example) pair and adds polarity * (o - o*), so that the
  *     tallies converge to the signed sum of Eq. 3 ("eventual consistency").
+ *
+ * Regression mode (the regression Tsetlin machine of Section 4.1).  The paper
+ * measures it but does not restate its update rule; this file follows the rule of
+ * the regression TM publication it cites (Abeyrathna et al., 2020), expressed in
+ * the quantities of Algorithm 1:
+ *   - one bank of n clauses (m = 1), every clause votes +1 (no negative polarity);
+ *   - the output is the vote sum clipped to [0, T]; targets are integers y in
+ *     [0, T] (the caller scales its continuous target to that range);
+ *   - with vc = clip(v, 0, T): nothing happens at vc = y; at vc < y every clause
+ *     receives Type I feedback with probability (y - vc)/T, at vc > y Type II
+ *     feedback with probability (vc - y)/T.  The draw is the gate's:
+ *     fire iff r * T < |y - vc| * 2^32.
+ * Everything else (clause evaluation, Type I / II tables, tally refresh, random
+ * streams) is shared with classification.
  *
  * Randomness: Philox4x32-10 (Salmon et al., SC'11), key = seed, counter
  *   ( blk | stream<<28 , g , i mod 2^32 , epoch | (i>>32)<<24 ).
@@ -56,6 +70,7 @@ typedef struct {
     uint64_t seed;
     int32_t  boost;  /* boost true positives: the strong Type I probability (s-1)/s becomes 1
                         (footnote of Section 2.2) */
+    int32_t  regression; /* 1: regression mode (m = 1, y in [0, T]), see above */
 } otm_config;
 
 enum { OTM_INIT = 0, OTM_GATE = 1, OTM_TYPE1 = 2, OTM_NEGCLASS = 3 };
@@ -126,6 +141,8 @@ static int clause_output(const otm_config *cfg, const int32_t *st, const uint8_t
 static int polarity_sign(const otm_config *cfg, int g)
 {
     int j = g % cfg->n;
+    if (cfg->regression)
+        return +1;
     return (j & 1) ? +1 : -1;
 }
 
@@ -176,7 +193,7 @@ void otm_clause_outputs(const otm_config *cfg, const int32_t *state, const uint8
     free(lit);
 }
 
-/* sums[i][c] = Eq. 3 per class; clamped to [-T,T] if clamp != 0 */
+/* sums[i][c] = Eq. 3 per class; clamped to [-T,T] ([0,T] in regression mode) if clamp != 0 */
 void otm_class_sums(const otm_config *cfg, const int32_t *state, const uint8_t *X,
                     int64_t q, int clamp, int32_t *sums)
 {
@@ -186,13 +203,14 @@ void otm_class_sums(const otm_config *cfg, const int32_t *state, const uint8_t *
         literals(cfg, X + i * cfg->o, lit);
         for (int c = 0; c < cfg->m; ++c) {
             int32_t v = vote_sum(cfg, state, lit, c);
-            sums[i * cfg->m + c] = clamp ? clip(v, -cfg->T, cfg->T) : v;
+            sums[i * cfg->m + c] = clamp ? clip(v, cfg->regression ? 0 : -cfg->T, cfg->T) : v;
         }
     }
     free(lit);
 }
 
-/* pred[i] = lowest class index with the largest clamped sum */
+/* pred[i] = lowest class index with the largest clamped sum; in regression mode the
+ * clipped vote sum itself (the prediction in units of 1/T of the target range) */
 void otm_predict(const otm_config *cfg, const int32_t *state, const uint8_t *X,
                  int64_t q, int32_t *pred)
 {
@@ -200,6 +218,10 @@ void otm_predict(const otm_config *cfg, const int32_t *state, const uint8_t *X,
     otm_class_sums(cfg, state, X, q, 1, sums);
     for (int64_t i = 0; i < q; ++i) {
         int best = 0;
+        if (cfg->regression) {
+            pred[i] = sums[i];
+            continue;
+        }
         for (int c = 1; c < cfg->m; ++c)
             if (sums[i * cfg->m + c] > sums[i * cfg->m + best])
                 best = c;
@@ -226,6 +248,19 @@ int otm_gate(const otm_config *cfg, int32_t g, int64_t i, uint32_t epoch, int32_
     uint32_t r[4];
     draw(cfg, OTM_GATE, 0, (uint32_t)g, (uint64_t)i, epoch, r);
     return (uint64_t)r[0] * (uint64_t)(2 * (int64_t)cfg->T) < ((uint64_t)e << 32);
+}
+
+/* Regression mode: which feedback, if any, clause g gives itself on example i whose
+ * recorded vote sum is v and whose target is y.  0 none, 1 Type I, 2 Type II. */
+int otm_gate_regression(const otm_config *cfg, int32_t g, int64_t i, uint32_t epoch, int32_t v, int32_t y)
+{
+    int32_t vc = clip(v, 0, cfg->T);
+    int32_t e = vc < y ? y - vc : vc - y;
+    uint32_t r[4];
+    draw(cfg, OTM_GATE, 0, (uint32_t)g, (uint64_t)i, epoch, r);
+    if (!((uint64_t)r[0] * (uint64_t)cfg->T < ((uint64_t)e << 32)))
+        return 0;
+    return vc < y ? 1 : 2;
 }
 
 /* threshold of the 16-bit uniform: P(u < thr) = 1/s */
@@ -287,13 +322,23 @@ void otm_type2(const otm_config *cfg, int32_t *st, const uint8_t *lit, int Cout)
  * tally of (i, class of g); ostar_gi at the stored previous output.  Either
  * may be NULL (synchronous training keeps neither). Returns 1 if feedback fired. */
 static int visit(const otm_config *cfg, int32_t *state, int32_t g, const uint8_t *lit,
-                 int64_t i, uint32_t epoch, int role /*0 none,1 target,2 negative*/,
-                 int32_t v_gate, int32_t *tally_ic, uint8_t *ostar_gi)
+                 int64_t i, uint32_t epoch, int role /*0 none,1 target,2 negative,3 regression*/,
+                 int32_t y_i, int32_t v_gate, int32_t *tally_ic, uint8_t *ostar_gi)
 {
     int L = 2 * cfg->o;
     int32_t *st = state + (size_t)g * L;
     int fired = 0;
-    if (role != 0) {
+    if (role == 3) {
+        int kind = otm_gate_regression(cfg, g, i, epoch, v_gate, y_i);
+        if (kind != 0) {
+            int Cout = clause_output(cfg, st, lit);
+            if (kind == 2)
+                otm_type2(cfg, st, lit, Cout);
+            else
+                otm_type1(cfg, st, lit, Cout, g, i, epoch);
+            fired = 1;
+        }
+    } else if (role != 0) {
         int target = (role == 1);
         int p = (polarity_sign(cfg, g) > 0);
         if (otm_gate(cfg, g, i, epoch, v_gate, target)) {
@@ -317,6 +362,7 @@ static int visit(const otm_config *cfg, int32_t *state, int32_t g, const uint8_t
 
 static int role_of(const otm_config *cfg, int c, int32_t y, uint32_t epoch, int64_t i)
 {
+    if (cfg->regression) return 3;
     if (c == y) return 1;
     if (c == otm_neg_class(cfg, epoch, i, y)) return 2;
     return 0;
@@ -360,7 +406,7 @@ void otm_feedback_step(const otm_config *cfg, int32_t *state, const uint8_t *X,
         for (int64_t i = i0; i < i0 + cnt && i < q; ++i) {
             literals(cfg, X + i * cfg->o, lit);
             int role = role_of(cfg, c, y[i], epoch, i);
-            fired += visit(cfg, state, g, lit, i, epoch, role, vhat[i * cfg->m + c],
+            fired += visit(cfg, state, g, lit, i, epoch, role, y[i], vhat[i * cfg->m + c],
                            &tally[i * cfg->m + c], &ostar[(size_t)g * q + i]);
         }
     }
@@ -388,7 +434,7 @@ void otm_feedback_step_subset(const otm_config *cfg, int32_t *state, const uint8
             int32_t scratch_tally = 0;
             literals(cfg, X + i * cfg->o, lit);
             int role = role_of(cfg, c, y[i], epoch, i);
-            fired += visit(cfg, state, g, lit, i, epoch, role, vhat[i * cfg->m + c],
+            fired += visit(cfg, state, g, lit, i, epoch, role, y[i], vhat[i * cfg->m + c],
                            &scratch_tally, &ostar_sub[(size_t)r * q + i]);
         }
     }
@@ -425,7 +471,7 @@ void otm_async_epoch(const otm_config *cfg, int32_t *state, const uint8_t *X,
             for (int g = 0; g < C; ++g) {
                 int c = g / cfg->n;
                 int role = role_of(cfg, c, y[i], epoch, i);
-                visit(cfg, state, g, lit, i, epoch, role, tally[i * cfg->m + c],
+                visit(cfg, state, g, lit, i, epoch, role, y[i], tally[i * cfg->m + c],
                       &tally[i * cfg->m + c], &ostar[(size_t)g * q + i]);
             }
         }
@@ -435,7 +481,7 @@ void otm_async_epoch(const otm_config *cfg, int32_t *state, const uint8_t *X,
             for (int64_t i = 0; i < q; ++i) {
                 literals(cfg, X + i * cfg->o, lit);
                 int role = role_of(cfg, c, y[i], epoch, i);
-                visit(cfg, state, g, lit, i, epoch, role, tally[i * cfg->m + c],
+                visit(cfg, state, g, lit, i, epoch, role, y[i], tally[i * cfg->m + c],
                       &tally[i * cfg->m + c], &ostar[(size_t)g * q + i]);
             }
         }
@@ -453,6 +499,12 @@ void otm_sync_epoch(const otm_config *cfg, int32_t *state, const uint8_t *X,
     uint8_t *lit = (uint8_t *)malloc((size_t)L);
     for (int64_t i = 0; i < q; ++i) {
         literals(cfg, X + i * cfg->o, lit);
+        if (cfg->regression) {
+            int32_t v0 = vote_sum(cfg, state, lit, 0);
+            for (int j = 0; j < cfg->n; ++j)
+                visit(cfg, state, j, lit, i, epoch, 3, y[i], v0, NULL, NULL);
+            continue;
+        }
         int cls[2];
         cls[0] = y[i];
         cls[1] = otm_neg_class(cfg, epoch, i, y[i]);
@@ -461,7 +513,7 @@ void otm_sync_epoch(const otm_config *cfg, int32_t *state, const uint8_t *X,
         v[1] = vote_sum(cfg, state, lit, cls[1]);
         for (int r = 0; r < 2; ++r)
             for (int j = 0; j < cfg->n; ++j)
-                visit(cfg, state, cls[r] * cfg->n + j, lit, i, epoch, r + 1, v[r], NULL, NULL);
+                visit(cfg, state, cls[r] * cfg->n + j, lit, i, epoch, r + 1, y[i], v[r], NULL, NULL);
     }
     free(lit);
 }

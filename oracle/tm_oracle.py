@@ -31,7 +31,7 @@ def build(force=False):
 class Config(ctypes.Structure):
     _fields_ = [("m", ctypes.c_int32), ("n", ctypes.c_int32), ("o", ctypes.c_int32),
                 ("N", ctypes.c_int32), ("T", ctypes.c_int32), ("s", ctypes.c_double),
-                ("seed", ctypes.c_uint64), ("boost", ctypes.c_int32)]
+                ("seed", ctypes.c_uint64), ("boost", ctypes.c_int32), ("regression", ctypes.c_int32)]
 
 
 _lib = None
@@ -43,6 +43,7 @@ def lib():
         _lib = ctypes.CDLL(build())
         _lib.otm_neg_class.restype = ctypes.c_int32
         _lib.otm_gate.restype = ctypes.c_int
+        _lib.otm_gate_regression.restype = ctypes.c_int
         _lib.otm_threshold.restype = ctypes.c_int32
     return _lib
 
@@ -61,8 +62,9 @@ def _chk(a, dtype, shape=None):
 class Oracle:
     """Holds a configuration and the TA states; methods mirror the C functions."""
 
-    def __init__(self, m, n, o, N, T, s, seed, init=True, boost=False):
-        self.cfg = Config(m, n, o, N, T, float(s), seed, 1 if boost else 0)
+    def __init__(self, m, n, o, N, T, s, seed, init=True, boost=False, regression=False):
+        assert not regression or m == 1
+        self.cfg = Config(m, n, o, N, T, float(s), seed, 1 if boost else 0, 1 if regression else 0)
         self.m, self.n, self.o, self.N, self.T, self.s, self.seed = m, n, o, N, T, float(s), seed
         self.C, self.L = m * n, 2 * o
         self.state = np.zeros((self.C, self.L), dtype=np.int32)
@@ -100,6 +102,11 @@ class Oracle:
     def gate(self, g, i, epoch, v, target):
         return int(lib().otm_gate(ctypes.byref(self.cfg), ctypes.c_int32(g), ctypes.c_int64(i),
                                   ctypes.c_uint32(epoch), ctypes.c_int32(v), ctypes.c_int(target)))
+
+    def gate_regression(self, g, i, epoch, v, y):
+        """0 no feedback, 1 Type I, 2 Type II."""
+        return int(lib().otm_gate_regression(ctypes.byref(self.cfg), ctypes.c_int32(g), ctypes.c_int64(i),
+                                             ctypes.c_uint32(epoch), ctypes.c_int32(v), ctypes.c_int32(y)))
 
     def threshold(self):
         return int(lib().otm_threshold(ctypes.byref(self.cfg)))

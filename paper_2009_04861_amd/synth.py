@@ -11,7 +11,8 @@ The generators stand in for the paper's datasets, which are not reproduced
 here: a noisy XOR (the paper's worked learning example, Section 2.2), an
 image-like 28x28 task, a sparse bag-of-words task (the paper's text workloads
 have thousands of clauses over up to ~100k sparse features, Section 4) and a
-large planted-conjunction stress case.
+large planted-conjunction stress case, and a tabular regression task with
+thermometer-coded columns (the paper's regression runs, Section 4.1).
 """
 import numpy as np
 
@@ -142,10 +143,35 @@ def planted_conjunctions(q=200000, o=20000, density=0.05, planted=64, width=3,
     return X, y
 
 
+def regression_like(q_train=13911, q_test=3478, features=16, thresholds=16, T=1280, noise=0.03,
+                    seed=DATA_SEED_BASE + 6):
+    """Tabular regression stand-in (the paper's regression runs use a 16-feature table of
+    17,389 rows split 80/20, T = n = 1280, s = 1.5): `features` uniform(0,1) columns, each
+    thermometer-coded with `thresholds` evenly spaced thresholds (o = features*thresholds
+    bits); the continuous target is a fixed smooth non-linear function of six columns plus
+    Gaussian noise, clipped to [0,1] and scaled to integers 0..T.  Test targets are noise-free."""
+    rng = np.random.default_rng(seed)
+    cuts = (np.arange(thresholds, dtype=np.float64) + 0.5) / thresholds
+
+    def draw(q, sigma):
+        u = rng.random((q, features))
+        f = (0.40 * np.exp(-((u[:, 0] - 0.55) / 0.18) ** 2) + 0.25 * u[:, 1]
+             + 0.20 * (u[:, 2] > 0.5) * u[:, 3] + 0.15 * u[:, 4] * u[:, 5])
+        f = np.clip(f + sigma * rng.standard_normal(q), 0.0, 1.0)
+        X = (u[:, :, None] > cuts[None, None, :]).reshape(q, features * thresholds).astype(np.uint8)
+        return np.ascontiguousarray(X), np.rint(f * T).astype(np.int32)
+
+    Xtr, ytr = draw(q_train, noise)
+    Xte, yte = draw(q_test, 0.0)
+    return Xtr, ytr, Xte, yte
+
+
 WORKLOADS = {
     # name: model hyper-parameters of the five benchmark configurations
     "noisy_xor": dict(m=2, n=10, o=12, N=100, T=15, s=3.9),
     "image_like": dict(m=10, n=2000, o=784, N=128, T=50, s=10.0),
     "text_like": dict(m=2, n=10000, o=10000, N=128, T=8000, s=2.0),
     "stress": dict(m=2, n=32768, o=20000, N=128, T=20000, s=5.0),
+    # regression mode: one bank of clauses, integer targets 0..T
+    "regression_like": dict(m=1, n=1280, o=256, N=128, T=1280, s=1.5, regression=True),
 }
