@@ -107,9 +107,17 @@ def make_workload(name, small=False, n_override=None, q_override=None):
         X, y = synth.planted_conjunctions(qtr + min(qtr, 20000))
         Xtr, ytr, Xte, yte = X[:qtr], y[:qtr], X[qtr:], y[qtr:]
         desc = "stress (configs[4]): %dx20000 train, %d test, 2 classes" % (qtr, len(yte))
+    elif name == "regression_like":
+        hp = dict(synth.WORKLOADS["regression_like"])
+        qtr = q_override or 13911
+        Xtr, ytr, Xte, yte = synth.regression_like(qtr, 3478, T=hp["T"])
+        desc = "regression_like (regression mode, targets 0..T): %dx256 train, %d test, one bank" % (qtr, len(yte))
     else:
         raise SystemExit("unknown workload %s" % name)
-    if n_override:
+    if n_override and hp.get("regression"):
+        hp["n"] = hp["T"] = n_override   # the paper's regression runs keep T = n
+        Xtr, ytr, Xte, yte = synth.regression_like(len(ytr), len(yte), T=hp["T"])
+    elif n_override:
         hp["n"] = n_override
         hp["T"] = max(1, int(round(0.8 * n_override)))
     desc += " x %d clauses, T=%d, s=%g, N=%d" % (hp["n"], hp["T"], hp["s"], hp["N"])
@@ -124,7 +132,7 @@ def cpu_baseline(hp, Xtr, ytr, Xte, seed, budget_s=15.0):
     tm_fit_epoch), plus tally pre-calculation and prediction on S examples."""
     import numpy as np
     from oracle import tm_oracle as O
-    ora = O.Oracle(hp["m"], hp["n"], hp["o"], hp["N"], hp["T"], hp["s"], seed)
+    ora = O.Oracle(hp["m"], hp["n"], hp["o"], hp["N"], hp["T"], hp["s"], seed, regression=hp.get("regression", False))
 
     def run(S):
         X = np.ascontiguousarray(Xtr[:S]); y = np.ascontiguousarray(ytr[:S])
@@ -160,6 +168,8 @@ def main():
     ap.add_argument("--clauses-per-class", type=int, default=None,
                     help="override n and set T = 0.8 n (clause-scaling sweep; not the headline configuration)")
     ap.add_argument("--q-train", type=int, default=None, help="override the number of training examples")
+    ap.add_argument("--clause-groups", type=int, default=1,
+                    help="sub-launches of consecutive clause ranges per training launch (tm_set_clause_groups)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference dispatch for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -180,6 +190,7 @@ def main():
     hp, (Xtr, ytr, Xte, yte), desc = make_workload(args.workload, args.small, args.clauses_per_class, args.q_train)
     q, qt = len(ytr), len(yte)
     tm = B.TsetlinMachine(seed=args.seed, **hp)
+    B.tm_set_clause_groups(tm.h, args.clause_groups)
     C, W = tm.C, 2 * tm.Wf
     Xd = tm.to_device_bits(synth.pack_features(Xtr))
     yd = torch.from_numpy(ytr).to(tm.dev)
@@ -231,7 +242,10 @@ def main():
     t1 = time.perf_counter()
     wall = t1 - t0
     cnt = tm.counters()
-    acc = float((pred.cpu().numpy() == yte).mean())
+    if hp.get("regression"):   # mean absolute error as a fraction of the target range instead of accuracy
+        acc = float(np.abs(pred.cpu().numpy() - yte).mean() / tm.T)
+    else:
+        acc = float((pred.cpu().numpy() == yte).mean())
 
     fit_ms = [e[0].elapsed_time(e[1]) for e in evs]
     sync_ms = [e[1].elapsed_time(e[2]) for e in evs]
@@ -259,7 +273,8 @@ def main():
     hbm_bytes = (2 * C * W * 32 + C * W * 4
                  + share * (2 * q * tm.Wf * 4 + 2 * tm.o * q / 8 + tm.m * q * 4 * 2 + q * 8)
                  + 2 * 8 * cnt["blocks_evaluated"] / max(1, n_train))
-    headline = args.workload == "image_like" and not (args.small or args.clauses_per_class or args.q_train)
+    headline = (args.workload == "image_like" and args.clause_groups == 1
+                and not (args.small or args.clauses_per_class or args.q_train))
     traffic = None
     if headline and MEASURED_TRAFFIC["image_like_train"]["fetch_kib"] > 0:
         t = MEASURED_TRAFFIC["image_like_train"]
@@ -292,7 +307,8 @@ def main():
             "type1_per_epoch": cnt["type1"] / args.steps,
             "tally_changes_per_epoch": cnt["tally_changes"] / args.steps,
             "blocks_evaluated_fraction": cnt["blocks_evaluated"] / max(1, args.steps * C * ((q + 63) // 64)),
-            "test_accuracy_after_run": acc,
+            ("test_mae_over_T_after_run" if hp.get("regression") else "test_accuracy_after_run"): acc,
+            "clause_groups": args.clause_groups,
         },
     }
     roof_train = {

@@ -55,7 +55,7 @@ typedef struct tm_handle tm_handle; /* opaque */
 
 /* Problem statement of the paper (Section 2.1, Section 2.2, Algorithm 1). */
 typedef struct {
-    int32_t n_classes;         /* m >= 2                                              */
+    int32_t n_classes;         /* m >= 2 (regression mode: exactly 1)                 */
     int32_t clauses_per_class; /* n, even and >= 2: half positive, half negative      */
     int32_t n_features;        /* o, 1 .. TM_MAX_FEATURES                             */
     int32_t states_per_action; /* N, 1 .. 128; a TA has 2N states, Include iff > N    */
@@ -65,7 +65,19 @@ typedef struct {
     int32_t device;            /* HIP device ordinal                                  */
     int32_t boost_true_positive; /* 0/1: strong Type I probability (s-1)/s replaced by 1
                                     (footnote of Section 2.2)                          */
+    int32_t regression;        /* 0/1: regression mode, see below                     */
 } tm_config;
+
+/* Regression mode (the regression Tsetlin machine measured in Section 4.1; the paper
+ * does not restate its update rule, the library follows the regression TM publication
+ * it cites).  One bank of n clauses (n_classes = 1) that all vote +1; the output is
+ * the vote sum clipped to [0, T]; y holds integer targets 0..T (the caller scales its
+ * continuous target to that range).  In Algorithm 1 the error becomes
+ * e = |y_i - clip(v_i, 0, T)| and a clause gives itself feedback with probability
+ * e/T: Type I where the vote sum lies below the target, Type II where it lies above.
+ * Evaluation, Type I / II feedback, tallies and their refresh are those of
+ * classification.  tm_class_sums* return the clipped vote sum [q][1]; tm_predict*
+ * return the same value in pred. */
 
 /* Size in bytes of the model state buffer (bit-sliced TA states + include
  * masks) for a configuration.  Host-only computation.  TM_EINVAL / TM_ELIMIT
@@ -89,7 +101,7 @@ int tm_create(const tm_config *cfg, void *state_buf, void *stream, tm_handle **o
 int tm_destroy(tm_handle *h);
 
 /* Binds a training set: X device uint32 [q][Wf], y device int32 [q] with
- * labels 0..m-1, ws device workspace of tm_train_ws_bytes(cfg, q) bytes
+ * labels 0..m-1 (regression mode: targets 0..T), ws device workspace of tm_train_ws_bytes(cfg, q) bytes
  * (256-byte aligned).  Builds the transposed copy of X and runs the tally
  * pre-calculation of Section 3.1 (every clause on every example; fills the
  * previous-output bits and the tallies).  Synchronises the stream once to
@@ -178,6 +190,15 @@ int tm_feedback_step(tm_handle *h, const int32_t *tally_snapshot, int64_t i0, in
  * launch of the training kernel each, so that a range's slice of the
  * transposed features stays resident in L2 (measurement aid). */
 int tm_train_chunk(tm_handle *h, int64_t *examples_per_launch);
+
+/* Schedule knob: every launch of the training kernel is split into `groups`
+ * consecutive sub-launches over clause ranges of equal size (1 <= groups <= C;
+ * default 1: all clauses at once).  The clauses of a sub-launch gate on the
+ * tallies as the sub-launches before it left them, which bounds how outdated a
+ * tally can be when thousands of clauses run in step; every such order is a
+ * legal schedule of Algorithm 1, and results under a frozen snapshot
+ * (tm_feedback_step) do not depend on it. */
+int tm_set_clause_groups(tm_handle *h, int32_t groups);
 
 /* Epoch counter used for the random counter of the next tm_fit_epoch. */
 int tm_set_epoch(tm_handle *h, uint32_t epoch);

@@ -19,7 +19,7 @@ EXPORTS = [
     "tm_state_bytes", "tm_train_ws_bytes", "tm_create", "tm_destroy", "tm_bind_train", "tm_fit_epoch", "tm_fit_batch",
     "tm_class_sums", "tm_predict", "tm_infer_ws_bytes", "tm_class_sums_ws", "tm_predict_ws", "tm_get_ta_state", "tm_set_ta_state", "tm_clause_outputs",
     "tm_sync_tallies", "tm_get_tallies", "tm_get_prev_outputs", "tm_feedback_step", "tm_train_chunk", "tm_set_epoch",
-    "tm_get_epoch", "tm_read_counters", "tm_kernel_timing", "tm_read_kernel_timing", "tm_strerror", "tm_last_hip_error",
+    "tm_get_epoch", "tm_set_clause_groups", "tm_read_counters", "tm_kernel_timing", "tm_read_kernel_timing", "tm_strerror", "tm_last_hip_error",
 ]
 
 
@@ -27,7 +27,8 @@ class tm_config(ctypes.Structure):
     _fields_ = [("n_classes", ctypes.c_int32), ("clauses_per_class", ctypes.c_int32),
                 ("n_features", ctypes.c_int32), ("states_per_action", ctypes.c_int32),
                 ("T", ctypes.c_int32), ("s", ctypes.c_double), ("seed", ctypes.c_uint64),
-                ("device", ctypes.c_int32), ("boost_true_positive", ctypes.c_int32)]
+                ("device", ctypes.c_int32), ("boost_true_positive", ctypes.c_int32),
+                ("regression", ctypes.c_int32)]
 
 
 class TMError(RuntimeError):
@@ -76,8 +77,9 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def make_config(m, n, o, N, T, s, seed, device=0, boost=False):
-    return tm_config(int(m), int(n), int(o), int(N), int(T), float(s), int(seed), int(device), 1 if boost else 0)
+def make_config(m, n, o, N, T, s, seed, device=0, boost=False, regression=False):
+    return tm_config(int(m), int(n), int(o), int(N), int(T), float(s), int(seed), int(device), 1 if boost else 0,
+                     1 if regression else 0)
 
 
 def tm_state_bytes(cfg):
@@ -182,6 +184,10 @@ def tm_set_epoch(h, epoch):
     _check(lib().tm_set_epoch(h, ctypes.c_uint32(epoch)), "tm_set_epoch")
 
 
+def tm_set_clause_groups(h, groups):
+    _check(lib().tm_set_clause_groups(h, ctypes.c_int32(groups)), "tm_set_clause_groups")
+
+
 def tm_get_epoch(h):
     e = ctypes.c_uint32(0)
     _check(lib().tm_get_epoch(h, ctypes.byref(e)), "tm_get_epoch")
@@ -214,11 +220,11 @@ class TsetlinMachine:
     Bit-packed uint32 data travels in int32 tensors (torch has no full uint32
     support); the bit patterns are what matters."""
 
-    def __init__(self, m, n, o, N, T, s, seed, device=0, boost=False):
+    def __init__(self, m, n, o, N, T, s, seed, device=0, boost=False, regression=False):
         self.m, self.n, self.o, self.N, self.T, self.s, self.seed = m, n, o, N, T, float(s), seed
         self.C, self.L, self.Wf = m * n, 2 * o, (o + 31) // 32
         self.dev = torch.device("cuda", device)
-        self.cfg = make_config(m, n, o, N, T, s, seed, device, boost)
+        self.cfg = make_config(m, n, o, N, T, s, seed, device, boost, regression)
         with torch.cuda.device(self.dev):
             self.state_buf = torch.empty(tm_state_bytes(self.cfg), dtype=torch.uint8, device=self.dev)
             self.h = tm_create(self.cfg, self.state_buf)

@@ -45,6 +45,7 @@ struct Dims {
     int m, n, o, N, T, C, Wf, W;
     uint32_t thr;      // 16-bit threshold: P(u < thr) = 1/s
     uint32_t boost;    // ~0 if true positives are boosted (strong Type I event certain), else 0
+    int regr;          // 1: regression mode (one bank of clauses that all vote +1, targets 0..T)
     uint32_t tailmask; // valid bits of the last feature word
     RngKey key;
 };
@@ -90,6 +91,7 @@ struct tm_handle {
     unsigned long long *counters;
     int32_t *flag;
     uint32_t epoch;
+    int clause_groups; // sub-launches of consecutive clause ranges per training launch
     uint64_t pairs_visited; // (clause, example) visits enqueued since the counters were last read
     int last_hip;
     // kernel timing (measurement aid): event pairs around the launches of the two main kernels
@@ -106,7 +108,9 @@ inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 int check_config(const tm_config *cfg)
 {
     if (!cfg) return TM_EINVAL;
-    if (cfg->n_classes < 2 || cfg->clauses_per_class < 2 || (cfg->clauses_per_class & 1)) return TM_EINVAL;
+    if (cfg->regression != 0 && cfg->regression != 1) return TM_EINVAL;
+    if (cfg->regression ? cfg->n_classes != 1 : cfg->n_classes < 2) return TM_EINVAL;
+    if (cfg->clauses_per_class < 2 || (cfg->clauses_per_class & 1)) return TM_EINVAL;
     if (cfg->n_features < 1) return TM_EINVAL;
     if (cfg->states_per_action < 1 || cfg->states_per_action > 128) return TM_EINVAL;
     if (cfg->T < 1 || cfg->T > (1 << 29)) return TM_EINVAL;
@@ -134,6 +138,7 @@ Dims make_dims(const tm_config *cfg)
     if (t > 65536.0) t = 65536.0;
     d.thr = (uint32_t)t;
     d.boost = cfg->boost_true_positive ? ~0u : 0u;
+    d.regr = cfg->regression ? 1 : 0;
     d.tailmask = (d.o & 31) ? ((1u << (d.o & 31)) - 1u) : ~0u;
     d.key.seed_lo = (uint32_t)(cfg->seed & 0xffffffffu);
     d.key.seed_hi = (uint32_t)(cfg->seed >> 32);
@@ -251,6 +256,7 @@ int launch_eval(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *bits, int6
     EvalArgs a;
     const EvalPtrs p{h->inc, X, bits, acc};
     a.q = q; a.Wf = d.Wf; a.W = d.W; a.C = d.C; a.n = d.n; a.m = d.m;
+    a.posmask = d.regr ? ~0ull : 0xAAAAAAAAAAAAAAAAull;
     a.bits_stride = bits_stride; a.acc_si = acc_si; a.acc_sc = acc_sc;
     // a wavefront takes one tile of 64 clauses and a range of examples (a multiple of 256);
     // ranges are sized so that the launch has a few thousand wavefronts per XCD
@@ -290,7 +296,7 @@ template <int WPL>
 void launch_train_t(const TrainPtrs &p, const TrainArgs &a, bool full, hipStream_t st)
 {
     const size_t lds = (size_t)a.lds_wave_words * TRAIN_WAVES * 4;
-    const dim3 grid((unsigned)((a.d.C + TRAIN_WAVES - 1) / TRAIN_WAVES)), block(64 * TRAIN_WAVES);
+    const dim3 grid((unsigned)((a.slot_hi - a.slot_lo + TRAIN_WAVES - 1) / TRAIN_WAVES)), block(64 * TRAIN_WAVES);
     if (full) hipLaunchKernelGGL((k_train<WPL, true>), grid, block, lds, st, p.X, p.XT, p.XB, p.gate, p.ngate, a);
     else hipLaunchKernelGGL((k_train<WPL, false>), grid, block, lds, st, p.X, p.XT, p.XB, p.gate, p.ngate, a);
 }
@@ -329,15 +335,12 @@ int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *li
     int64_t chunk = (((d.n + S - 1) / S) + 15) & ~(int64_t)15;
     S = (d.n + chunk - 1) / chunk;
     a.S = (int)S; a.chunk = (int)chunk; a.T = (S == 1) ? clampT : 0;
+    a.Tlo = d.regr ? 0 : -a.T; a.all_pos = d.regr;
     if (acc && S > 1) {
         // partial sums of several workgroups are added up: start from zero
-        if (acc_si == 1) {
-            const int rc = fill(h, acc, (size_t)d.m * acc_sc * 4, 0u, st);
-            if (rc) return rc;
-        } else {
-            const int rc = fill(h, acc, (size_t)q * d.m * 4, 0u, st);
-            if (rc) return rc;
-        }
+        // (either layout, [m][qp] or [q][m]: up to the last element written)
+        const int rc = fill(h, acc, (size_t)((q - 1) * acc_si + (d.m - 1) * acc_sc + 1) * 4, 0u, st);
+        if (rc) return rc;
     }
     int rc = timing_mark(h, timed_kind, true, st);
     if (rc) return rc;
@@ -351,11 +354,13 @@ int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *li
     if (rc) return rc;
     // what is left: clamp the added-up sums, pick the class
     if (acc && S > 1 && clampT > 0 && pred)
-        hipLaunchKernelGGL(k_clamp_argmax, dim3(blocks_for(q, 256)), dim3(256), 0, st, acc, pred, q, d.m, clampT);
+        hipLaunchKernelGGL(k_clamp_argmax, dim3(blocks_for(q, 256)), dim3(256), 0, st, acc, pred, q, d.m,
+                           d.regr ? 0 : -clampT, clampT, d.regr);
     else if (acc && S > 1 && clampT > 0)
-        hipLaunchKernelGGL(k_clamp, dim3(blocks_for(q * d.m, 256)), dim3(256), 0, st, acc, q * d.m, clampT);
+        hipLaunchKernelGGL(k_clamp, dim3(blocks_for(q * d.m, 256)), dim3(256), 0, st, acc, q * d.m,
+                           d.regr ? 0 : -clampT, clampT);
     else if (pred)
-        hipLaunchKernelGGL(k_argmax, dim3(blocks_for(q, 256)), dim3(256), 0, st, acc, pred, q, d.m);
+        hipLaunchKernelGGL(k_argmax, dim3(blocks_for(q, 256)), dim3(256), 0, st, acc, pred, q, d.m, d.regr);
     TM_HIP(h, hipGetLastError());
     return TM_OK;
 }
@@ -381,6 +386,7 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     TrainArgs a;
     const TrainPtrs p{h->X, h->XT, h->XB, h->gate, h->ngate};
     a.d = d; a.sat = h->sat; a.planes = h->planes; a.inc = h->inc; a.tally = h->tally;
+    a.y_regr = d.regr ? h->y : nullptr;
     a.vhat = vhat; a.ostar = h->ostar; a.fresh = h->fresh; a.order = h->order; a.counters = h->counters;
     a.q = (int32_t)h->q; a.qp = (int32_t)h->qp; a.Qw = (int32_t)h->Qw; a.epoch = h->epoch;
     a.lds_mask_words = (d.W + 3) & ~3;
@@ -394,12 +400,18 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     for (int64_t b = (i_begin / chunk) * chunk; b < i_end; b += chunk) {
         a.i_begin = (int32_t)std::max(b, i_begin);
         a.i_end = (int32_t)std::min(b + chunk, i_end);
+      for (int grp = 0; grp < h->clause_groups; ++grp) {
+        // clause ranges of (nearly) equal size; a later group gates on the tallies as the earlier ones left them
+        a.slot_lo = (int)((int64_t)d.C * grp / h->clause_groups);
+        a.slot_hi = (int)((int64_t)d.C * (grp + 1) / h->clause_groups);
+        if (a.slot_hi <= a.slot_lo) continue;
         PrepArgs pa;
         pa.y = h->y; pa.negcls = h->negcls; pa.tally = h->tally; pa.vhat = vhat; pa.fresh = h->fresh;
         pa.gate = h->gate; pa.ngate = h->ngate; pa.order = h->order; pa.seg_cnt = h->seg_cnt; pa.counters = h->counters;
         pa.i_begin = a.i_begin; pa.i_end = a.i_end; pa.qp = a.qp; pa.m = d.m; pa.n = d.n; pa.C = d.C; pa.T = d.T;
+        pa.regr = d.regr; pa.g_lo = a.slot_lo; pa.g_hi = a.slot_hi;
         pa.segs = (int)prep_segments(d, h->qp);
-        const int64_t items = std::max<int64_t>(a.i_end - a.i_begin, d.C);
+        const int64_t items = std::max<int64_t>(a.i_end - a.i_begin, a.slot_hi - a.slot_lo);
         const dim3 pgrid((unsigned)((items + PREP_SEG - 1) / PREP_SEG), (unsigned)(d.m + 1));
         hipLaunchKernelGGL(k_launch_prep<false>, pgrid, dim3(1024), 0, st, pa);
         TM_HIP(h, hipGetLastError());
@@ -421,12 +433,14 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
         TM_HIP(h, hipGetLastError());
         rc = timing_mark(h, TIMED_TRAIN, false, st);
         if (rc) return rc;
+      }
     }
     return TM_OK;
 }
 
 int run_negcls(tm_handle *h, hipStream_t st)
 {
+    if (h->d.regr) return TM_OK; // one bank of clauses: every example trains it
     hipLaunchKernelGGL(k_negcls, dim3(blocks_for(h->qp, 256)), dim3(256), 0, st, h->d, h->y, h->negcls, h->q,
                        h->qp, h->epoch);
     TM_HIP(h, hipGetLastError());
@@ -480,6 +494,7 @@ int tm_create(const tm_config *cfg, void *state_buf, void *stream, tm_handle **o
     if (!h) return TM_EINVAL;
     h->cfg = *cfg;
     h->d = make_dims(cfg);
+    h->clause_groups = 1;
     const uint32_t top = (uint32_t)(127 + h->d.N), bottom = (uint32_t)(128 - h->d.N);
     for (int b = 0; b < 8; ++b) {
         h->sat.kmax[b] = ((top >> b) & 1u) ? 0u : ~0u;
@@ -548,7 +563,8 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
     if (rc) return rc;
     rc = fill(h, h->counters, (size_t)COUNTER_SETS * 64, 0u, st);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_check_labels, dim3(blocks_for(q, 256)), dim3(256), 0, st, y, q, d.m, h->flag);
+    hipLaunchKernelGGL(k_check_labels, dim3(blocks_for(q, 256)), dim3(256), 0, st, y, q, d.regr ? d.T + 1 : d.m,
+                       h->flag);
     TM_HIP(h, hipGetLastError());
     int32_t bad = 0;
     TM_HIP(h, hipMemcpyAsync(&bad, h->flag, sizeof(bad), hipMemcpyDeviceToHost, st));
@@ -626,7 +642,8 @@ int tm_class_sums(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, voi
     if (rc) return rc;
     rc = launch_eval(h, X, q, nullptr, 0, sums, d.m, 1, st);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_clamp, dim3(blocks_for(q * d.m, 256)), dim3(256), 0, st, sums, q * d.m, d.T);
+    hipLaunchKernelGGL(k_clamp, dim3(blocks_for(q * d.m, 256)), dim3(256), 0, st, sums, q * d.m, d.regr ? 0 : -d.T,
+                       d.T);
     TM_HIP(h, hipGetLastError());
     return TM_OK;
 }
@@ -639,7 +656,7 @@ int tm_predict(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, int32_
     const int rc = tm_class_sums(h, X, q, sums_scratch, stream);
     if (rc) return rc;
     hipLaunchKernelGGL(k_argmax, dim3(blocks_for(q, 256)), dim3(256), 0, (hipStream_t)stream, sums_scratch, pred, q,
-                       h->d.m);
+                       h->d.m, h->d.regr);
     TM_HIP(h, hipGetLastError());
     return TM_OK;
 }
@@ -752,6 +769,13 @@ int tm_train_chunk(tm_handle *h, int64_t *examples_per_launch)
 {
     if (!h || !examples_per_launch) return TM_EINVAL;
     *examples_per_launch = train_chunk(h->d);
+    return TM_OK;
+}
+
+int tm_set_clause_groups(tm_handle *h, int32_t groups)
+{
+    if (!h || groups < 1 || groups > h->d.C) return TM_EINVAL;
+    h->clause_groups = groups;
     return TM_OK;
 }
 

@@ -107,7 +107,9 @@ struct SparseArgs {
     int lit_cap;         // entries per literal list
     int ranges, by_xcd;  // ranges of 2048 examples; workgroup -> (range, class, share) mapping
     int S, chunk;        // clauses of a class are split over S workgroups, `chunk` (a multiple of 16) each
-    int T;               // > 0: the sums are clamped to [-T, T] (only with S = 1)
+    int T;               // > 0: the sums are clamped to [Tlo, T] (only with S = 1)
+    int Tlo;             // -T, or 0 in regression mode
+    int all_pos;         // regression mode: every clause votes +1
 };
 
 // Output of clause g on the 32 examples of this lane's word, taken from its include masks
@@ -247,7 +249,7 @@ __global__ __launch_bounds__(64 * SP_WAVES) void k_eval_sparse(const uint32_t *_
         }
     }
     if (!a.acc) return;
-    const bool positive = (wave & 1) != 0; // odd index within the class: positive polarity
+    const bool positive = (wave & 1) != 0 || a.all_pos; // odd index within the class: positive polarity
 #pragma unroll 4
     for (int e = 0; e < 32; ++e) {
         int v = 0;
@@ -261,7 +263,7 @@ __global__ __launch_bounds__(64 * SP_WAVES) void k_eval_sparse(const uint32_t *_
         if (i >= a.q) continue;
         int v = sums[(idx >> 5) * 33 + (idx & 31)];
         int32_t *dst = a.acc + i * a.acc_si + (int64_t)c * a.acc_sc;
-        if (a.S == 1) *dst = a.T > 0 ? min(max(v, -a.T), a.T) : v;
+        if (a.S == 1) *dst = a.T > 0 ? min(max(v, a.Tlo), a.T) : v;
         else if (v) atomicAdd(dst, v);
     }
 }

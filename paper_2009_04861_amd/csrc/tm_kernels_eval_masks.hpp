@@ -19,6 +19,7 @@ struct EvalArgs {
     int64_t bits_stride;
     int64_t acc_si, acc_sc;
     int64_t ex_per_wave; // multiple of 256
+    uint64_t posmask;    // lanes of a tile whose clause votes +1: the odd ones, or all in regression mode
 };
 
 // A wavefront owns 64 consecutive clauses (a "tile") and a range of examples.
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(64) void k_eval_resident(const uint32_t *__restrict
     const bool one_class = (c_first == c_last);
     const int my_class = gv ? g / a.n : -1;
     const uint64_t cm0 = ballot(my_class == c_first);
-    const uint64_t cmpos0 = cm0 & 0xAAAAAAAAAAAAAAAAull, cmneg0 = cm0 & 0x5555555555555555ull;
+    const uint64_t cmpos0 = cm0 & a.posmask, cmneg0 = cm0 & ~a.posmask;
     const int64_t safe_end = (a.Wf == CH) ? e_end : min(e_end, a.q - 1);
 
     for (int64_t b0 = e_begin; b0 < e_end; b0 += 64) {
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(64) void k_eval_resident(const uint32_t *__restrict
             if (!one_class) { // tiles that straddle class boundaries: remaining classes from the stored bits
                 for (int cc = c_first + 1; cc <= c_last; ++cc) {
                     const uint64_t cm = ballot(my_class == cc);
-                    const uint64_t cmpos = cm & 0xAAAAAAAAAAAAAAAAull, cmneg = cm & 0x5555555555555555ull;
+                    const uint64_t cmpos = cm & a.posmask, cmneg = cm & ~a.posmask;
                     int av = 0;
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
@@ -259,8 +260,8 @@ __global__ __launch_bounds__(64) void k_eval_stream(const uint32_t *__restrict__
         if (acc) {
             for (int cc = c_first; cc <= c_last; ++cc) {
                 const uint64_t cm = ballot(my_class == cc);
-                const uint64_t cmpos = cm & 0xAAAAAAAAAAAAAAAAull; // odd index within class: positive polarity
-                const uint64_t cmneg = cm & 0x5555555555555555ull;
+                const uint64_t cmpos = cm & a.posmask; // odd index within class: positive polarity
+                const uint64_t cmneg = cm & ~a.posmask;
                 int accv[4] = {0, 0, 0, 0};
 #pragma unroll
                 for (int fb = 0; fb < 8; ++fb) {

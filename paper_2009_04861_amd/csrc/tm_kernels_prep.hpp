@@ -10,7 +10,8 @@ namespace tsetlin {
 //
 // Task c < m: gate list of class c = the examples of the range, ascending, whose gate can
 // open for a clause of c, packed as (example << 1 | target): target 1 where y_i = c,
-// target 0 where c is the class drawn against y_i, and error e > 0 under the tally as it
+// target 0 where c is the class drawn against y_i (regression mode: every example, the bit
+// says whether the vote sum lies below the target), and error e > 0 under the tally as it
 // stands now (or under the snapshot vhat).  The examples with e = 0 are left out: their
 // gate probability e/2T is 0, so a clause that read this tally would not act, and reading
 // a tally that is one launch old is within the method's premise of outdated tallies
@@ -31,6 +32,8 @@ struct PrepArgs {
     int32_t *gate, *ngate, *order, *seg_cnt; // seg_cnt [m + 1][segs][2]
     unsigned long long *counters;
     int i_begin, i_end, qp, m, n, C, T, segs;
+    int regr; // regression mode: no classes, targets y in [0, T]
+    int g_lo, g_hi; // clauses of the launch (a launch may cover a range of the clauses only)
 };
 
 constexpr int COUNTER_SETS = 64; // interleaved copies of the 8 event counters
@@ -46,7 +49,7 @@ __global__ __launch_bounds__(1024) void k_launch_prep(const PrepArgs a)
     const int task = blockIdx.y, seg = blockIdx.x;
     const bool ordering = task == a.m;
     const int c = task;
-    const int lo = ordering ? 0 : a.i_begin, hi = ordering ? a.C : a.i_end;
+    const int lo = ordering ? a.g_lo : a.i_begin, hi = ordering ? a.g_hi : a.i_end;
     const int p0 = lo + seg * PREP_SEG;
     if (p0 >= hi) return; // the grid is sized for the longer of the two kinds of task
     const int32_t *vsrc = a.vhat ? a.vhat + c : a.tally + (int64_t)c * a.qp;
@@ -67,12 +70,20 @@ __global__ __launch_bounds__(1024) void k_launch_prep(const PrepArgs a)
             f[r] = live && stale;
             bk[r] = live && !stale;
         } else {
-            const int yy = a.y[tc], ng = a.negcls[tc], v = vsrc[(int64_t)tc * vstride];
-            tg[r] = live && yy == c;
-            const bool match = live && (tg[r] || ng == c);
-            const int vc = min(max(v, -a.T), a.T);
-            n_seen += match ? 1 : 0;
-            f[r] = match && (tg[r] ? a.T - vc : a.T + vc) > 0; // Algorithm 1: error of the recorded vote sum
+            const int yy = a.y[tc], v = vsrc[(int64_t)tc * vstride];
+            if (a.regr) { // one bank of clauses: an example is listed unless its clipped vote sum equals its target
+                const int vc = min(max(v, 0), a.T);
+                tg[r] = live && vc < yy;
+                n_seen += live ? 1 : 0;
+                f[r] = live && vc != yy;
+            } else {
+                const int ng = a.negcls[tc];
+                tg[r] = live && yy == c;
+                const bool match = live && (tg[r] || ng == c);
+                const int vc = min(max(v, -a.T), a.T);
+                n_seen += match ? 1 : 0;
+                f[r] = match && (tg[r] ? a.T - vc : a.T + vc) > 0; // Algorithm 1: error of the recorded vote sum
+            }
         }
     }
     uint64_t bf[PREP_ROUNDS], bb[PREP_ROUNDS];
@@ -121,12 +132,13 @@ __global__ __launch_bounds__(1024) void k_launch_prep(const PrepArgs a)
             for (int sh = 32; sh > 0; sh >>= 1) n_seen += __shfl_down(n_seen, sh, 64);
             if (lane == 0 && n_seen)
                 atomicAdd(&a.counters[((seg * 16 + wave) & (COUNTER_SETS - 1)) * 8 + 4],
-                          (unsigned long long)n_seen * (unsigned long long)a.n);
+                          (unsigned long long)n_seen *
+                              (unsigned long long)max(0, min((c + 1) * a.n, a.g_hi) - max(c * a.n, a.g_lo)));
         }
         return;
     }
     __syncthreads();
-    int32_t *out = ordering ? a.order : a.gate + (int64_t)c * a.qp;
+    int32_t *out = ordering ? a.order + a.g_lo : a.gate + (int64_t)c * a.qp;
 #pragma unroll
     for (int r = 0; r < PREP_ROUNDS; ++r) {
         const int t = p0 + r * 1024 + tid;
@@ -137,7 +149,7 @@ __global__ __launch_bounds__(1024) void k_launch_prep(const PrepArgs a)
             out[before_f + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bf[r] >> 32),
                                                           __builtin_amdgcn_mbcnt_lo((uint32_t)bf[r], 0u))] = value;
         if (bk[r])
-            out[a.C - 1 - (before_b + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bb[r] >> 32),
+            out[a.g_hi - a.g_lo - 1 - (before_b + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bb[r] >> 32),
                                                                      __builtin_amdgcn_mbcnt_lo((uint32_t)bb[r], 0u)))] = value;
     }
     // the last segment of a gate list knows its length

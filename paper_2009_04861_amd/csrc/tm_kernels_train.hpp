@@ -16,6 +16,7 @@ struct TrainArgs {
     uint32_t *inc;
     int32_t *tally;
     const int32_t *vhat; // [q][m] snapshot the gate reads instead of the live tally, or null
+    const int32_t *y_regr; // regression mode: targets [q] in 0..T; null for classification
     uint32_t *ostar;
     int32_t *fresh; // [C][4] per clause: examples whose stored output may be outdated lie in [plo,phi) or [slo,qp)
     const int32_t *order; // [C] clause handled by each wavefront of the launch
@@ -26,6 +27,7 @@ struct TrainArgs {
     int lds_off_words;  // Wf + EVAL_PAD rounded up to a multiple of 4
     int lds_wave_words; // LDS words per wavefront
     int QW;             // words per row of XB
+    int slot_lo, slot_hi; // positions of `order` this launch covers
 };
 
 constexpr int EVAL_PAD = 16; // empty entries after the list: a group may read that far past its end
@@ -171,8 +173,8 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     const Dims &d = a.d;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int slot = blockIdx.x * TRAIN_WAVES + wave;
-    if (slot >= d.C) return; // whole wavefront; the kernel has no workgroup-wide barrier
+    const int slot = a.slot_lo + blockIdx.x * TRAIN_WAVES + wave;
+    if (slot >= a.slot_hi) return; // whole wavefront; the kernel has no workgroup-wide barrier
     const int g = __builtin_amdgcn_readfirstlane(a.order[slot]);
     uint32_t *lmask = lds + wave * a.lds_wave_words;        // [W] include masks, literal-word order
     uint32_t *eoff = lmask + a.lds_mask_words;              // [Wf + EVAL_PAD] (rounded to 4 words)
@@ -180,7 +182,8 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     uint32_t *llist = lmask + a.lds_wave_words - (TRAIN_LIT_MAX + 8); // [TRAIN_LIT_MAX + 8] literal list for the sweeps
 
     const int c = g / d.n;
-    const bool pos = ((g - c * d.n) & 1) != 0; // odd index within the class: positive polarity
+    const bool regr = a.y_regr != nullptr;        // regression mode: every clause votes +1
+    const bool pos = ((g - c * d.n) & 1) != 0 || regr; // odd index within the class: positive polarity
     const int sign = pos ? 1 : -1;
     const int T = d.T;
     const uint32_t row_bytes = (uint32_t)a.qp * 4u;
@@ -376,8 +379,10 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
         return a.vhat ? a.vhat[(int64_t)i * d.m + c]
                       : __hip_atomic_load(&tally_c[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
+    auto load_y = [&](int ent) { return (regr && ent >= 0) ? a.y_regr[ent >> 1] : 0; };
     int ent_cur = load_ent(k_lo);
     int v_cur = load_v(ent_cur);
+    int y_cur = load_y(ent_cur);
     int ent_nxt = load_ent(k_lo + 64);
 
     for (int k0 = k_lo;; k0 += 64) {
@@ -385,21 +390,33 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
         uint64_t fmask = 0, tmask = 0;
         int iv = 0;
         if (!last) {
-            const int ent = ent_cur, v = v_cur;
+            const int ent = ent_cur, v = v_cur, yv = y_cur;
             ent_cur = ent_nxt;
             v_cur = load_v(ent_cur);
+            y_cur = load_y(ent_cur);
             ent_nxt = load_ent(k0 + 128);
             const bool valid = ent >= 0;
             iv = ent >> 1;
-            const bool target = (ent & 1) != 0;
+            bool target = (ent & 1) != 0;
             bool fire = false, open = false;
             if (valid) {
-                const int vc = min(max(v, -T), T);
-                const int e = target ? T - vc : T + vc; // Algorithm 1: error of the recorded vote sum
+                int e, span;
+                if (regr) {
+                    // regression: error of the clipped vote sum against the target, probability e/T;
+                    // below the target the clause is trained towards 1, above it towards 0
+                    const int vc = min(max(v, 0), T);
+                    target = vc < yv;
+                    e = target ? yv - vc : vc - yv;
+                    span = T;
+                } else {
+                    const int vc = min(max(v, -T), T);
+                    e = target ? T - vc : T + vc; // Algorithm 1: error of the recorded vote sum
+                    span = 2 * T;
+                }
                 open = e > 0;
                 if (open) {
                     const U4 r = draw(d.key, STREAM_GATE, 0, (uint32_t)g, (uint64_t)(uint32_t)iv, a.epoch);
-                    fire = (uint64_t)r.x * (uint64_t)(2 * (int64_t)T) < ((uint64_t)e << 32);
+                    fire = (uint64_t)r.x * (uint64_t)span < ((uint64_t)e << 32);
                 }
             }
             fmask = ballot(fire);

@@ -94,6 +94,7 @@ __global__ void k_transpose_x(const uint32_t *X, uint32_t *XT, int64_t q, int64_
     XT[t] = (i < q) ? X[i * Wf + fw] : 0u;
 }
 
+// labels must lie in [0, m) (regression mode: targets in [0, T], m = T + 1)
 __global__ void k_check_labels(const int32_t *y, int64_t q, int m, int32_t *flag)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -116,18 +117,23 @@ __global__ void k_negcls(Dims d, const int32_t *y, int32_t *negcls, int64_t q, i
     negcls[i] = r;
 }
 
-// sums[i][c] = clamp(sums[i][c], -T, T)
-__global__ void k_clamp(int32_t *sums, int64_t n, int T)
+// sums[i][c] = clamp(sums[i][c], lo, T): lo = -T, or 0 in regression mode
+__global__ void k_clamp(int32_t *sums, int64_t n, int lo, int T)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < n) sums[t] = min(max(sums[t], -T), T);
+    if (t < n) sums[t] = min(max(sums[t], lo), T);
 }
 
-// pred[i] = lowest class index with the largest (already clamped) sum
-__global__ void k_argmax(const int32_t *sums, int32_t *pred, int64_t q, int m)
+// pred[i] = lowest class index with the largest (already clamped) sum; in regression mode
+// the clamped vote sum itself
+__global__ void k_argmax(const int32_t *sums, int32_t *pred, int64_t q, int m, int regr)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= q) return;
+    if (regr) {
+        pred[i] = sums[i];
+        return;
+    }
     int best = 0;
     int32_t bv = sums[i * m];
     for (int c = 1; c < m; ++c) {
@@ -141,21 +147,21 @@ __global__ void k_argmax(const int32_t *sums, int32_t *pred, int64_t q, int m)
 }
 
 // both of the above in one pass over the unclamped sums
-__global__ void k_clamp_argmax(int32_t *sums, int32_t *pred, int64_t q, int m, int T)
+__global__ void k_clamp_argmax(int32_t *sums, int32_t *pred, int64_t q, int m, int lo, int T, int regr)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= q) return;
     int best = 0;
     int32_t bv = 0;
     for (int c = 0; c < m; ++c) {
-        const int32_t v = min(max(sums[i * m + c], -T), T);
+        const int32_t v = min(max(sums[i * m + c], lo), T);
         sums[i * m + c] = v;
         if (c == 0 || v > bv) {
             bv = v;
             best = c;
         }
     }
-    pred[i] = best;
+    pred[i] = regr ? bv : best;
 }
 
 // out[i][c] = tally[c][i]

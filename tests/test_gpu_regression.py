@@ -1,0 +1,302 @@
+"""GPU parity of regression mode (regression Tsetlin machine, Section 4.1) against the CPU
+oracle, through the C boundary: one bank of clauses that all vote +1, output clipped to
+[0, T], targets 0..T, feedback probability |y - v|/T, Type I below the target and Type II
+above.  Integer / bit work throughout: the bar is exact equality.  Asynchronous training
+is checked by invariants and by the mean absolute error it reaches."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tm_oracle as O
+from paper_2009_04861_amd import binding as B
+from paper_2009_04861_amd import synth
+from tests.helpers import bits_to_u8, dev_bits, dev_i32, gpu_state_as_oracle, push_state, sparse_random_state
+
+pytestmark = pytest.mark.gpu
+
+# (n, o, N, T, s): one and several register slots per lane, ragged tails, T below / equal / above n
+SHAPES = [
+    (10, 12, 100, 10, 3.9),
+    (70, 37, 20, 40, 1.5),
+    (200, 256, 128, 200, 1.5),      # the regression workload's feature count
+    (36, 1100, 64, 20, 5.0),        # 2 register slots
+    (8, 2500, 128, 8, 2.0),         # 3 slots
+    (4, 10000, 128, 3, 2.0),        # 10 slots: block-by-block sweeps only
+]
+
+
+def pair(n, o, N, T, s, seed):
+    return (O.Oracle(1, n, o, N, T, s, seed, regression=True),
+            B.TsetlinMachine(1, n, o, N, T, s, seed, regression=True))
+
+
+def rand_problem(rng, q, o, T, density=0.3):
+    X = (rng.random((q, o)) < density).astype(np.uint8)
+    y = rng.integers(0, T + 1, size=q).astype(np.int32)
+    return X, y
+
+
+def test_configuration_checks(device):
+    with pytest.raises(B.TMError):
+        B.TsetlinMachine(2, 10, 12, 100, 10, 3.9, 1, regression=True)     # regression has one bank of clauses
+    with pytest.raises(B.TMError):
+        B.TsetlinMachine(1, 10, 12, 100, 10, 3.9, 1)                      # classification needs two classes
+    gpu = B.TsetlinMachine(1, 10, 12, 100, 10, 3.9, 1, regression=True)
+    X = np.zeros((5, 12), dtype=np.uint8)
+    for bad in (-1, 11):
+        y = np.array([0, 10, 5, bad, 3], dtype=np.int32)
+        with pytest.raises(B.TMError):
+            gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, np.array([0, 10, 5, 7, 3], dtype=np.int32)))
+    gpu.close()
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("q", [1, 300, 2100])
+def test_inference_matches(shape, q, device):
+    n, o, N, T, s = shape
+    print("regression inference", shape, q, flush=True)
+    rng = np.random.default_rng(q + o)
+    ora, gpu = pair(n, o, N, T, s, 7)
+    assert np.array_equal(gpu_state_as_oracle(gpu), ora.state)
+    ora.state[:] = sparse_random_state(rng, ora.C, ora.L, N, 1.5 / o)
+    push_state(gpu, ora.state)
+    X, _ = rand_problem(rng, q, o, T)
+    Xd = dev_bits(gpu, X)
+    assert np.array_equal(bits_to_u8(gpu.clause_outputs(Xd), q), ora.clause_outputs(X).T)
+    want = ora.class_sums(X)
+    assert want.min() >= 0 and (q < 300 or want.max() > 0)
+    for lists in (True, False):
+        assert np.array_equal(gpu.class_sums(Xd, lists=lists).cpu().numpy(), want)
+        assert np.array_equal(gpu.predict(Xd, lists=lists).cpu().numpy(), ora.predict(X))
+    gpu.close()
+
+
+def test_output_is_clipped_at_T_and_counts_every_clause(device):
+    # empty clauses are satisfied by everything: raw sum n, clipped output T
+    for n, T in [(64, 5), (6, 6), (4082, 3000), (9000, 9000)]:
+        ora, gpu = pair(n, 20, 128, T, 3.0, 3)
+        ora.state[:] = 1
+        ora.state[0:n:3, 0] = 256          # a third of the clauses require x0
+        push_state(gpu, ora.state)
+        X = np.zeros((70, 20), dtype=np.uint8)
+        X[::2, 0] = 1
+        Xd = dev_bits(gpu, X)
+        want = ora.class_sums(X)
+        assert want[0, 0] == min(n, T) and want[1, 0] == min(n - (n + 2) // 3, T)
+        for lists in (True, False):
+            assert np.array_equal(gpu.class_sums(Xd, lists=lists).cpu().numpy(), want)
+        gpu.bind_train(Xd, dev_i32(gpu, np.zeros(70, dtype=np.int32)))
+        assert np.array_equal(gpu.tallies().cpu().numpy(), ora.class_sums(X, clamp=False))
+        gpu.close()
+
+
+def run_frozen(ora, gpu, X, y, epoch, i0, cnt, snap, tally, ostar):
+    gpu.feedback_step(dev_i32(gpu, snap), i0, cnt)
+    return ora.feedback_step(X, y, snap, tally, ostar, epoch, i0, cnt)
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_feedback_step_matches_bit_exactly(shape, device):
+    n, o, N, T, s = shape
+    print("regression feedback", shape, flush=True)
+    rng = np.random.default_rng(21)
+    q = 200
+    ora, gpu = pair(n, o, N, T, s, 99)
+    X, y = rand_problem(rng, q, o, T)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    assert np.array_equal(gpu.tallies().cpu().numpy(), tally)
+    assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar)
+    total = 0
+    for step, (i0, cnt) in enumerate([(0, 1), (1, 70), (71, 57), (128, 72), (0, q), (0, q), (0, q)]):
+        B.tm_set_epoch(gpu.h, step)
+        # the exact tallies, then snapshots with sums below 0, above T and equal to the target
+        snap = tally.copy() if step < 5 else rng.integers(-3, T + 4, size=(q, 1)).astype(np.int32)
+        if step == 6:
+            snap[::3, 0] = y[::3]
+        total += run_frozen(ora, gpu, X, y, step, i0, cnt, snap, tally, ostar)
+        assert np.array_equal(gpu_state_as_oracle(gpu), ora.state), ("state", step)
+        assert np.array_equal(gpu.tallies().cpu().numpy(), tally), ("tally", step)
+        assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar), ("ostar", step)
+    assert total > 0
+    assert gpu.counters()["fired"] == total
+    gpu.close()
+
+
+@pytest.mark.parametrize("s", [1.0, 1.5, 25.0])
+@pytest.mark.parametrize("N", [3, 128])
+def test_feedback_saturation_paths(s, N, device):
+    print("regression saturation", s, N, flush=True)
+    n, o, T = 16, 45, 12
+    rng = np.random.default_rng(5)
+    q = 150
+    ora, gpu = pair(n, o, N, T, s, 17)
+    X, y = rand_problem(rng, q, o, T, density=0.5)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    for ep in range(10):
+        B.tm_set_epoch(gpu.h, ep)
+        run_frozen(ora, gpu, X, y, ep, 0, q, tally.copy(), tally, ostar)
+    assert np.array_equal(gpu_state_as_oracle(gpu), ora.state)
+    assert np.array_equal(gpu.tallies().cpu().numpy(), tally)
+    assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar)
+    gpu.close()
+
+
+def test_several_launches_and_list_sweeps(device):
+    """5,000 examples (two segments of the launch preparation), sparse clauses pushed after
+    bind so that every stored output is outdated, and a snapshot that equals the target on
+    most examples: long runs of blocks without a fired gate are refreshed through literal lists."""
+    n, o, N, T, s = 18, 100, 64, 9, 4.0
+    rng = np.random.default_rng(31)
+    q = 5000
+    ora, gpu = pair(n, o, N, T, s, 5)
+    X, y = rand_problem(rng, q, o, T)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    ora.state[:] = sparse_random_state(rng, ora.C, ora.L, N, 2.5 / o)
+    push_state(gpu, ora.state)
+    gpu.counters()
+    snap = y.reshape(q, 1).copy()
+    open_ = rng.random(q) < 0.02
+    snap[open_, 0] = rng.integers(0, T + 1, size=int(open_.sum()))
+    fired = 0
+    for ep, (i0, cnt) in enumerate([(1234, 3000), (0, q), (4097, 903), (0, q)]):
+        B.tm_set_epoch(gpu.h, ep)
+        fired += run_frozen(ora, gpu, X, y, ep, i0, cnt, snap, tally, ostar)
+        assert np.array_equal(gpu_state_as_oracle(gpu), ora.state), ep
+        assert np.array_equal(gpu.tallies().cpu().numpy(), tally), ep
+        assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar), ep
+    c = gpu.counters()
+    assert fired > 20 and c["fired"] == fired and c["blocks_listed"] > 0
+    gpu.close()
+
+
+def test_asynchronous_epochs_keep_the_invariants(device):
+    T = 60
+    Xtr, ytr, _, _ = synth.regression_like(3000, 10, features=6, thresholds=8, T=T, seed=5)
+    n, o = 60, Xtr.shape[1]
+    ora, gpu = pair(n, o, 128, T, 2.0, 3)
+    gpu.bind_train(dev_bits(gpu, Xtr), dev_i32(gpu, ytr))
+    for ep in range(4):
+        gpu.fit_epoch()
+        st = gpu.get_ta_state()
+        assert int(st.max()) <= 255
+        # the tally is the plain sum of the stored outputs at any quiet moment
+        prev = bits_to_u8(gpu.prev_outputs(), len(ytr))
+        assert np.array_equal(gpu.tallies().cpu().numpy()[:, 0], prev.astype(np.int32).sum(axis=0))
+    gpu.sync_tallies()
+    ora.state[:] = gpu_state_as_oracle(gpu)
+    assert np.array_equal(gpu.tallies().cpu().numpy(), ora.class_sums(Xtr, clamp=False))
+    assert np.array_equal(bits_to_u8(gpu.prev_outputs(), len(ytr)), ora.clause_outputs(Xtr).T)
+    gpu.close()
+
+
+def test_clause_groups_do_not_change_frozen_results(device):
+    # sub-launches over clause ranges are a schedule: under a frozen snapshot every schedule gives the same result
+    n, o, N, T, s = 70, 37, 20, 40, 1.5
+    rng = np.random.default_rng(41)
+    q = 700
+    ora, gpu = pair(n, o, N, T, s, 9)
+    X, y = rand_problem(rng, q, o, T)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    for ep, groups in enumerate([1, 3, 70, 8]):
+        B.tm_set_clause_groups(gpu.h, groups)
+        B.tm_set_epoch(gpu.h, ep)
+        run_frozen(ora, gpu, X, y, ep, 0, q, tally.copy(), tally, ostar)
+        assert np.array_equal(gpu_state_as_oracle(gpu), ora.state), groups
+        assert np.array_equal(gpu.tallies().cpu().numpy(), tally), groups
+        assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar), groups
+    assert gpu.counters()["candidates"] == 4 * q * n
+    with pytest.raises(B.TMError):
+        B.tm_set_clause_groups(gpu.h, 0)
+    with pytest.raises(B.TMError):
+        B.tm_set_clause_groups(gpu.h, n + 1)
+    gpu.close()
+
+
+def test_training_error_against_the_oracle(device):
+    """Mean absolute error on a regression task with 400 clauses (mean of the last 8 of 16 epochs,
+    3 seeds), asynchronous GPU training against the oracle's synchronous training.  Regression is a
+    control loop on the error: when all clauses run in step, each sees the tally of an example as
+    its previous visit left it, all correct the same error at once and the output overshoots (the
+    oracle shows the same with such tallies).  With the launch split into 16 clause groups, a group
+    sees what the groups before it did, and the error must come within 2 % of the target range of
+    synchronous training.  Asynchronous training is not reproducible run to run: a statistical check."""
+    T = n = 400
+    Xtr, ytr, Xte, yte = synth.regression_like(4000, 1000, features=6, thresholds=16, T=T, seed=77)
+    o = Xtr.shape[1]
+    base = float(np.abs(yte - np.median(ytr)).mean())
+    mg, mc = [], []
+    for seed in (1, 2, 3):
+        print("regression error seed", seed, flush=True)
+        ora, gpu = pair(n, o, 128, T, 1.5, seed)
+        B.tm_set_clause_groups(gpu.h, 16)
+        gpu.bind_train(dev_bits(gpu, Xtr), dev_i32(gpu, ytr))
+        Xd = dev_bits(gpu, Xte)
+        eg, ec = [], []
+        for ep in range(16):
+            gpu.fit_epoch()
+            ora.sync_epoch(Xtr, ytr, ep)
+            if ep >= 8:
+                eg.append(np.abs(gpu.predict(Xd).cpu().numpy() - yte).mean())
+                ec.append(np.abs(ora.predict(Xte) - yte).mean())
+        mg.append(np.mean(eg))
+        mc.append(np.mean(ec))
+        gpu.close()
+    g, c = float(np.mean(mg)), float(np.mean(mc))
+    print("mean absolute error (T = %d): gpu async, 16 clause groups %.2f, oracle synchronous %.2f, constant predictor %.2f"
+          % (T, g, c, base), flush=True)
+    assert c < 0.5 * base
+    assert g <= c + 0.02 * T, (mg, mc, base)
+
+
+def test_regression_workload_full_size_sampled_clauses(device):
+    """The regression workload at its full size (13,911 x 256 bits, 1,280 clauses, T = 1,280, s = 1.5):
+    sampled clauses and examples against the oracle, then asynchronous epochs with all clauses in
+    one launch, which on this workload reach an error far below the best constant predictor's."""
+    hp = dict(synth.WORKLOADS["regression_like"])
+    Xtr, ytr, Xte, yte = synth.regression_like(T=hp["T"])
+    n, T, q = hp["n"], hp["T"], len(ytr)
+    rng = np.random.default_rng(0)
+    ora = O.Oracle(seed=3, **hp)
+    gpu = B.TsetlinMachine(seed=3, **hp)
+    ids = np.array([0, 1, 63, 64, 700, n - 2, n - 1], dtype=np.int32)
+    assert np.array_equal(gpu_state_as_oracle(gpu), ora.state)
+    gpu.bind_train(dev_bits(gpu, Xtr), dev_i32(gpu, ytr))
+    ex = np.concatenate([[0, 1, 63, 64, q - 1], rng.integers(0, q, size=11)])
+    assert np.array_equal(gpu.tallies().cpu().numpy()[ex], ora.class_sums(np.ascontiguousarray(Xtr[ex]), clamp=False))
+    ostar_sub = ora.clause_outputs_subset(Xtr, ids)
+    sel = torch.from_numpy(ids).long().to(gpu.dev)
+    assert np.array_equal(bits_to_u8(gpu.prev_outputs()[sel], q), ostar_sub)
+    vhat = rng.integers(0, T + 1, size=(q, 1)).astype(np.int32)
+    vhat[::4, 0] = ytr[::4]
+    B.tm_set_epoch(gpu.h, 5)
+    gpu.feedback_step(dev_i32(gpu, vhat), 0, q)
+    fired = ora.feedback_step_subset(Xtr, ytr, vhat, ostar_sub, 5, 0, q, ids)
+    assert fired > 1000
+    assert np.array_equal(gpu_state_as_oracle(gpu)[ids], ora.state[ids])
+    prev = gpu.prev_outputs()
+    assert np.array_equal(bits_to_u8(prev[sel], q), ostar_sub)
+    assert np.array_equal(gpu.tallies().cpu().numpy()[:, 0], bits_to_u8(prev, q).astype(np.int32).sum(axis=0))
+    gpu.close()
+
+    gpu = B.TsetlinMachine(seed=4, **hp)
+    gpu.bind_train(dev_bits(gpu, Xtr), dev_i32(gpu, ytr))
+    Xd = dev_bits(gpu, Xte)
+    errs = []
+    for ep in range(12):
+        gpu.fit_epoch()
+        errs.append(float(np.abs(gpu.predict(Xd).cpu().numpy() - yte).mean()))
+    base = float(np.abs(yte - np.median(ytr)).mean())
+    print("full-size regression: late mean absolute error %.1f of T = %d, constant predictor %.1f"
+          % (np.mean(errs[6:]), T, base), flush=True)
+    assert np.mean(errs[6:]) < 0.6 * base
+    ora.state[:] = gpu_state_as_oracle(gpu)
+    ex = rng.integers(0, len(yte), size=12)
+    Xs = np.ascontiguousarray(Xte[ex])
+    assert np.array_equal(gpu.predict(Xd).cpu().numpy()[ex], ora.predict(Xs))
+    assert np.array_equal(gpu.class_sums(Xd, lists=False).cpu().numpy()[ex], ora.class_sums(Xs))
+    gpu.close()
