@@ -6,12 +6,42 @@ form, a probability printed in Table 1 / Table 2, an invariant, or a brute
 force written in a different form (sets / table look-up) in pure Python.
 """
 import itertools
+import os
 
 import numpy as np
 import pytest
 
 from oracle import tm_oracle as O
 from paper_2009_04861_amd import synth
+
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def golden_table(name):
+    """{(include, C, l): (reward, inaction, penalty) or None for NA} with the symbols of the fixture."""
+    cells = {}
+    for line in open(os.path.join(GOLDEN, name)):
+        line = line.split("#")[0].split()
+        if line:
+            action, C, l, r, i, p = line
+            cells[(action == "include", int(C), int(l))] = None if r == "NA" else (r, i, p)
+    assert len(cells) == 8
+    return cells
+
+
+def golden_examples():
+    out = {}
+    for line in open(os.path.join(GOLDEN, "worked_examples.txt")):
+        line = line.split("#")[0]
+        if "=" in line:
+            k, v = line.split("=", 1)
+            out[k.strip()] = v.split()
+    return out
+
+
+def prob(sym, s):
+    return {"strong": (s - 1.0) / s, "weak": 1.0 / s}.get(sym, None) if sym in ("strong", "weak") else float(sym)
 
 
 def make(m=2, n=4, o=3, N=4, T=3, s=3.0, seed=11, init=True):
@@ -35,8 +65,9 @@ def test_paper_clause_example_x1_and_not_x2():
     t.state[0, 2 + 1] = 10              # ... and NOT x2
     X = np.array(list(itertools.product([0, 1], repeat=2)), dtype=np.uint8)
     out = t.clause_outputs(X)[:, 0]
-    want = [(1 if (a == 1 and b == 0) else 0) for a, b in X]
-    assert out.tolist() == want
+    printed = dict(item.split(":") for item in golden_examples()["clause_x1_and_not_x2"])   # "x1x2" -> output
+    assert out.tolist() == [int(printed["%d%d" % (a, b)]) for a, b in X]
+    assert sorted(printed.values()) == ["0", "0", "0", "1"]
 
 
 def test_include_boundary_is_state_greater_than_N():
@@ -99,13 +130,17 @@ def test_xor_classifier_all_4096_inputs():
 
 
 def test_polarity_odd_positive_even_negative():
-    # one satisfied clause at a time: its vote is +1 for odd j, -1 for even j
+    # one satisfied clause at a time: its vote is +1 for the clauses the paper's XOR walk-through
+    # (n = 4) lets vote for y = 1, -1 for those it lets vote for y = 0
+    ex = golden_examples()
+    pos, neg = {int(v) for v in ex["xor_clauses_voting_for_1"]}, {int(v) for v in ex["xor_clauses_voting_for_0"]}
+    assert pos == {1, 3} and neg == {0, 2}
     for j in range(4):
         t = make(m=2, n=4, o=2, N=5, T=9, init=False)
         t.state[:] = 10                   # everything included -> all clauses 0
         t.state[4 + j, :] = 1             # clause j of class 1 empty -> 1
         s = t.class_sums(np.array([[1, 0]], dtype=np.uint8), clamp=False)
-        assert s[0, 1] == (1 if j % 2 == 1 else -1) and s[0, 0] == 0
+        assert s[0, 1] == (1 if j in pos else -1) and s[0, 0] == 0
 
 
 def test_class_sum_clamped_to_T_and_argmax_ties_low_index():
@@ -173,30 +208,23 @@ def test_gate_draw_depends_on_clause_example_epoch():
 # --------------------------------------------------------------------------
 
 def table1(action_include, C, lit, s):
-    """(P reward, P inaction, P penalty) typed from Table 1 of the paper."""
-    hi, lo = (s - 1.0) / s, 1.0 / s
-    if action_include:
-        if C == 1 and lit == 1: return (hi, lo, 0.0)
-        if C == 1 and lit == 0: return None                     # NA
-        return (0.0, hi, lo)
-    else:
-        if C == 1 and lit == 1: return (0.0, lo, hi)
-        return (lo, hi, 0.0)
+    """(P reward, P inaction, P penalty) of Table 1 of the paper (tests/golden/table1_type1_feedback.txt)."""
+    cell = golden_table("table1_type1_feedback.txt")[(bool(action_include), C, lit)]
+    return None if cell is None else tuple(prob(x, s) for x in cell)
 
 
 def table2(action_include, C, lit):
-    """(P reward, P inaction, P penalty) typed from Table 2 of the paper."""
-    if (not action_include) and C == 1 and lit == 0:
-        return (0.0, 0.0, 1.0)
-    return (0.0, 1.0, 0.0)
+    """(P reward, P inaction, P penalty) of Table 2 of the paper (tests/golden/table2_type2_feedback.txt)."""
+    cell = golden_table("table2_type2_feedback.txt")[(bool(action_include), C, lit)]
+    return None if cell is None else tuple(prob(x, 1.0) for x in cell)
 
 
 def delta_of(outcome, action_include):
     # Section 2.2: reinforcing Include (reward Include / penalise Exclude)
     # increases the counter, reinforcing Exclude decreases it.
     if outcome == "inaction": return 0
-    if outcome == "reward": return +1 if action_include else -1
-    return -1 if action_include else +1
+    d = dict(item.split(":") for item in golden_examples()["counter_delta"])
+    return int(d["%s_%s" % (outcome, "include" if action_include else "exclude")])
 
 
 @pytest.mark.parametrize("s", [2.0, 3.9, 10.0])
@@ -266,15 +294,20 @@ def test_type1_paper_worked_example():
     # includes x1 and outputs 0; the TA of x1 gets Inaction w.p. (s-1)/s and
     # Penalty (towards Exclude) w.p. 1/s.
     s, N, o = 3.9, 100, 2
+    ex = golden_examples()
     t = O.Oracle(2, 4, o, N, 15, s, 9, init=False)
-    lit = lits([0, 1])
+    lit = lits([int(v) for v in ex["xor_step1_input"]])
+    assert [int(v) for v in ex["xor_step1_input"]] == [0, 1] and ex["xor_step1_clause_output"] == ["0"]
+    printed = dict(item.split(":") for item in ex["xor_step1_include_x1"])
+    assert printed == dict(item.split(":") for item in ex["xor_step1_include_not_x2"])
     trials, pen = 40000, 0
     for i in range(trials):
         st = np.array([N + 1, 1, 1, N + 1], dtype=np.int32)   # includes x1 and NOT x2
         t.type1(st, lit, 0, 1, i, 0)
         assert st[0] in (N, N + 1)
         pen += int(st[0] == N)
-    p = 1 / s
+    p = prob(printed["penalty"], s)
+    assert abs(p + prob(printed["inaction"], s) - 1.0) < 1e-12
     assert abs(pen / trials - p) < 4.5 * np.sqrt(p * (1 - p) / trials)
 
 
