@@ -86,6 +86,7 @@ def test_output_is_clipped_at_T_and_counts_every_clause(device):
         assert want[0, 0] == min(n, T) and want[1, 0] == min(n - (n + 2) // 3, T)
         for lists in (True, False):
             assert np.array_equal(gpu.class_sums(Xd, lists=lists).cpu().numpy(), want)
+            assert np.array_equal(gpu.predict(Xd, lists=lists).cpu().numpy(), want[:, 0])   # the prediction is the clipped sum
         gpu.bind_train(Xd, dev_i32(gpu, np.zeros(70, dtype=np.int32)))
         assert np.array_equal(gpu.tallies().cpu().numpy(), ora.class_sums(X, clamp=False))
         gpu.close()
