@@ -21,7 +21,7 @@ namespace tsetlin {
 // but then some literal is false on every example after a few loads and the loop stops.
 
 constexpr int LIT_CAP_MIN = 128, LIT_CAP_MAX = 1024; // bounds of the list capacity (entries per clause)
-constexpr int SP_WAVES = 16;   // wavefronts per workgroup of k_eval_sparse
+constexpr int SP_WAVES = 8;    // wavefronts per workgroup of k_eval_sparse
 constexpr int SP_PLANES = 8;   // bit planes of a wavefront's vote counter: at most 255 clauses per wavefront
 
 // XB from row-major X: one workgroup of 4 wavefronts per 64 examples, each wavefront a
@@ -134,8 +134,8 @@ __device__ __forceinline__ uint32_t clause_from_masks(const uint32_t *__restrict
 }
 
 // One workgroup per (range of 2048 examples, class c, share s of S).  It evaluates its share
-// of the clauses of class c on the range: wavefront w takes the clauses j = j_lo + w + 16 k
-// (all of one polarity, because j_lo and 16 are even), lane = word of 32 examples.
+// of the clauses of class c on the range: wavefront w of the 8 takes the clauses j = j_lo + w + 8 k
+// (all of one polarity, because j_lo and 8 are even), lane = word of 32 examples.
 // Votes are counted bit-sliced: the outputs of eight clauses go through a tree of
 // carry-save adders (two bit operations each) into ones/twos/fours and one ripple into
 // the higher planes, about three operations per clause and word instead of one counter

@@ -163,7 +163,7 @@ constexpr int TRAIN_WAVES = 4; // clauses (wavefronts) per workgroup of the trai
 // list entry.  Blocks of 64 consecutive examples are evaluated (lane = example) only
 // when a gate in them fired or their stored outputs may be outdated; all other blocks
 // of the pass are never touched.
-template <int WPL, bool FULL>
+template <int WPL, bool FULL, bool REGR>
 __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
                                                             const uint32_t *__restrict__ XB,
                                                             const int32_t *__restrict__ gate,
@@ -182,7 +182,8 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     uint32_t *llist = lmask + a.lds_wave_words - (TRAIN_LIT_MAX + 8); // [TRAIN_LIT_MAX + 8] literal list for the sweeps
 
     const int c = g / d.n;
-    const bool regr = a.y_regr != nullptr;        // regression mode: every clause votes +1
+    constexpr bool regr = REGR;                   // regression mode: every clause votes +1 (a compile-time
+                                                  // switch: as a run-time one it cost wide clauses 36 registers)
     const bool pos = ((g - c * d.n) & 1) != 0 || regr; // odd index within the class: positive polarity
     const int sign = pos ? 1 : -1;
     const int T = d.T;
@@ -379,7 +380,10 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
         return a.vhat ? a.vhat[(int64_t)i * d.m + c]
                       : __hip_atomic_load(&tally_c[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
-    auto load_y = [&](int ent) { return (regr && ent >= 0) ? a.y_regr[ent >> 1] : 0; };
+    auto load_y = [&](int ent) {
+        if constexpr (REGR) return ent >= 0 ? a.y_regr[ent >> 1] : 0;
+        else return 0;
+    };
     int ent_cur = load_ent(k_lo);
     int v_cur = load_v(ent_cur);
     int y_cur = load_y(ent_cur);
