@@ -155,7 +155,7 @@ __device__ __forceinline__ int build_literals(const u32x8 (&p)[WPL], uint32_t *l
     return base;
 }
 
-constexpr int TRAIN_WAVES = 4; // clauses (wavefronts) per workgroup of the training kernel
+constexpr int TRAIN_WAVES_MAX = 4; // most clauses (wavefronts) per workgroup of the training kernel; the launch chooses
 
 // One wavefront = one clause of class c.  The examples whose gate can open for this
 // clause are those of the gate list of c for this launch (label c: trained towards 1;
@@ -164,7 +164,7 @@ constexpr int TRAIN_WAVES = 4; // clauses (wavefronts) per workgroup of the trai
 // when a gate in them fired or their stored outputs may be outdated; all other blocks
 // of the pass are never touched.
 template <int WPL, bool FULL, bool REGR>
-__global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
+__global__ __launch_bounds__(64 * TRAIN_WAVES_MAX) void k_train(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
                                                             const uint32_t *__restrict__ XB,
                                                             const int32_t *__restrict__ gate,
                                                             const int32_t *__restrict__ ngate, const TrainArgs a)
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES) void k_train(const uint32_t *__re
     const Dims &d = a.d;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int slot = a.slot_lo + blockIdx.x * TRAIN_WAVES + wave;
+    const int slot = a.slot_lo + (int)(blockIdx.x * (blockDim.x >> 6)) + wave;
     if (slot >= a.slot_hi) return; // whole wavefront; the kernel has no workgroup-wide barrier
     const int g = __builtin_amdgcn_readfirstlane(a.order[slot]);
     uint32_t *lmask = lds + wave * a.lds_wave_words;        // [W] include masks, literal-word order
