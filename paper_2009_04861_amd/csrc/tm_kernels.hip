@@ -315,7 +315,11 @@ int build_xb(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *XB, hipStream
 {
     const Dims &d = h->d;
     const int64_t QW = xb_row_words(q);
-    hipLaunchKernelGGL(k_transpose_bits, dim3((unsigned)(QW / 2)), dim3(256), 0, st, X, XB, q, d.Wf, d.o, (int)QW);
+    // enough workgroups for a few thousand wavefronts: the feature words are split when the examples are few
+    const int64_t wgs_x = QW / 2;
+    const int64_t split = std::max<int64_t>(1, std::min<int64_t>((d.Wf + 3) / 4, (2048 + wgs_x - 1) / wgs_x));
+    hipLaunchKernelGGL(k_transpose_bits, dim3((unsigned)wgs_x, (unsigned)split), dim3(256), 0, st, X, XB, q, d.Wf, d.o,
+                       (int)QW);
     TM_HIP(h, hipGetLastError());
     return TM_OK;
 }

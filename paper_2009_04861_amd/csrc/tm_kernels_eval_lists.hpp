@@ -24,8 +24,8 @@ constexpr int LIT_CAP_MIN = 128, LIT_CAP_MAX = 1024; // bounds of the list capac
 constexpr int SP_WAVES = 8;    // wavefronts per workgroup of k_eval_sparse
 constexpr int SP_PLANES = 8;   // bit planes of a wavefront's vote counter: at most 255 clauses per wavefront
 
-// XB from row-major X: one workgroup of 4 wavefronts per 64 examples, each wavefront a
-// contiguous share of the feature words; the 64 ballots of bit b of a word are two words
+// XB from row-major X: workgroups of 4 wavefronts per 64 examples (blockIdx.x) and share of the
+// feature words (blockIdx.y), each wavefront a contiguous share of the workgroup's words; the 64 ballots of bit b of a word are two words
 // of row 32 fw + b, their complement two words of row o + 32 fw + b.  Examples from q up
 // to 32 QW read as feature 0 (no clause output is taken from them).  Row 2o is set to ones.
 __global__ __launch_bounds__(256) void k_transpose_bits(const uint32_t *__restrict__ X, uint32_t *__restrict__ XB,
@@ -33,11 +33,12 @@ __global__ __launch_bounds__(256) void k_transpose_bits(const uint32_t *__restri
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t i = (int64_t)blockIdx.x * 64 + lane;
-    if (threadIdx.x == 0) // this block's two words of the all-ones row
+    if (threadIdx.x == 0 && blockIdx.y == 0) // these examples' two words of the all-ones row
         *reinterpret_cast<uint2 *>(XB + (int64_t)2 * o * QW + (int64_t)blockIdx.x * 2) = make_uint2(~0u, ~0u);
-    const int per = (Wf + 3) / 4;
-    const int f_end = min(Wf, (wave + 1) * per);
-    for (int fw = wave * per; fw < f_end; ++fw) {
+    const int per = (Wf + 4 * (int)gridDim.y - 1) / (4 * (int)gridDim.y);
+    const int share = (int)blockIdx.y * 4 + wave;
+    const int f_end = min(Wf, (share + 1) * per);
+    for (int fw = share * per; fw < f_end; ++fw) {
         const uint32_t x = (i < q) ? X[i * Wf + fw] : 0u;
         uint64_t r = 0;
 #pragma unroll
