@@ -11,7 +11,6 @@
 //                  XT     uint32 [Wf][qp]   transposed features (word-major) for lane = example evaluation
 //                  XB     uint32 [2o+1][QW] literals as bit rows over the examples (row 2o all ones), QW = 64*ceil(q/2048)
 //                  lits   uint32 [C][cap]   literal lists of the clauses (cap = 128..1024), nlit int32 [C] their lengths
-//                  negcls int32  [qp]       class trained towards 0 for each example, this epoch
 //                  gate   int32  [m][qp]    per class and launch: ascending list of (example << 1 | target) whose gate can open
 //                  fresh  int32  [C][4]     per clause: example ranges whose stored outputs may be outdated
 //                  order  int32  [C]        launch order of the clauses (outdated ones first)
@@ -79,7 +78,6 @@ struct tm_handle {
     int32_t *tally;
     uint32_t *ostar;
     uint32_t *XT;
-    int32_t *negcls;
     uint32_t *XB;   // [2o+1][QW] literal rows of the bound data
     uint32_t *lits; // [C][lit_cap(d)]
     int32_t *nlit;  // [C]
@@ -161,7 +159,7 @@ inline int lit_cap(const Dims &d)
 }
 
 struct WsLayout {
-    size_t tally, ostar, xt, xb, lits, nlit, negcls, gate, ngate, fresh, order, seg_cnt, counters, flag, total;
+    size_t tally, ostar, xt, xb, lits, nlit, gate, ngate, fresh, order, seg_cnt, counters, flag, total;
 };
 
 WsLayout ws_layout(const Dims &d, int64_t q)
@@ -176,7 +174,6 @@ WsLayout ws_layout(const Dims &d, int64_t q)
     L.xb = off; off += align256(xb_bytes(d, q));
     L.lits = off; off += align256((size_t)d.C * lit_cap(d) * 4);
     L.nlit = off; off += align256((size_t)d.C * 4);
-    L.negcls = off; off += align256((size_t)qp * 4);
     L.gate = off; off += align256((size_t)d.m * qp * 4);
     L.ngate = off; off += align256((size_t)d.m * 4);
     L.fresh = off; off += align256((size_t)d.C * 16);
@@ -424,7 +421,7 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
         a.slot_hi = (int)((int64_t)d.C * (grp + 1) / h->clause_groups);
         if (a.slot_hi <= a.slot_lo) continue;
         PrepArgs pa;
-        pa.y = h->y; pa.negcls = h->negcls; pa.tally = h->tally; pa.vhat = vhat; pa.fresh = h->fresh;
+        pa.y = h->y; pa.key = d.key; pa.epoch = h->epoch; pa.tally = h->tally; pa.vhat = vhat; pa.fresh = h->fresh;
         pa.gate = h->gate; pa.ngate = h->ngate; pa.order = h->order; pa.seg_cnt = h->seg_cnt; pa.counters = h->counters;
         pa.i_begin = a.i_begin; pa.i_end = a.i_end; pa.qp = a.qp; pa.m = d.m; pa.n = d.n; pa.C = d.C; pa.T = d.T;
         pa.regr = d.regr; pa.g_lo = a.slot_lo; pa.g_hi = a.slot_hi;
@@ -453,15 +450,6 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
         if (rc) return rc;
       }
     }
-    return TM_OK;
-}
-
-int run_negcls(tm_handle *h, hipStream_t st)
-{
-    if (h->d.regr) return TM_OK; // one bank of clauses: every example trains it
-    hipLaunchKernelGGL(k_negcls, dim3(blocks_for(h->qp, 256)), dim3(256), 0, st, h->d, h->y, h->negcls, h->q,
-                       h->qp, h->epoch);
-    TM_HIP(h, hipGetLastError());
     return TM_OK;
 }
 
@@ -565,7 +553,6 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
     h->tally = (int32_t *)(base + L.tally);
     h->ostar = (uint32_t *)(base + L.ostar);
     h->XT = (uint32_t *)(base + L.xt);
-    h->negcls = (int32_t *)(base + L.negcls);
     h->XB = (uint32_t *)(base + L.xb);
     h->lits = (uint32_t *)(base + L.lits);
     h->nlit = (int32_t *)(base + L.nlit);
@@ -599,8 +586,6 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
                        d.Wf);
     TM_HIP(h, hipGetLastError());
     h->bound = true;
-    rc = run_negcls(h, st);
-    if (rc) return rc;
     return sync_tallies(h, st);
 }
 
@@ -611,9 +596,7 @@ int tm_fit_epoch(tm_handle *h, void *stream)
     if (h->epoch >= (1u << 24)) return TM_ELIMIT;
     hipStream_t st = (hipStream_t)stream;
     TM_HIP(h, hipSetDevice(h->cfg.device));
-    int rc = run_negcls(h, st);
-    if (rc) return rc;
-    rc = launch_train(h, nullptr, 0, h->q, st);
+    const int rc = launch_train(h, nullptr, 0, h->q, st);
     if (rc) return rc;
     h->epoch += 1;
     return TM_OK;
@@ -628,8 +611,6 @@ int tm_fit_batch(tm_handle *h, int64_t i0, int64_t cnt, void *stream)
     hipStream_t st = (hipStream_t)stream;
     TM_HIP(h, hipSetDevice(h->cfg.device));
     const int64_t i_end = (cnt > h->q - i0) ? h->q : i0 + cnt;
-    int rc = run_negcls(h, st);
-    if (rc) return rc;
     if (i_end <= i0) return TM_OK;
     return launch_train(h, nullptr, i0, i_end, st);
 }
@@ -642,8 +623,6 @@ int tm_feedback_step(tm_handle *h, const int32_t *tally_snapshot, int64_t i0, in
     hipStream_t st = (hipStream_t)stream;
     TM_HIP(h, hipSetDevice(h->cfg.device));
     const int64_t i_end = (cnt > h->q - i0) ? h->q : i0 + cnt;
-    int rc = run_negcls(h, st);
-    if (rc) return rc;
     if (i_end <= i0) return TM_OK;
     return launch_train(h, tally_snapshot, i0, i_end, st);
 }

@@ -28,11 +28,13 @@ namespace tsetlin {
 // at once; the kernel runs twice: the first run leaves the number of flagged items of
 // every segment in seg_cnt, the second run places them.
 struct PrepArgs {
-    const int32_t *y, *negcls, *tally, *vhat, *fresh;
+    const int32_t *y, *tally, *vhat, *fresh;
     int32_t *gate, *ngate, *order, *seg_cnt; // seg_cnt [m + 1][segs][2]
     unsigned long long *counters;
     int i_begin, i_end, qp, m, n, C, T, segs;
     int regr; // regression mode: no classes, targets y in [0, T]
+    RngKey key;     // the class trained towards 0 for an example is drawn here: uniform over the m - 1 classes other
+    uint32_t epoch; // than y_i, a function of (seed, epoch, i) only, so that all clauses agree without communicating
     int g_lo, g_hi; // clauses of the launch (a launch may cover a range of the clauses only)
 };
 
@@ -77,7 +79,9 @@ __global__ __launch_bounds__(1024) void k_launch_prep(const PrepArgs a)
                 n_seen += live ? 1 : 0;
                 f[r] = live && vc != yy;
             } else {
-                const int ng = a.negcls[tc];
+                const U4 u = draw(a.key, STREAM_NEGCLASS, 0, 0, (uint64_t)tc, a.epoch);
+                const int dd = (int)(((uint64_t)u.x * (uint64_t)(a.m - 1)) >> 32);
+                const int ng = dd + (dd >= yy ? 1 : 0);
                 tg[r] = live && yy == c;
                 const bool match = live && (tg[r] || ng == c);
                 const int vc = min(max(v, -a.T), a.T);

@@ -101,22 +101,6 @@ __global__ void k_check_labels(const int32_t *y, int64_t q, int m, int32_t *flag
     if (i < q && (y[i] < 0 || y[i] >= m)) *flag = 1;
 }
 
-// The class trained towards output 0 for example i in this epoch: uniform over
-// the m-1 classes other than y_i, a function of (seed, epoch, i) only so that
-// all clauses agree without communicating.
-__global__ void k_negcls(Dims d, const int32_t *y, int32_t *negcls, int64_t q, int64_t qp, uint32_t epoch)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= qp) return;
-    int32_t r = -1;
-    if (i < q) {
-        const U4 u = draw(d.key, STREAM_NEGCLASS, 0, 0, (uint64_t)i, epoch);
-        const int32_t dd = (int32_t)(((uint64_t)u.x * (uint64_t)(d.m - 1)) >> 32);
-        r = dd + (dd >= y[i] ? 1 : 0);
-    }
-    negcls[i] = r;
-}
-
 // sums[i][c] = clamp(sums[i][c], lo, T): lo = -T, or 0 in regression mode
 __global__ void k_clamp(int32_t *sums, int64_t n, int lo, int T)
 {

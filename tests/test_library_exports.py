@@ -40,9 +40,9 @@ def test_sizes_and_validation_are_host_only():
     ws = B.tm_train_ws_bytes(cfg, 60000)
     qp = 60032
     # tallies + one bit per example per clause + transposed X + bit rows of X + literal lists
-    # + negative class + gate lists + per-clause freshness ranges + launch order + counters/flag
+    # + gate lists + per-clause freshness ranges + launch order + counters/flag
     qw = ((60000 + 2047) // 2048) * 64
-    need = (10 * qp * 4 + C * qp // 8 + 25 * qp * 4 + 1569 * qw * 4 + C * 128 * 4 + C * 4 + qp * 4 + 10 * qp * 4
+    need = (10 * qp * 4 + C * qp // 8 + 25 * qp * 4 + 1569 * qw * 4 + C * 128 * 4 + C * 4 + 10 * qp * 4
             + C * 16 + C * 4)
     assert ws >= need
     assert ws < 1.01 * need + 8192
