@@ -330,9 +330,6 @@ int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *li
 {
     const Dims &d = h->d;
     const int64_t QW = xb_row_words(q);
-    hipLaunchKernelGGL(k_literal_lists, dim3(blocks_for(d.C, 4)), dim3(256), 0, st, h->inc, lits, nlit, d.C, d.Wf, d.W,
-                       d.o, lit_cap(d), (uint32_t)(QW * 4), fresh, (int)h->qp);
-    TM_HIP(h, hipGetLastError());
     SparseArgs a;
     a.bits = bits; a.bits_stride = bits_stride; a.acc = acc; a.acc_si = acc_si; a.acc_sc = acc_sc;
     a.q = q; a.QW = (int)QW; a.QWq = (int)((q + 31) / 32); a.n = d.n; a.m = d.m; a.o = d.o; a.Wf = d.Wf; a.W = d.W; a.lit_cap = lit_cap(d);
@@ -351,12 +348,13 @@ int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *li
     S = (d.n + chunk - 1) / chunk;
     a.S = (int)S; a.chunk = (int)chunk; a.T = (S == 1) ? clampT : 0;
     a.Tlo = d.regr ? 0 : -a.T; a.all_pos = d.regr;
-    if (acc && S > 1) {
-        // partial sums of several workgroups are added up: start from zero
-        // (either layout, [m][qp] or [q][m]: up to the last element written)
-        const int rc = fill(h, acc, (size_t)((q - 1) * acc_si + (d.m - 1) * acc_sc + 1) * 4, 0u, st);
-        if (rc) return rc;
-    }
+    // partial sums of several workgroups are added up: they start from zero (either layout, [m][qp] or
+    // [q][m]: up to the last element written), cleared by the kernel that builds the lists
+    const int64_t zero_words = (acc && S > 1) ? (q - 1) * acc_si + (d.m - 1) * acc_sc + 1 : 0;
+    hipLaunchKernelGGL(k_literal_lists, dim3(blocks_for(d.C, 4)), dim3(256), 0, st, h->inc, lits, nlit, d.C, d.Wf, d.W,
+                       d.o, lit_cap(d), (uint32_t)(QW * 4), fresh, (int)h->qp, reinterpret_cast<uint32_t *>(acc),
+                       zero_words);
+    TM_HIP(h, hipGetLastError());
     int rc = timing_mark(h, timed_kind, true, st);
     if (rc) return rc;
     a.ranges = (int)ranges;

@@ -64,8 +64,11 @@ __global__ __launch_bounds__(256) void k_transpose_bits(const uint32_t *__restri
 // their masks).
 __global__ __launch_bounds__(256) void k_literal_lists(const uint32_t *__restrict__ inc, uint32_t *__restrict__ lits,
                                                        int32_t *__restrict__ nlit, int C, int Wf, int W, int o,
-                                                       int cap, uint32_t row_bytes, int32_t *fresh, int qp)
+                                                       int cap, uint32_t row_bytes, int32_t *fresh, int qp,
+                                                       uint32_t *zero, int64_t zero_words)
 {
+    // on the side: clear the buffer in which the evaluation kernel will add up partial sums
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < zero_words; t += (int64_t)gridDim.x * 256) zero[t] = 0u;
     const int lane = threadIdx.x & 63;
     const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (g >= C) return;
