@@ -449,6 +449,30 @@ def test_random_small_configurations(case, device):
     assert np.array_equal(gpu.tallies().cpu().numpy(), ora.class_sums(X, clamp=False))
 
 
+def test_clause_groups_are_a_schedule_only(device):
+    """Sub-launches over clause ranges (tm_set_clause_groups) must not change the result of a frozen
+    pass: group boundaries inside a class, groups of one clause, more examples than one preparation segment."""
+    m, n, o, N, T, s = 3, 10, 70, 20, 6, 3.0
+    rng = np.random.default_rng(55)
+    q = 4500
+    ora, gpu = make_pair(m, n, o, N, T, s, 12)
+    X, y = rand_problem(rng, q, o, m)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    gpu.counters()
+    for ep, groups in enumerate([4, 30, 1, 7]):
+        B.tm_set_clause_groups(gpu.h, groups)
+        B.tm_set_epoch(gpu.h, ep)
+        run_frozen(ora, gpu, X, y, ep, 100 * ep, q, tally, ostar)
+        assert np.array_equal(gpu_state_as_oracle(gpu), ora.state), groups
+        assert np.array_equal(gpu.tallies().cpu().numpy(), tally), groups
+        assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar), groups
+    c = gpu.counters()
+    visited = sum(q - 100 * ep for ep in range(4))
+    assert c["pairs"] == visited * ora.C
+    assert c["candidates"] == 2 * n * visited      # every example trains its own class and one other
+
+
 def test_error_codes(device):
     gpu = B.TsetlinMachine(3, 4, 20, 10, 5, 3.0, 1)
     with pytest.raises(B.TMError) as e:
