@@ -489,6 +489,40 @@ void otm_async_epoch(const otm_config *cfg, int32_t *state, const uint8_t *X,
     free(lit);
 }
 
+/* The same sequential execution restricted to the batch of examples i0 .. i0+cnt-1
+ * (Algorithm 1's batch size b = cnt): with clauses outermost, every clause in turn
+ * walks the whole batch before the next clause starts. */
+void otm_async_range(const otm_config *cfg, int32_t *state, const uint8_t *X,
+                     const int32_t *y, int64_t q, int32_t *tally, uint8_t *ostar,
+                     uint32_t epoch, int64_t i0, int64_t cnt, int example_major)
+{
+    int L = 2 * cfg->o, C = cfg->m * cfg->n;
+    int64_t i1 = i0 + cnt < q ? i0 + cnt : q;
+    uint8_t *lit = (uint8_t *)malloc((size_t)L);
+    if (example_major) {
+        for (int64_t i = i0; i < i1; ++i) {
+            literals(cfg, X + i * cfg->o, lit);
+            for (int g = 0; g < C; ++g) {
+                int c = g / cfg->n;
+                int role = role_of(cfg, c, y[i], epoch, i);
+                visit(cfg, state, g, lit, i, epoch, role, y[i], tally[i * cfg->m + c],
+                      &tally[i * cfg->m + c], &ostar[(size_t)g * q + i]);
+            }
+        }
+    } else {
+        for (int g = 0; g < C; ++g) {
+            int c = g / cfg->n;
+            for (int64_t i = i0; i < i1; ++i) {
+                literals(cfg, X + i * cfg->o, lit);
+                int role = role_of(cfg, c, y[i], epoch, i);
+                visit(cfg, state, g, lit, i, epoch, role, y[i], tally[i * cfg->m + c],
+                      &tally[i * cfg->m + c], &ostar[(size_t)g * q + i]);
+            }
+        }
+    }
+    free(lit);
+}
+
 /* Standard (synchronous) TM training, Section 3.1 first paragraph: examples
  * one by one; the exact vote sum of Eq. 3 is computed from the current
  * clauses before any of them receives feedback. */

@@ -171,6 +171,14 @@ class Oracle:
                               _p(tally), _p(ostar), ctypes.c_uint32(epoch),
                               ctypes.c_int(1 if example_major else 0))
 
+    def async_range(self, X, y, tally, ostar, epoch, i0, cnt, example_major=True):
+        q = X.shape[0]
+        _chk(X, np.uint8, (q, self.o)); _chk(y, np.int32, (q,))
+        _chk(tally, np.int32, (q, self.m)); _chk(ostar, np.uint8, (self.C, q))
+        lib().otm_async_range(ctypes.byref(self.cfg), _p(self.state), _p(X), _p(y), ctypes.c_int64(q),
+                              _p(tally), _p(ostar), ctypes.c_uint32(epoch), ctypes.c_int64(i0),
+                              ctypes.c_int64(cnt), ctypes.c_int(1 if example_major else 0))
+
     def sync_epoch(self, X, y, epoch):
         q = X.shape[0]
         _chk(X, np.uint8, (q, self.o)); _chk(y, np.int32, (q,))
