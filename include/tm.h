@@ -79,16 +79,21 @@ typedef struct {
  * classification.  tm_class_sums* return the clipped vote sum [q][1]; tm_predict*
  * return the same value in pred. */
 
-/* Size in bytes of the model state buffer (bit-sliced TA states + include
- * masks) for a configuration.  Host-only computation.  TM_EINVAL / TM_ELIMIT
- * on a bad configuration. */
+/* Size in bytes of the model state buffer for a configuration: one counter of
+ * 2N states per Tsetlin automaton, 2o automata per clause (Section 2.2: a TA
+ * "team" per clause, states 1..2N), stored bit-sliced (one byte per
+ * automaton), plus the include masks the clauses are evaluated from (Eq. 1).
+ * Host-only computation.  TM_EINVAL / TM_ELIMIT on a bad configuration. */
 int tm_state_bytes(const tm_config *cfg, size_t *out);
 
-/* Size in bytes of the training workspace for q examples (voting tallies,
- * previous-output bits - one bit per example per clause -, transposed copy of
- * X, the features as bit rows over the examples, literal lists of the clauses,
- * per-example negative class, per-class gate lists, per-clause bookkeeping,
- * counters).  Host-only computation. */
+/* Size in bytes of the training workspace for q examples.  Section 3.1 gives
+ * every training example a voting tally and every clause one bit per example
+ * (its previous output); the workspace holds those (int32 [m][q], 1 bit per
+ * (clause, example)) plus what the kernels derive from X and the clauses: the
+ * transposed copy of X, the literals as bit rows over the examples, literal
+ * lists of the clauses, per-class gate lists, per-clause bookkeeping, counters.
+ * Host-only computation.  The library cannot check the size of the buffer it
+ * is given in tm_bind_train: passing fewer bytes than this is undefined. */
 int tm_train_ws_bytes(const tm_config *cfg, int64_t q, size_t *out);
 
 /* Creates a machine whose state lives in state_buf (device, at least
@@ -97,7 +102,9 @@ int tm_train_ws_bytes(const tm_config *cfg, int64_t q, size_t *out);
  * initialisation on `stream`. */
 int tm_create(const tm_config *cfg, void *state_buf, void *stream, tm_handle **out);
 
-/* Frees the host-side handle only.  Device buffers stay with the caller. */
+/* Frees the host-side handle only (and the timing events it created).  Device
+ * buffers - the TA states of Section 2.2, the tallies of Section 3.1 - stay
+ * with the caller and keep their contents. */
 int tm_destroy(tm_handle *h);
 
 /* Binds a training set: X device uint32 [q][Wf], y device int32 [q] with
@@ -108,6 +115,11 @@ int tm_destroy(tm_handle *h);
  * report labels out of range as TM_EINVAL.  q >= 1. */
 int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, void *ws,
                   void *stream);
+
+/* Limits of the random counter (seed, epoch, example, clause, literal block):
+ * epoch < 2^24 (tm_fit_epoch, tm_fit_batch and tm_feedback_step return TM_ELIMIT
+ * once the epoch counter reaches it, tm_set_epoch refuses it with TM_EINVAL) and
+ * example index < 2^30 (checked in tm_bind_train). */
 
 /* One pass of Algorithm 1 with batch size b = q over the bound examples: every
  * clause visits examples 0..q-1 in order, gates on the (possibly outdated)
@@ -156,7 +168,9 @@ int tm_predict_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, int
 
 /* ---- hooks used by tests, checkpoints and measurements ---------------- */
 
-/* TA states as bytes: device uint8 [C][2o], value = state - 1 (0 .. 2N-1). */
+/* TA states as bytes (Section 2.2: every literal of every clause has an
+ * automaton with states 1..2N; Include iff state > N): device uint8 [C][2o],
+ * value = state - 1 (0 .. 2N-1), literal k < o is x_k, literal o+k is NOT x_k. */
 int tm_get_ta_state(tm_handle *h, uint8_t *out, void *stream);
 /* Inverse of tm_get_ta_state; values above 2N-1 are clamped.  Also rebuilds
  * the include masks.  Tallies of bound data become outdated (call
@@ -171,7 +185,9 @@ int tm_clause_outputs(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *bits
 /* Re-runs the tally pre-calculation (Section 3.1) on the bound data. */
 int tm_sync_tallies(tm_handle *h, void *stream);
 
-/* Copies the live tallies (unclamped) to out, device int32 [q][m]. */
+/* Copies the live voting tallies of Section 3.1 (one per training example and
+ * class, the recorded vote sum v_i that Algorithm 1 clips and gates on;
+ * unclamped, possibly outdated) to out, device int32 [q][m]. */
 int tm_get_tallies(tm_handle *h, int32_t *out, void *stream);
 
 /* Copies the stored previous clause outputs o* of Algorithm 1 to bits, same
@@ -199,6 +215,12 @@ int tm_train_chunk(tm_handle *h, int64_t *examples_per_launch);
  * legal schedule of Algorithm 1, and results under a frozen snapshot
  * (tm_feedback_step) do not depend on it. */
 int tm_set_clause_groups(tm_handle *h, int32_t groups);
+
+/* How the literal-list evaluation splits the n clauses of a class for q examples: into
+ * `shares` workgroups of `clauses_per_share` clauses each (host-only; measurement and test
+ * aid).  A wavefront counts the votes of an eighth of a share in 8 bit planes, so
+ * clauses_per_share <= 2032 always. */
+int tm_eval_shares(const tm_config *cfg, int64_t q, int32_t *shares, int32_t *clauses_per_share);
 
 /* Epoch counter used for the random counter of the next tm_fit_epoch. */
 int tm_set_epoch(tm_handle *h, uint32_t epoch);

@@ -19,7 +19,7 @@ EXPORTS = [
     "tm_state_bytes", "tm_train_ws_bytes", "tm_create", "tm_destroy", "tm_bind_train", "tm_fit_epoch", "tm_fit_batch",
     "tm_class_sums", "tm_predict", "tm_infer_ws_bytes", "tm_class_sums_ws", "tm_predict_ws", "tm_get_ta_state", "tm_set_ta_state", "tm_clause_outputs",
     "tm_sync_tallies", "tm_get_tallies", "tm_get_prev_outputs", "tm_feedback_step", "tm_train_chunk", "tm_set_epoch",
-    "tm_get_epoch", "tm_set_clause_groups", "tm_read_counters", "tm_kernel_timing", "tm_read_kernel_timing", "tm_strerror", "tm_last_hip_error",
+    "tm_get_epoch", "tm_set_clause_groups", "tm_eval_shares", "tm_read_counters", "tm_kernel_timing", "tm_read_kernel_timing", "tm_strerror", "tm_last_hip_error",
 ]
 
 
@@ -186,6 +186,14 @@ def tm_set_epoch(h, epoch):
 
 def tm_set_clause_groups(h, groups):
     _check(lib().tm_set_clause_groups(h, ctypes.c_int32(groups)), "tm_set_clause_groups")
+
+
+def tm_eval_shares(cfg, q):
+    """(shares, clauses per share) of the literal-list evaluation for q examples."""
+    S, chunk = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().tm_eval_shares(ctypes.byref(cfg), ctypes.c_int64(q), ctypes.byref(S), ctypes.byref(chunk)),
+           "tm_eval_shares")
+    return S.value, chunk.value
 
 
 def tm_get_epoch(h):

@@ -321,6 +321,28 @@ int build_xb(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *XB, hipStream
     return TM_OK;
 }
 
+// How k_eval_sparse splits the clauses of a class: over S workgroups (8 wavefronts each, three of
+// them per CU) of `chunk` clauses (a multiple of 16).  About 1,024 workgroups in all, but at least 256
+// clauses per workgroup (zeroing, converting and adding up a workgroup's sums costs as much as walking
+// a few hundred clauses), at least 16 per workgroup.  Measured on 10 x 2,000 clauses: 60,000 examples
+// 0.23 -> 0.19 ms against one workgroup of 16 wavefronts per CU, 10,000 examples 0.072 -> 0.054 ms.
+// A wavefront walks chunk / SP_WAVES clauses and counts their votes in SP_PLANES bit planes, so a
+// chunk holds at most (2^SP_PLANES - 1) * SP_WAVES clauses, rounded DOWN to a multiple of 16.
+// Returns false if the bound is violated (cannot happen).
+inline bool eval_shares(const Dims &d, int64_t ranges, int64_t *S_out, int64_t *chunk_out)
+{
+    const int64_t chunk_max = (((int64_t)((1 << SP_PLANES) - 1) * SP_WAVES) / 16) * 16;
+    int64_t S = (8192 / SP_WAVES + d.m * ranges - 1) / (d.m * ranges);
+    S = std::min<int64_t>(S, std::max<int64_t>(1, d.n / 256));
+    S = std::max<int64_t>(S, (d.n + chunk_max - 1) / chunk_max);
+    S = std::min<int64_t>(S, (d.n + 15) / 16);
+    const int64_t chunk = std::min<int64_t>((((d.n + S - 1) / S) + 15) & ~(int64_t)15, chunk_max);
+    S = (d.n + chunk - 1) / chunk;
+    *S_out = S;
+    *chunk_out = chunk;
+    return chunk / SP_WAVES < (1 << SP_PLANES) && S * chunk >= d.n && chunk % 16 == 0;
+}
+
 // Evaluation of all clauses on the q examples behind XB from their literal lists (rebuilt
 // here from the current masks); writes bits and/or the class sums.  With clampT > 0 the
 // sums are clamped.  acc need not be zeroed by the caller.
@@ -333,19 +355,9 @@ int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *li
     SparseArgs a;
     a.bits = bits; a.bits_stride = bits_stride; a.acc = acc; a.acc_si = acc_si; a.acc_sc = acc_sc;
     a.q = q; a.QW = (int)QW; a.QWq = (int)((q + 31) / 32); a.n = d.n; a.m = d.m; a.o = d.o; a.Wf = d.Wf; a.W = d.W; a.lit_cap = lit_cap(d);
-    // The clauses of a class are split over S workgroups (8 wavefronts each, three of them per CU):
-    // about 1,024 workgroups in all, but at least 256 clauses per workgroup (zeroing, converting and
-    // adding up a workgroup's sums costs as much as walking a few hundred clauses); at most 255
-    // clauses per wavefront, at least 16 per workgroup.  Measured on 10 x 2,000 clauses: 60,000
-    // examples 0.23 -> 0.19 ms against one workgroup of 16 wavefronts per CU, 10,000 examples
-    // 0.072 -> 0.054 ms.
+    int64_t S, chunk;
     const int64_t ranges = QW / 64;
-    int64_t S = (8192 / SP_WAVES + d.m * ranges - 1) / (d.m * ranges);
-    S = std::min<int64_t>(S, std::max<int64_t>(1, d.n / 256));
-    S = std::max<int64_t>(S, (d.n + 255 * SP_WAVES - 1) / (255 * SP_WAVES));
-    S = std::min<int64_t>(S, (d.n + 15) / 16);
-    int64_t chunk = (((d.n + S - 1) / S) + 15) & ~(int64_t)15;
-    S = (d.n + chunk - 1) / chunk;
+    if (!eval_shares(d, ranges, &S, &chunk)) return TM_ELIMIT; // cannot happen; guards the vote counters
     a.S = (int)S; a.chunk = (int)chunk; a.T = (S == 1) ? clampT : 0;
     a.Tlo = d.regr ? 0 : -a.T; a.all_pos = d.regr;
     // partial sums of several workgroups are added up: they start from zero (either layout, [m][qp] or
@@ -618,6 +630,7 @@ int tm_feedback_step(tm_handle *h, const int32_t *tally_snapshot, int64_t i0, in
     if (!h || !tally_snapshot || i0 < 0 || cnt < 0) return TM_EINVAL;
     if (!h->bound) return TM_ESTATE;
     if (i0 > h->q) return TM_EINVAL;
+    if (h->epoch >= (1u << 24)) return TM_ELIMIT;
     hipStream_t st = (hipStream_t)stream;
     TM_HIP(h, hipSetDevice(h->cfg.device));
     const int64_t i_end = (cnt > h->q - i0) ? h->q : i0 + cnt;
@@ -764,6 +777,18 @@ int tm_train_chunk(tm_handle *h, int64_t *examples_per_launch)
 {
     if (!h || !examples_per_launch) return TM_EINVAL;
     *examples_per_launch = train_chunk(h->d);
+    return TM_OK;
+}
+
+int tm_eval_shares(const tm_config *cfg, int64_t q, int32_t *shares, int32_t *clauses_per_share)
+{
+    const int rc = check_config(cfg);
+    if (rc) return rc;
+    if (q < 1 || !shares || !clauses_per_share) return TM_EINVAL;
+    int64_t S, chunk;
+    if (!eval_shares(make_dims(cfg), xb_row_words(q) / 64, &S, &chunk)) return TM_ELIMIT;
+    *shares = (int32_t)S;
+    *clauses_per_share = (int32_t)chunk;
     return TM_OK;
 }
 

@@ -131,6 +131,41 @@ def test_vote_counters_at_capacity(n, device):
     assert np.array_equal(gpu.tallies().cpu().numpy(), ora.class_sums(X, clamp=False))
 
 
+@pytest.mark.parametrize("n", [16264, 18288])
+def test_vote_counters_when_the_capacity_sets_the_split(n, device):
+    """2 classes x 131,067 examples give 128 (class, range) pairs, so the workgroup count alone would
+    split a class 8 ways: 2,033 .. 2,040 clauses per share, which the rounding to a multiple of 16
+    must not turn into 2,048 (256 same-polarity clauses per wavefront, one more than its 8-plane
+    counter holds).  Every positive clause of class 0 is empty (satisfied by every example) and no
+    negative one can be satisfied: every example's sum is n/2, in closed form; sampled examples are
+    checked against the oracle as well.  n = 18,288 = 9 x 2,032 fills the counters to their bound:
+    254 satisfied clauses per wavefront."""
+    m, o, N, T, q = 2, 8, 128, 9500, 131067
+    print("vote counters, split set by capacity", n, flush=True)
+    S, chunk = B.tm_eval_shares(B.make_config(m, n, o, N, T, 4.0, 5), q)
+    assert chunk <= 2032 and S * chunk >= n and S == 9 and (n != 18288 or chunk == 2032)
+    rng = np.random.default_rng(n)
+    ora, gpu = make_pair(m, n, o, N, T, 4.0, 5)
+    st = np.ones((ora.C, ora.L), dtype=np.int32)
+    st[0:n:2, 0] = 2 * N          # negative clauses of class 0: x0 AND NOT x0
+    st[0:n:2, o] = 2 * N
+    st[n + 1:2 * n:4, 1] = 2 * N  # some positive clauses of class 1: x1
+    st[n:2 * n:2, 2] = 2 * N      # negative clauses of class 1: x2
+    ora.state[:] = st
+    push_state(gpu, ora.state)
+    X, y = rand_problem(rng, q, o, m)
+    Xd = dev_bits(gpu, X)
+    got = gpu.class_sums(Xd, lists=True).cpu().numpy()
+    assert np.all(got[:, 0] == n // 2)
+    closed = ((n + 2) // 4) * X[:, 1].astype(np.int64) + ((n // 2 - (n + 2) // 4)) - (n // 2) * X[:, 2].astype(np.int64)
+    assert np.array_equal(got[:, 1], closed)
+    ex = np.concatenate([[0, 1, 2047, 2048, q - 1], rng.integers(0, q, size=20)])
+    assert np.array_equal(got[ex], ora.class_sums(np.ascontiguousarray(X[ex])))
+    gpu.bind_train(Xd, dev_i32(gpu, y))
+    assert np.array_equal(gpu.tallies().cpu().numpy(), got)     # T is above every sum: nothing is clamped
+    gpu.close()
+
+
 def test_class_sums_are_clamped(device):
     ora, gpu = make_pair(2, 64, 20, 128, 5, 3.0, 3)
     ora.state[:] = 1

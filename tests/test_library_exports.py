@@ -62,3 +62,21 @@ def test_sizes_and_validation_are_host_only():
         B.tm_state_bytes(B.make_config(2, 4, 20481, 10, 5, 3.0, 1))
     assert e.value.code == B.TM_ELIMIT
     assert B.strerror(B.TM_ESTATE).startswith("no training data")
+
+
+def test_vote_counter_capacity_holds_for_every_split_of_a_class():
+    """The literal-list evaluation gives a wavefront an eighth of a share of a class's clauses and
+    counts their votes in 8 bit planes (at most 255).  Whatever the number of clauses, classes and
+    examples, the split must keep a share at 2,032 clauses or fewer after all rounding, cover all
+    clauses and stay a multiple of 16 (polarity alternates with the clause index)."""
+    worst = 0
+    shapes = [(2, 100), (2, 131067), (2, 200000), (10, 60000), (10, 10000), (5, 26624), (3, 2_100_000)]
+    for m, q in shapes:
+        ns = set(range(2, 70000, 2)) if (m, q) in ((2, 131067), (10, 60000)) else set()
+        for S in range(1, 40):
+            ns |= {n for n in range(S * 2030, S * 2050) if n % 2 == 0 and n >= 2}
+        for n in sorted(ns):
+            S, chunk = B.tm_eval_shares(B.make_config(m, n, 8, 128, 5, 3.0, 1), q)
+            assert chunk % 16 == 0 and chunk <= 2032 and S * chunk >= n and (S - 1) * chunk < n, (m, q, n, S, chunk)
+            worst = max(worst, chunk)
+    assert worst == 2032      # the cap is reached (a share of 2,033 .. 2,040 clauses would round to 2,048)
