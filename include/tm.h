@@ -166,6 +166,22 @@ int tm_class_sums_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, 
 int tm_predict_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, int32_t *sums_scratch, void *ws,
                   void *stream);
 
+/* tm_predict_ws for callers that cannot allocate or bring a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the workspace and the sums scratch live in a static device array
+ * of TM_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held until
+ * the process ends.  Same result as tm_predict_ws.  Calls no hipMalloc / hipFree
+ * and creates no events or streams; enqueues kernels on `stream` only.
+ * TM_ELIMIT when tm_infer_ws_bytes(cfg, q) rounded up to 256 plus q*m*4 bytes
+ * exceed TM_STATIC_SCRATCH_BYTES (split q; the literal lists of all clauses
+ * alone take C * (128..1024) * 4 bytes, so large machines do not fit at all).
+ * All calls on one GPU share that GPU's array: two calls whose kernels can run
+ * at the same time (different streams, different handles, different host
+ * threads) race on it; calls on one stream are safe.  Nothing needs to be kept
+ * in the array between calls. */
+#define TM_STATIC_SCRATCH_BYTES (32u << 20)
+int tm_predict_static(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, void *stream);
+
 /* ---- hooks used by tests, checkpoints and measurements ---------------- */
 
 /* TA states as bytes (Section 2.2: every literal of every clause has an

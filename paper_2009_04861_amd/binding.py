@@ -17,7 +17,7 @@ TM_OK, TM_EINVAL, TM_ESTATE, TM_EHIP, TM_ELIMIT = 0, -1, -2, -3, -4
 
 EXPORTS = [
     "tm_state_bytes", "tm_train_ws_bytes", "tm_create", "tm_destroy", "tm_bind_train", "tm_fit_epoch", "tm_fit_batch",
-    "tm_class_sums", "tm_predict", "tm_infer_ws_bytes", "tm_class_sums_ws", "tm_predict_ws", "tm_get_ta_state", "tm_set_ta_state", "tm_clause_outputs",
+    "tm_class_sums", "tm_predict", "tm_infer_ws_bytes", "tm_class_sums_ws", "tm_predict_ws", "tm_predict_static", "tm_get_ta_state", "tm_set_ta_state", "tm_clause_outputs",
     "tm_sync_tallies", "tm_get_tallies", "tm_get_prev_outputs", "tm_feedback_step", "tm_train_chunk", "tm_set_epoch",
     "tm_get_epoch", "tm_set_clause_groups", "tm_eval_shares", "tm_read_counters", "tm_kernel_timing", "tm_read_kernel_timing", "tm_strerror", "tm_last_hip_error",
 ]
@@ -142,6 +142,11 @@ def tm_class_sums_ws(h, X, sums, ws):
 def tm_predict_ws(h, X, pred, sums_scratch, ws):
     _check(lib().tm_predict_ws(h, _ptr(X, torch.int32), ctypes.c_int64(X.shape[0]), _ptr(pred, torch.int32),
                                _ptr(sums_scratch, torch.int32), _ptr(ws), _stream()), "tm_predict_ws")
+
+
+def tm_predict_static(h, X, pred):
+    _check(lib().tm_predict_static(h, _ptr(X, torch.int32), ctypes.c_int64(X.shape[0]), _ptr(pred, torch.int32),
+                                   _stream()), "tm_predict_static")
 
 
 def tm_get_ta_state(h, out):

@@ -30,6 +30,7 @@
 #include <hip/hip_runtime.h>
 #include <algorithm>
 #include <math.h>
+#include <mutex>
 #include <new>
 #include <stdint.h>
 #include <string.h>
@@ -61,6 +62,12 @@ struct Dims {
 // ------------------------------------------------------------------------
 // host side: handle, validation, launches
 // ------------------------------------------------------------------------
+
+// Scratch of tm_predict_static: device memory of the code object itself, so that the call needs no
+// caller workspace and allocates nothing.  Every GPU the library runs on holds its own copy at its own
+// address until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress: kernels and copies are given the per-device address kept in static_scratch[].
+static __device__ __align__(256) unsigned char scratch[TM_STATIC_SCRATCH_BYTES];
 
 using namespace tsetlin;
 
@@ -100,6 +107,28 @@ struct tm_handle {
 };
 
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+void *static_scratch[MAX_DEVICES]; // address of `scratch` on each device, looked up once per device
+std::mutex static_scratch_lock;
+
+// Address of this device's copy of `scratch` (the device must be current); null with the HIP error in *err.
+void *static_scratch_of(int device, hipError_t *err)
+{
+    *err = hipSuccess;
+    if (device < 0 || device >= MAX_DEVICES) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> guard(static_scratch_lock);
+    if (!static_scratch[device]) {
+        void *p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess) return nullptr;
+        static_scratch[device] = p;
+    }
+    return static_scratch[device];
+}
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -205,7 +234,7 @@ enum { TIMED_TRAIN = 0, TIMED_PRECALC = 1, TIMED_INFER = 2, TIMED_KINDS = 3 };
 // and after the launch of a timed kernel.
 int timing_mark(tm_handle *h, int kind, bool first, hipStream_t st)
 {
-    if (!h->timing) return TM_OK;
+    if (!h->timing || kind < 0) return TM_OK;
     if (h->ev_used == h->ev_pool.size()) {
         hipEvent_t e;
         TM_HIP(h, hipEventCreate(&e));
@@ -523,6 +552,10 @@ int tm_create(const tm_config *cfg, void *state_buf, void *stream, tm_handle **o
         delete h;
         return TM_EHIP;
     }
+    if (!static_scratch_of(cfg->device, &e)) { // once per device, with that device current
+        delete h;
+        return TM_EHIP;
+    }
     const int64_t nt = (int64_t)h->d.C * h->d.W;
     hipLaunchKernelGGL(k_init_state, dim3(blocks_for(nt, 256)), dim3(256), 0, (hipStream_t)stream, h->d, h->planes,
                        h->inc);
@@ -680,7 +713,8 @@ int tm_infer_ws_bytes(const tm_config *cfg, int64_t q, size_t *out)
 }
 
 // class sums (and, with pred, the decision) of q examples through literal lists; ws as tm_infer_ws_bytes
-static int infer_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, int32_t *pred, void *ws, void *stream)
+static int infer_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, int32_t *pred, void *ws, void *stream,
+                    int timed_kind)
 {
     if (!h || q < 0) return TM_EINVAL;
     if (q == 0) return TM_OK;
@@ -695,19 +729,40 @@ static int infer_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, i
     int32_t *nlit = (int32_t *)(base + align256(xb_bytes(d, q)) + align256((size_t)d.C * lit_cap(d) * 4));
     const int rc = build_xb(h, X, q, XB, st);
     if (rc) return rc;
-    return launch_eval_sparse(h, XB, q, lits, nlit, nullptr, 0, sums, d.m, 1, d.T, pred, nullptr, TIMED_INFER, st);
+    return launch_eval_sparse(h, XB, q, lits, nlit, nullptr, 0, sums, d.m, 1, d.T, pred, nullptr, timed_kind, st);
 }
 
 int tm_class_sums_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, void *ws, void *stream)
 {
-    return infer_ws(h, X, q, sums, nullptr, ws, stream);
+    return infer_ws(h, X, q, sums, nullptr, ws, stream, TIMED_INFER);
 }
 
 int tm_predict_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, int32_t *sums_scratch, void *ws,
                   void *stream)
 {
     if (q > 0 && !pred) return TM_EINVAL;
-    return infer_ws(h, X, q, sums_scratch, pred, ws, stream);
+    return infer_ws(h, X, q, sums_scratch, pred, ws, stream, TIMED_INFER);
+}
+
+int tm_predict_static(tm_handle *h, const uint32_t *X, int64_t q, int32_t *pred, void *stream)
+{
+    if (!h || q < 0) return TM_EINVAL;
+    if (q == 0) return TM_OK;
+    if (!X || !pred) return TM_EINVAL;
+    // scratch = workspace of tm_predict_ws followed by its sums_scratch [q][m]
+    size_t ws_bytes = 0;
+    const int rc = tm_infer_ws_bytes(&h->cfg, q, &ws_bytes);
+    if (rc) return rc;
+    const size_t need = align256(ws_bytes) + (size_t)q * h->d.m * 4;
+    if (need > (size_t)TM_STATIC_SCRATCH_BYTES) return TM_ELIMIT;
+    TM_HIP(h, hipSetDevice(h->cfg.device));
+    hipError_t e;
+    char *base = (char *)static_scratch_of(h->cfg.device, &e); // looked up in tm_create: no HIP call here
+    if (!base) return hip_fail(h, e);
+    // every word the kernels read is written first by this call (literal rows, lists, lengths; partial sums
+    // are cleared by the list kernel), so what an earlier call left in the array does not matter; the
+    // kernels are not timed here because recording a new event would allocate
+    return infer_ws(h, X, q, (int32_t *)(base + align256(ws_bytes)), pred, base, stream, -1);
 }
 
 int tm_get_ta_state(tm_handle *h, uint8_t *out, void *stream)
