@@ -244,7 +244,8 @@ int tm_get_epoch(tm_handle *h, uint32_t *epoch);
 
 /* Device-side event counters of the training kernel since the last call of
  * this function (or since tm_bind_train): out is HOST uint64 [9]:
- * [0] visited (clause, example) pairs, [1] fired gates, [2] Type I feedbacks,
+ * [0] visited (clause, example) pairs (every wavefront of the training kernel adds the
+ * number of examples of its launch that it walked for its clause), [1] fired gates, [2] Type I feedbacks,
  * [3] tally changes, [4] pairs whose class was trained for the example (gate
  * candidates), [5] Type II feedbacks given to a clause with output 1,
  * [6] blocks of 64 examples that a clause had to evaluate (blocks whose stored

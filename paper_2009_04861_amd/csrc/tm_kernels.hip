@@ -14,7 +14,7 @@
 //                  gate   int32  [m][qp]    per class and launch: ascending list of (example << 1 | target) whose gate can open
 //                  fresh  int32  [C][4]     per clause: example ranges whose stored outputs may be outdated
 //                  order  int32  [C]        launch order of the clauses (outdated ones first)
-//                  counters uint64 [64][8] interleaved event counters, flag int32
+//                  counters uint64 [64][16] interleaved event counters, flag int32
 //   literal word lw < Wf holds x_(32 lw + j), literal word Wf + fw holds NOT x_(32 fw + j).
 //
 // Three evaluation layouts are used:
@@ -97,7 +97,6 @@ struct tm_handle {
     int32_t *flag;
     uint32_t epoch;
     int clause_groups; // sub-launches of consecutive clause ranges per training launch
-    uint64_t pairs_visited; // (clause, example) visits enqueued since the counters were last read
     int last_hip;
     // kernel timing (measurement aid): event pairs around the launches of the two main kernels
     bool timing;
@@ -208,7 +207,7 @@ WsLayout ws_layout(const Dims &d, int64_t q)
     L.fresh = off; off += align256((size_t)d.C * 16);
     L.order = off; off += align256((size_t)d.C * 4);
     L.seg_cnt = off; off += align256((size_t)(d.m + 1) * prep_segments(d, qp) * 8);
-    L.counters = off; off += align256((size_t)COUNTER_SETS * 8 * 8);
+    L.counters = off; off += align256((size_t)COUNTER_SETS * COUNTER_WIDTH * 8);
     L.flag = off; off += 256;
     L.total = off;
     return L;
@@ -450,7 +449,6 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
     const bool full = (d.N == 128);
     const int wpl = (d.W + 63) / 64;
     const int64_t chunk = train_chunk(d);
-    h->pairs_visited += (uint64_t)d.C * (uint64_t)(i_end - i_begin);
     for (int64_t b = (i_begin / chunk) * chunk; b < i_end; b += chunk) {
         a.i_begin = (int32_t)std::max(b, i_begin);
         a.i_end = (int32_t)std::min(b + chunk, i_end);
@@ -609,7 +607,7 @@ int tm_bind_train(tm_handle *h, const uint32_t *X, const int32_t *y, int64_t q, 
 
     int rc = fill(h, h->flag, 256, 0u, st);
     if (rc) return rc;
-    rc = fill(h, h->counters, (size_t)COUNTER_SETS * 64, 0u, st);
+    rc = fill(h, h->counters, (size_t)COUNTER_SETS * COUNTER_WIDTH * 8, 0u, st);
     if (rc) return rc;
     hipLaunchKernelGGL(k_check_labels, dim3(blocks_for(q, 256)), dim3(256), 0, st, y, q, d.regr ? d.T + 1 : d.m,
                        h->flag);
@@ -904,17 +902,18 @@ int tm_read_counters(tm_handle *h, uint64_t *out, void *stream)
     if (!h->bound) return TM_ESTATE;
     hipStream_t st = (hipStream_t)stream;
     TM_HIP(h, hipSetDevice(h->cfg.device));
-    unsigned long long tmp[COUNTER_SETS * 8];
+    unsigned long long tmp[COUNTER_SETS * COUNTER_WIDTH];
     TM_HIP(h, hipMemcpyAsync(tmp, h->counters, sizeof(tmp), hipMemcpyDeviceToHost, st));
     TM_HIP(h, hipStreamSynchronize(st));
-    for (int k = 0; k < 8; ++k) {
-        out[k] = 0;
-        for (int c = 0; c < COUNTER_SETS; ++c) out[k] += tmp[c * 8 + k];
+    uint64_t sum[9];
+    for (int k = 0; k < 9; ++k) {
+        sum[k] = 0;
+        for (int c = 0; c < COUNTER_SETS; ++c) sum[k] += tmp[c * COUNTER_WIDTH + k];
     }
-    out[8] = out[0];           // device slot 0: blocks evaluated through literal lists
-    out[0] = h->pairs_visited; // every clause visits every example of a pass; known on the host
-    h->pairs_visited = 0;
-    return fill(h, h->counters, (size_t)COUNTER_SETS * 64, 0u, st);
+    for (int k = 1; k < 8; ++k) out[k] = sum[k];
+    out[0] = sum[8]; // examples walked, summed over the wavefronts (clauses) that ran
+    out[8] = sum[0]; // blocks evaluated through literal lists
+    return fill(h, h->counters, (size_t)COUNTER_SETS * COUNTER_WIDTH * 8, 0u, st);
 }
 
 const char *tm_strerror(int code)

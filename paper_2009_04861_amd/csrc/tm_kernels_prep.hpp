@@ -38,7 +38,8 @@ struct PrepArgs {
     int g_lo, g_hi; // clauses of the launch (a launch may cover a range of the clauses only)
 };
 
-constexpr int COUNTER_SETS = 64; // interleaved copies of the 8 event counters
+constexpr int COUNTER_SETS = 64; // interleaved copies of the event counters
+constexpr int COUNTER_WIDTH = 16; // 64-bit words per copy (9 in use)
 constexpr int PREP_ROUNDS = 4;   // rounds of 1024 items per segment
 constexpr int PREP_SEG = 1024 * PREP_ROUNDS;
 
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(1024) void k_launch_prep(const PrepArgs a)
         if (!ordering) { // pairs of the range whose class is trained for the example
             for (int sh = 32; sh > 0; sh >>= 1) n_seen += __shfl_down(n_seen, sh, 64);
             if (lane == 0 && n_seen)
-                atomicAdd(&a.counters[((seg * 16 + wave) & (COUNTER_SETS - 1)) * 8 + 4],
+                atomicAdd(&a.counters[((seg * 16 + wave) & (COUNTER_SETS - 1)) * COUNTER_WIDTH + 4],
                           (unsigned long long)n_seen *
                               (unsigned long long)max(0, min((c + 1) * a.n, a.g_hi) - max(c * a.n, a.g_lo)));
         }

@@ -385,17 +385,29 @@ def test_noisy_xor_frozen_epochs_match(device):
     assert np.array_equal(gpu.predict(dev_bits(gpu, Xte)).cpu().numpy(), ora.predict(Xte))
 
 
-@pytest.mark.parametrize("shape", SHAPES[:4])
-def test_async_epoch_invariants(shape, device):
+# narrow machines (one launch per epoch) and wide ones: 3 register slots with list sweeps, 10 and 20
+# slots with block-by-block sweeps and 3 / 5 launches per epoch (4,000 examples against launches of
+# 1,664 and 832)
+ASYNC_SHAPES = [(sh, 500) for sh in SHAPES[:4]] + [
+    ((2, 6, 2500, 128, 3, 10.0), 4000),
+    ((2, 4, 10000, 128, 20, 2.0), 4000),
+    ((2, 2, 20000, 128, 10, 5.0), 4000),
+]
+
+
+@pytest.mark.parametrize("shape,q", ASYNC_SHAPES)
+def test_async_epoch_invariants(shape, q, device):
     m, n, o, N, T, s = shape
-    print("async", shape, flush=True)
+    print("async", shape, q, flush=True)
     rng = np.random.default_rng(31)
-    q = 500
     ora, gpu = make_pair(m, n, o, N, T, s, 3)
     X, y = rand_problem(rng, q, o, m)
     Xd = dev_bits(gpu, X)
     gpu.bind_train(Xd, dev_i32(gpu, y))
+    launches = -(-q // B.tm_train_chunk(gpu.h))
+    assert launches == (1 if o <= 4096 else 3 if o == 10000 else 5)
     sign = np.where(np.arange(ora.C) % n % 2 == 1, 1, -1)
+    gpu.counters()
     for ep in range(4):
         gpu.fit_epoch()
         st = gpu.get_ta_state().cpu().numpy()
@@ -410,6 +422,7 @@ def test_async_epoch_invariants(shape, device):
     ora.state[:] = gpu_state_as_oracle(gpu)
     assert np.array_equal(gpu.tallies().cpu().numpy(), ora.class_sums(X, clamp=False))
     c = gpu.counters()
+    # counted on the device: every clause got a wavefront in every launch and walked the launch's examples
     assert c["pairs"] == 4 * q * ora.C and 0 < c["fired"] < c["pairs"]
 
 
