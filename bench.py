@@ -45,13 +45,40 @@ GATE_OPS = PHILOX_OPS + 8                                # one block + clip, err
 # `rocprofv3 --pmc` runs of this program (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch, averaged
 # over the timed launches).  The scale factors come from the same counters read for a plain
 # 1 GiB device copy in the same runs (--calibration-copy): FETCH_SIZE reads 524,309 KiB for
-# 1,048,576 KiB fetched, WRITE_SIZE reads 1,048,576 KiB for 1,048,576 KiB written.  Summaries are
-# under profiles/.
+# 1,048,576 KiB fetched, WRITE_SIZE reads 1,048,576 KiB for 1,048,576 KiB written.  The figures
+# belong to the kernel sources whose digest is recorded with them (kernel_sources_digest() at the
+# time of the profile runs); with other sources `traffic` is reported as null.
 MEASURED_TRAFFIC = {
+    "profile": "profiles/image_like_default_benchmark.txt",
+    "kernel_sources_sha256": "",
     "image_like_train": {"fetch_kib": 149544.0, "fetch_scale": 2.0, "write_kib": 95014.0, "write_scale": 1.0},
     # k_eval_sparse in tm_sync_tallies
     "image_like_precalc": {"fetch_kib": 56142.0, "fetch_scale": 2.0, "write_kib": 165313.0, "write_scale": 1.0},
 }
+
+
+def kernel_sources_digest():
+    """sha256 over the HIP sources the library is built from (names and contents, sorted)."""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2009_04861_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".hpp", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(key):
+    """(bytes per launch, provenance) of a profiled kernel, or (None, reason) if the sources changed since."""
+    digest = kernel_sources_digest()
+    src = {"profile": MEASURED_TRAFFIC["profile"], "kernel_sources_sha256": MEASURED_TRAFFIC["kernel_sources_sha256"],
+           "current_sources_sha256": digest}
+    if MEASURED_TRAFFIC["kernel_sources_sha256"] != digest:
+        src["stale"] = "kernel sources differ from those profiled: traffic not reported"
+        return None, src
+    t = MEASURED_TRAFFIC[key]
+    return 1024.0 * (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"]), src
 
 
 def train_kernel_ops(counters, W, lits, entries, nominal=False):
@@ -151,9 +178,111 @@ def cpu_baseline(hp, Xtr, ytr, Xte, seed, budget_s=15.0):
     if S2 > S:
         S, t = S2, run(S2)
     return {"value": S / t, "unit": "examples/s", "cores": 1, "kind": "oracle",
+            "regime": "untrained machine (initial states, epoch 0): every gate open, heavy Type I feedback; "
+                      "compare with first_step_ms / first_step_examples_per_s of the GPU, not with `value`, "
+                      "which is measured on the machine after the warm-up epochs",
             "sample": "sequential C oracle, 1 thread: tally pre-calculation + one Algorithm-1 pass over the first %d "
                       "training examples (all %d clauses) + prediction of %d test examples; %.1f s"
                       % (S, hp["m"] * hp["n"], max(1, S // 6), t)}
+
+
+def clause_sparsity(tm):
+    """(mean included literals, mean non-zero feature words) per clause of the current state, computed
+    on the device (the states of the largest sweep point are 300 MB)."""
+    import torch
+    inc = tm.get_ta_state() >= tm.N                       # uint8 (state - 1) [C][2o]: Include iff state > N
+    lits = float(inc.sum(1, dtype=torch.int64).double().mean())
+    either = inc[:, :tm.o] | inc[:, tm.o:]
+    pad = tm.Wf * 32 - tm.o
+    if pad:
+        either = torch.nn.functional.pad(either, (0, pad))
+    entries = float(either.view(tm.C, tm.Wf, 32).any(2).sum(1, dtype=torch.int64).double().mean())
+    return lits, entries
+
+
+def time_fit_epochs(tm, epochs):
+    """Runs `epochs` calls of tm_fit_epoch; returns (ms per epoch from stream events, counters, kernel timing)."""
+    import torch
+    from paper_2009_04861_amd import binding as B
+    tm.counters()
+    B.tm_kernel_timing(tm.h, True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(epochs):
+        B.tm_fit_epoch(tm.h)
+    e1.record()
+    torch.cuda.synchronize()
+    cnt = tm.counters()
+    kt = B.tm_read_kernel_timing(tm.h)
+    B.tm_kernel_timing(tm.h, False)
+    return e0.elapsed_time(e1) / epochs, cnt, kt
+
+
+def first_step(hp, seed, Xd, yd, Xte_d):
+    """The whole step on an untrained machine (the regime the cpu_baseline sample runs): first
+    tm_fit_epoch after bind, then tally pre-calculation and prediction."""
+    import torch
+    from paper_2009_04861_amd import binding as B
+    tm = B.TsetlinMachine(seed=seed, **hp)
+    qt = Xte_d.shape[0]
+    pred = torch.empty(qt, dtype=torch.int32, device=tm.dev)
+    scratch = torch.empty((qt, tm.m), dtype=torch.int32, device=tm.dev)
+    infer_ws = torch.empty(B.tm_infer_ws_bytes(tm.cfg, qt), dtype=torch.uint8, device=tm.dev)
+    tm.bind_train(Xd, yd)
+    tm.counters()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    B.tm_fit_epoch(tm.h)
+    ev[1].record()
+    B.tm_sync_tallies(tm.h)
+    B.tm_predict_ws(tm.h, Xte_d, pred, scratch, infer_ws)
+    ev[2].record()
+    torch.cuda.synchronize()
+    cnt = tm.counters()
+    out = {"first_epoch_ms": ev[0].elapsed_time(ev[1]), "first_step_ms": ev[0].elapsed_time(ev[2]),
+           "first_step_examples_per_s": Xd.shape[0] / (ev[0].elapsed_time(ev[2]) * 1e-3),
+           "first_epoch_gate_rate_of_candidates": cnt["fired"] / max(1, cnt["candidates"]),
+           "first_epoch_type1": cnt["type1"]}
+    tm.close()
+    return out
+
+
+SWEEP_N = (20, 100, 500, 2000, 7000, 20000)
+
+
+def clause_sweep(hp, seed, Xd, yd, epochs=2):
+    """Clause-scaling sweep on the same data (configs[3]): n clauses per class, T = 0.8 n so that the
+    gate never closes (steady feedback load).  One untimed epoch, then `epochs` timed ones per point."""
+    from paper_2009_04861_amd import binding as B
+    q = Xd.shape[0]
+    points = []
+    for n in SWEEP_N:
+        h2 = dict(hp)
+        h2["n"], h2["T"] = n, max(1, int(round(0.8 * n)))
+        tm = B.TsetlinMachine(seed=seed, **h2)
+        tm.bind_train(Xd, yd)
+        B.tm_fit_epoch(tm.h)
+        ms, cnt, kt = time_fit_epochs(tm, epochs)
+        lits, entries = clause_sparsity(tm)
+        train_ms, n_train = kt["train"]
+        ops = train_kernel_ops(cnt, 2 * tm.Wf, lits, entries)
+        points.append({"clauses_per_class": n, "clauses_total": tm.C, "T": h2["T"], "fit_epoch_ms": ms,
+                       "examples_per_s": q / (ms * 1e-3),
+                       "k_train_frac_alu": ops / (train_ms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
+                       "k_train_ms_per_epoch": train_ms / epochs,
+                       "gate_rate_of_candidates": cnt["fired"] / max(1, cnt["candidates"]),
+                       "us_per_clause_epoch": 1e3 * ms / tm.C})
+        tm.close()
+        del tm
+    t_min = min(p["fit_epoch_ms"] for p in points)
+    flat = [p["clauses_total"] for p in points if p["fit_epoch_ms"] <= 1.25 * t_min]
+    return {"points": points, "epochs_timed_per_point": epochs,
+            "flat_up_to_clauses_total": max(flat),
+            "knee": "epoch time within 1.25x of the smallest machine's up to this many clauses in total "
+                    "(one wavefront per clause, 1,024 SIMDs); beyond it time grows with the clause count",
+            "ratio_7000_to_20_clauses_per_class":
+                [p for p in points if p["clauses_per_class"] == 7000][0]["fit_epoch_ms"] / points[0]["fit_epoch_ms"]}
 
 
 def main():
@@ -170,6 +299,8 @@ def main():
     ap.add_argument("--q-train", type=int, default=None, help="override the number of training examples")
     ap.add_argument("--clause-groups", type=int, default=1,
                     help="sub-launches of consecutive clause ranges per training launch (tm_set_clause_groups)")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="leave out the first-step and clause-scaling measurements that follow the timed steps")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference dispatch for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -256,11 +387,7 @@ def main():
     train_ms, n_train = kt["train"]
     launch_ms = train_ms / max(1, n_train)
     # sparsity of the final state: included literals and non-zero feature words per clause
-    inc = (tm.get_ta_state() >= tm.N).cpu().numpy()
-    lits = float(inc.sum(1).mean())
-    pad = tm.Wf * 32 - tm.o
-    anyw = np.pad(inc[:, :tm.o] | inc[:, tm.o:], ((0, 0), (0, pad))).reshape(C, tm.Wf, 32).any(2)
-    entries = float(anyw.sum(1).mean())
+    lits, entries = clause_sparsity(tm)
     ops = train_kernel_ops(cnt, W, lits, entries) / max(1, n_train)
     ops_nominal = train_kernel_ops(cnt, W, lits, entries, nominal=True) / max(1, n_train)
     achieved = ops / (launch_ms * 1e-3) / 1e12
@@ -275,10 +402,8 @@ def main():
                  + 2 * 8 * cnt["blocks_evaluated"] / max(1, n_train))
     headline = (args.workload == "image_like" and args.clause_groups == 1
                 and not (args.small or args.clauses_per_class or args.q_train))
-    traffic = None
-    if headline and MEASURED_TRAFFIC["image_like_train"]["fetch_kib"] > 0:
-        t = MEASURED_TRAFFIC["image_like_train"]
-        traffic = 1024.0 * (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"])
+    traffic, traffic_src = (measured_traffic("image_like_train") if headline
+                            else (None, {"stale": "not the profiled configuration"}))
 
     out = {
         "metric": "training examples/sec per epoch (one step = fit epoch + tally pre-calculation + test-set prediction)",
@@ -309,6 +434,14 @@ def main():
             "blocks_evaluated_fraction": cnt["blocks_evaluated"] / max(1, args.steps * C * ((q + 63) // 64)),
             ("test_mae_over_T_after_run" if hp.get("regression") else "test_accuracy_after_run"): acc,
             "clause_groups": args.clause_groups,
+            "gate_draws_per_epoch": cnt["gate_draws"] / args.steps,
+            "regime": "epochs %d..%d of training: on this workload the machine has converged by then (most gates "
+                      "closed, most blocks skipped), so `value` measures the quiet regime of Algorithm 1; the "
+                      "feedback-loaded regime is in first_step_ms and in `sweep`"
+                      % (args.warmup + 1, args.warmup + args.steps),
+            "north_star_targets_not_met": "clause-evaluation kernel at >= 50 % of HBM bandwidth (see roofline of "
+                                          "k_eval_sparse); near-flat epoch time from 20 to 7,000 clauses per class "
+                                          "under steady feedback load (see sweep)",
         },
     }
     roof_train = {
@@ -319,6 +452,7 @@ def main():
         "unit": "Tlane-op/s (32-bit integer)",
         "frac": achieved / ALU_PEAK_TOPS,
         "traffic": traffic,
+        "traffic_source": traffic_src,
         "avg_launch_ms": launch_ms,
         "launches": n_train,
         "share_of_timed_region": train_ms / (1e3 * wall),
@@ -342,10 +476,8 @@ def main():
     words = (q + 31) // 32
     pre_bytes = 2 * tm.o * words * 4 + C * lits * 4 + C * words * 4 + tm.m * q * 4
     pre_ops = C * words * (lits + 3)
-    pre_traffic = None
-    if headline and MEASURED_TRAFFIC["image_like_precalc"]["fetch_kib"] > 0:
-        t = MEASURED_TRAFFIC["image_like_precalc"]
-        pre_traffic = 1024.0 * (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"])
+    pre_traffic, pre_traffic_src = (measured_traffic("image_like_precalc") if headline
+                                    else (None, {"stale": "not the profiled configuration"}))
     roof_eval = {
         "kernel": "k_eval_sparse (clause evaluation from literal lists + votes, in tm_sync_tallies)",
         "bound": "hbm",
@@ -354,6 +486,7 @@ def main():
         "unit": "GB/s",
         "frac": pre_bytes / (pre_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "traffic": pre_traffic,
+        "traffic_source": pre_traffic_src,
         "avg_launch_ms": pre_launch_ms,
         "launches": n_pre,
         "share_of_timed_region": pre_ms / (1e3 * wall),
@@ -370,10 +503,15 @@ def main():
         out["roofline"], out["roofline_other"] = roof_train, roof_eval
     else:
         out["roofline"], out["roofline_other"] = roof_eval, roof_train
+    tm.close()
+    del tm
+    if not args.no_sweep:
+        out["config"].update(first_step(hp, args.seed, Xd, yd, Xte_d))
+        if args.workload == "image_like" and not (args.clauses_per_class or args.small):
+            out["sweep"] = clause_sweep(hp, args.seed, Xd, yd)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(hp, Xtr, ytr, Xte, args.seed)
     print(json.dumps(out))
-    tm.close()
 
 
 if __name__ == "__main__":

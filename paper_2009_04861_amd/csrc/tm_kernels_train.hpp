@@ -106,8 +106,12 @@ __device__ __forceinline__ uint64_t eval64(const uint32_t *eoff, const uint2 *em
 }
 
 // Literals a clause's list in LDS can hold for the sweeps over outdated outputs; clauses
-// with more (untrained ones) are swept block by block with eval64.
-constexpr int TRAIN_LIT_MAX = 64;
+// with more (untrained ones) are swept block by block with eval64.  Trained clauses of the
+// image-like workload have 17 literals on average, but a few dozen of 20,000 grow past 64 within
+// 30 epochs and past 128 within 100 (always-true negated literals of pixels that are never set
+// cost nothing to include); block by block such a clause took 0.45 ms alone when it changed.
+constexpr int TRAIN_LIT_MAX = 256;
+constexpr int SWEEP_WORDS = 2; // words of 32 examples per lane and pass of a sweep through the literal list
 
 // Number of included literals of the clause held in p: the per-lane counts are summed bit by
 // bit with ballots, a loop-free wave sum.  (An atomic add on one LDS word would do, but the
@@ -163,19 +167,16 @@ constexpr int TRAIN_WAVES_MAX = 4; // most clauses (wavefronts) per workgroup of
 // list entry.  Blocks of 64 consecutive examples are evaluated (lane = example) only
 // when a gate in them fired or their stored outputs may be outdated; all other blocks
 // of the pass are never touched.
-template <int WPL, bool FULL, bool REGR>
-__global__ __launch_bounds__(64 * TRAIN_WAVES_MAX) void k_train(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
-                                                            const uint32_t *__restrict__ XB,
-                                                            const int32_t *__restrict__ gate,
-                                                            const int32_t *__restrict__ ngate, const TrainArgs a)
+// LAZY: the automata (all planes but the include masks) are fetched only when the first feedback
+// is due and written back only if there was one; otherwise they are loaded up front.  The kernel
+// holds both versions of the loop and picks per clause (see k_train).
+template <int WPL, bool FULL, bool REGR, bool LAZY>
+__device__ __forceinline__ void train_clause(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
+                                             const uint32_t *__restrict__ XB, const int32_t *__restrict__ gate,
+                                             const int k_hi, const TrainArgs &a, uint32_t *lds, const int g,
+                                             const int lane, const int wave)
 {
-    extern __shared__ uint32_t lds[];
     const Dims &d = a.d;
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int slot = a.slot_lo + (int)(blockIdx.x * (blockDim.x >> 6)) + wave;
-    if (slot >= a.slot_hi) return; // whole wavefront; the kernel has no workgroup-wide barrier
-    const int g = __builtin_amdgcn_readfirstlane(a.order[slot]);
     uint32_t *lmask = lds + wave * a.lds_wave_words;        // [W] include masks, literal-word order
     uint32_t *eoff = lmask + a.lds_mask_words;              // [Wf + EVAL_PAD] (rounded to 4 words)
     uint2 *emask = reinterpret_cast<uint2 *>(eoff + a.lds_off_words);
@@ -190,19 +191,35 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES_MAX) void k_train(const uint32_t *
     const uint32_t row_bytes = (uint32_t)a.qp * 4u;
     const int i_begin = a.i_begin, i_end = a.i_end, q = a.q;
 
+    // The automata of the clause.  Until the first gate fires only the include masks (plane 7, of
+    // which `inc` holds a compact copy) are needed - for evaluation and sweeps -, so the other seven
+    // planes are fetched when the first feedback is due and written back only if there was one: in a
+    // trained machine most clauses get no feedback in an epoch and move 200 bytes instead of 3.2 KB.
     u32x8 p[WPL];
 #pragma unroll
     for (int r = 0; r < WPL; ++r) {
         const int lw = r * 64 + lane;
         u32x8 t = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-        if (lw < d.W) {
-            const uint4 *src = reinterpret_cast<const uint4 *>(a.planes + ((int64_t)g * d.W + lw) * 8);
-            const uint4 v0 = src[0], v1 = src[1];
-            t[0] = v0.x; t[1] = v0.y; t[2] = v0.z; t[3] = v0.w;
-            t[4] = v1.x; t[5] = v1.y; t[6] = v1.z; t[7] = v1.w;
-        }
+        if (lw < d.W) t[7] = a.inc[(int64_t)g * d.W + lw];
         p[r] = t;
     }
+    bool have_planes = false;
+    auto load_planes = [&]() {
+#pragma unroll
+        for (int r = 0; r < WPL; ++r) {
+            const int lw = r * 64 + lane;
+            if (lw < d.W) {
+                const uint4 *src = reinterpret_cast<const uint4 *>(a.planes + ((int64_t)g * d.W + lw) * 8);
+                const uint4 v0 = src[0], v1 = src[1];
+                u32x8 t;
+                t[0] = v0.x; t[1] = v0.y; t[2] = v0.z; t[3] = v0.w;
+                t[4] = v1.x; t[5] = v1.y; t[6] = v1.z; t[7] = v1.w; // equals the include mask held so far
+                p[r] = t;
+            }
+        }
+        have_planes = true;
+    };
+    if (!LAZY) load_planes();
     int nent = build_entries<WPL>(p, lmask, eoff, emask, lane, d.Wf, d.W, row_bytes);
 
     // lowest Philox block of the Type I comparator that can matter: bits of the
@@ -234,7 +251,7 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES_MAX) void k_train(const uint32_t *
 
     // the gate list of this class for this launch
     const int32_t *list = gate + (int64_t)c * a.qp;
-    const int k_lo = 0, k_hi = ngate[c];
+    const int k_lo = 0;
     const int32_t *tally_c = a.tally + (int64_t)c * a.qp;
 
     // state of the block of 64 examples that is currently open (cb < 0: none)
@@ -293,35 +310,61 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES_MAX) void k_train(const uint32_t *
     const char *xb_base = reinterpret_cast<const char *>(XB);
     uint32_t *ostar_row = a.ostar + (int64_t)g * a.Qw;
     auto sweep_listed = [&](int bs, int be) { // blocks [bs, be), all of them possibly outdated
-        for (int w0 = 2 * bs; w0 < 2 * be; w0 += 64) {
-            const int w = w0 + lane;
-            const bool act = w < 2 * be;
-            const int e0 = w << 5;
-            const int lo = min(max(i_begin - e0, 0), 32), hi = min(max(i_end - e0, 0), 32);
-            uint32_t rm = 0u; // examples of the word that belong to this launch
-            if (act && hi > lo) rm = (hi == 32 ? ~0u : (1u << hi) - 1u) & ~((1u << lo) - 1u);
-            const uint32_t woff = act ? (uint32_t)w * 4u : 0u;
-            const uint32_t ost = act ? ostar_row[w] : 0u;
-            uint32_t accv = rm;
-            for (int k = 0; k < n_listed; k += 8) { // eight literals per round (the list is padded to a multiple of 8)
-                const uint4 e = *reinterpret_cast<const uint4 *>(llist + k), e2 = *reinterpret_cast<const uint4 *>(llist + k + 4);
-                const uint32_t x0 = *reinterpret_cast<const uint32_t *>(xb_base + (e.x + woff));
-                const uint32_t x1 = *reinterpret_cast<const uint32_t *>(xb_base + (e.y + woff));
-                const uint32_t x2 = *reinterpret_cast<const uint32_t *>(xb_base + (e.z + woff));
-                const uint32_t x3 = *reinterpret_cast<const uint32_t *>(xb_base + (e.w + woff));
-                const uint32_t x4 = *reinterpret_cast<const uint32_t *>(xb_base + (e2.x + woff));
-                const uint32_t x5 = *reinterpret_cast<const uint32_t *>(xb_base + (e2.y + woff));
-                const uint32_t x6 = *reinterpret_cast<const uint32_t *>(xb_base + (e2.z + woff));
-                const uint32_t x7 = *reinterpret_cast<const uint32_t *>(xb_base + (e2.w + woff));
-                accv &= x0 & x1 & x2 & x3 & x4 & x5 & x6 & x7;
+        // SWEEP_WORDS words per lane and pass, eight literals per round: 16 independent loads in flight.
+        // What a sweep costs is the number of dependent trips to the L2 - a clause whose mask changed
+        // walks the rest of the epoch alone, and the last such clause is the tail of the launch
+        // (measured per wavefront: 2.6 us per pass of 2,048 examples and 28 literals before, one word
+        // per lane).  Four words per lane halve the trips again but cost 24 registers and with them a
+        // wavefront per SIMD: 6-8 % on feedback-bound epochs, so two it is.
+        const int w_end = 2 * be;
+        for (int w0 = 2 * bs; w0 < w_end; w0 += 64 * SWEEP_WORDS) {
+            uint32_t rm[SWEEP_WORDS], woff[SWEEP_WORDS], ost[SWEEP_WORDS], accv[SWEEP_WORDS];
+#pragma unroll
+            for (int u = 0; u < SWEEP_WORDS; ++u) {
+                const int w = w0 + u * 64 + lane;
+                const bool act = w < w_end;
+                const int e0 = w << 5;
+                const int lo = min(max(i_begin - e0, 0), 32), hi = min(max(i_end - e0, 0), 32);
+                rm[u] = 0u; // examples of the word that belong to this launch
+                if (act && hi > lo) rm[u] = (hi == 32 ? ~0u : (1u << hi) - 1u) & ~((1u << lo) - 1u);
+                woff[u] = act ? (uint32_t)w * 4u : 0u;
+                ost[u] = act ? ostar_row[w] : 0u;
+                accv[u] = rm[u];
             }
-            uint32_t diff = (accv ^ ost) & rm;
-            if (diff) ostar_row[w] = ost ^ diff;
-            n_changes_v += (uint32_t)__builtin_popcount(diff);
-            while (diff) { // one tally correction per changed example
-                const int bit = __builtin_ctz(diff);
-                diff &= diff - 1u;
-                atomicAdd(&a.tally[(int64_t)c * a.qp + e0 + bit], ((accv >> bit) & 1u) ? sign : -sign);
+            for (int k = 0; k < n_listed; k += 8) { // the list is padded to a multiple of 8 with the all-ones row
+                const uint4 e = *reinterpret_cast<const uint4 *>(llist + k), e2 = *reinterpret_cast<const uint4 *>(llist + k + 4);
+                uint32_t x[SWEEP_WORDS][8];
+#pragma unroll
+                for (int u = 0; u < SWEEP_WORDS; ++u) {
+                    x[u][0] = *reinterpret_cast<const uint32_t *>(xb_base + (e.x + woff[u]));
+                    x[u][1] = *reinterpret_cast<const uint32_t *>(xb_base + (e.y + woff[u]));
+                    x[u][2] = *reinterpret_cast<const uint32_t *>(xb_base + (e.z + woff[u]));
+                    x[u][3] = *reinterpret_cast<const uint32_t *>(xb_base + (e.w + woff[u]));
+                    x[u][4] = *reinterpret_cast<const uint32_t *>(xb_base + (e2.x + woff[u]));
+                    x[u][5] = *reinterpret_cast<const uint32_t *>(xb_base + (e2.y + woff[u]));
+                    x[u][6] = *reinterpret_cast<const uint32_t *>(xb_base + (e2.z + woff[u]));
+                    x[u][7] = *reinterpret_cast<const uint32_t *>(xb_base + (e2.w + woff[u]));
+                }
+                uint32_t any = 0u;
+#pragma unroll
+                for (int u = 0; u < SWEEP_WORDS; ++u) {
+                    accv[u] &= x[u][0] & x[u][1] & x[u][2] & x[u][3] & x[u][4] & x[u][5] & x[u][6] & x[u][7];
+                    any |= accv[u];
+                }
+                // a clause of many literals is false on all examples of the pass after a few rounds
+                if (n_listed > 32 && ballot(any != 0u) == 0) break;
+            }
+#pragma unroll
+            for (int u = 0; u < SWEEP_WORDS; ++u) {
+                const int w = w0 + u * 64 + lane;
+                uint32_t diff = (accv[u] ^ ost[u]) & rm[u];
+                if (diff) ostar_row[w] = ost[u] ^ diff;
+                n_changes_v += (uint32_t)__builtin_popcount(diff);
+                while (diff) { // one tally correction per changed example
+                    const int bit = __builtin_ctz(diff);
+                    diff &= diff - 1u;
+                    atomicAdd(&a.tally[(int64_t)c * a.qp + (w << 5) + bit], ((accv[u] >> bit) & 1u) ? sign : -sign);
+                }
             }
         }
         n_eval += (uint32_t)(be - bs);
@@ -490,6 +533,8 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES_MAX) void k_train(const uint32_t *
             const int bl = ii & 63;                  // position of the example in the open block
             const bool tgt = (tmask >> l) & 1;
             const bool Cout = (obits >> bl) & 1;     // clause output on the state before the update
+            // Type II feedback to a clause whose output is 0 changes nothing (Table 2): no automata needed
+            if (LAZY && !have_planes && (tgt == pos || Cout)) load_planes();
             uint32_t changed = 0;
             uint32_t xw[WPL];
 #pragma unroll
@@ -591,15 +636,17 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES_MAX) void k_train(const uint32_t *
     if (plo >= phi) plo = phi = 0;
     if (lane == 0) *reinterpret_cast<int4 *>(a.fresh + (int64_t)g * 4) = make_int4(plo, phi, slo, 0);
 
+    if (!LAZY || have_planes) { // a gate fired: the automata may have moved
 #pragma unroll
-    for (int r = 0; r < WPL; ++r) {
-        const int lw = r * 64 + lane;
-        if (lw < d.W) {
-            uint4 *dst = reinterpret_cast<uint4 *>(a.planes + ((int64_t)g * d.W + lw) * 8);
-            const u32x8 t = p[r];
-            dst[0] = make_uint4(t[0], t[1], t[2], t[3]);
-            dst[1] = make_uint4(t[4], t[5], t[6], t[7]);
-            a.inc[(int64_t)g * d.W + lw] = t[7];
+        for (int r = 0; r < WPL; ++r) {
+            const int lw = r * 64 + lane;
+            if (lw < d.W) {
+                uint4 *dst = reinterpret_cast<uint4 *>(a.planes + ((int64_t)g * d.W + lw) * 8);
+                const u32x8 t = p[r];
+                dst[0] = make_uint4(t[0], t[1], t[2], t[3]);
+                dst[1] = make_uint4(t[4], t[5], t[6], t[7]);
+                a.inc[(int64_t)g * d.W + lw] = t[7];
+            }
         }
     }
     for (int sh = 32; sh > 0; sh >>= 1) n_changes_v += __shfl_xor(n_changes_v, sh, 64);
@@ -612,6 +659,29 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES_MAX) void k_train(const uint32_t *
                          : (uint32_t)(i_end - i_begin);
         if (v) atomicAdd(&a.counters[(g & (COUNTER_SETS - 1)) * COUNTER_WIDTH + lane], (unsigned long long)v);
     }
+}
+
+// A clause whose class has many open gates in this launch is all but certain to get feedback: its
+// automata are loaded up front and the loop carries no check for them (the check and the pointers it
+// keeps alive cost the feedback-bound regime 3-10 %).  With few open gates - a trained machine - most
+// clauses get none, and the lazy version saves moving their automata (16 % of a quiet epoch).
+constexpr int TRAIN_EAGER_CANDIDATES = 256;
+
+template <int WPL, bool FULL, bool REGR>
+__global__ __launch_bounds__(64 * TRAIN_WAVES_MAX) void k_train(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
+                                                            const uint32_t *__restrict__ XB,
+                                                            const int32_t *__restrict__ gate,
+                                                            const int32_t *__restrict__ ngate, const TrainArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int slot = a.slot_lo + (int)(blockIdx.x * (blockDim.x >> 6)) + wave;
+    if (slot >= a.slot_hi) return; // whole wavefront; the kernel has no workgroup-wide barrier
+    const int g = __builtin_amdgcn_readfirstlane(a.order[slot]);
+    const int k_hi = __builtin_amdgcn_readfirstlane(ngate[g / a.d.n]);
+    if (k_hi >= TRAIN_EAGER_CANDIDATES) train_clause<WPL, FULL, REGR, false>(X, XT, XB, gate, k_hi, a, lds, g, lane, wave);
+    else train_clause<WPL, FULL, REGR, true>(X, XT, XB, gate, k_hi, a, lds, g, lane, wave);
 }
 
 } // namespace tsetlin

@@ -295,7 +295,7 @@ def test_set_state_after_bind_then_step_refreshes_everything(device):
 def test_long_runs_of_outdated_blocks_are_swept_through_literal_lists(o, device):
     """Sparse clauses pushed after bind leave every stored output outdated; few gates can open,
     so the passes refresh long runs of blocks, 2048 examples at a time through the clause's
-    literal list (clauses of up to 4 register slots per lane; o = 5000 keeps to the block-by-block path).  Ranges start and
+    literal list (clauses of up to 4 register slots per lane and 256 literals; o = 5000 keeps to the block-by-block path).  Ranges start and
     end inside blocks and words; 5,000 examples span two segments of the launch preparation."""
     m, n, N, T, s = 3, 6, 64, 2, 4.0
     print("list sweeps", o, flush=True)
@@ -303,11 +303,14 @@ def test_long_runs_of_outdated_blocks_are_swept_through_literal_lists(o, device)
     q = 5000
     ora, gpu = make_pair(m, n, o, N, T, s, 5)
     X, y = rand_problem(rng, q, o, m)
+    X[::7, :300] = 0                                           # every seventh example satisfies the 300-literal clause below
     gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
     tally, ostar = ora.sync_tallies(X)
     ora.state[:] = sparse_random_state(rng, ora.C, ora.L, N, 2.5 / o)
     ora.state[0, :] = 1                                        # an empty clause
-    ora.state[1, :70] = 2 * N                                  # 70 literals: more than the list in LDS holds
+    ora.state[1, :70] = 2 * N                                  # 70 literals: several rounds of the list sweep
+    if o >= 300:
+        ora.state[2, o:o + 300] = 2 * N                        # 300 negated literals: more than the list in LDS holds
     push_state(gpu, ora.state)
     gpu.counters()
     # snapshot that closes every gate (+T for the label, -T elsewhere) except on 2 % of the examples
