@@ -493,6 +493,11 @@ def main():
         "hbm_algorithmic_bytes_per_launch": pre_bytes,
         "algorithmic_lane_ops_per_launch": pre_ops,
         "alu_frac": pre_ops / (pre_launch_ms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
+        # Eq. 1 as literally read: every pair tested against all 2*Wf mask words (one fused bit operation each).
+        # Above 1 means the launch finishes faster than the integer-ALU peak allows for that reading; the
+        # literal lists are what makes the difference.
+        "nominal_lane_ops_per_launch": float(q) * C * W,
+        "nominal_alu_frac": float(q) * C * W / (pre_launch_ms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
         "l1_bytes_per_launch": C * words * (4 * ((lits + 3) // 4)) * 4,
         "clause_evals_per_s": q * C / (pre_launch_ms * 1e-3),
     }

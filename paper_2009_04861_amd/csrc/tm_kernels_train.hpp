@@ -680,8 +680,10 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES_MAX) void k_train(const uint32_t *
     if (slot >= a.slot_hi) return; // whole wavefront; the kernel has no workgroup-wide barrier
     const int g = __builtin_amdgcn_readfirstlane(a.order[slot]);
     const int k_hi = __builtin_amdgcn_readfirstlane(ngate[g / a.d.n]);
-    if (k_hi >= TRAIN_EAGER_CANDIDATES) train_clause<WPL, FULL, REGR, false>(X, XT, XB, gate, k_hi, a, lds, g, lane, wave);
-    else train_clause<WPL, FULL, REGR, true>(X, XT, XB, gate, k_hi, a, lds, g, lane, wave);
+    // wide clauses keep to the one version: the lazy one holds the addresses of all their register slots
+    // alive through the loop (36 more registers with 10 slots: one wavefront per SIMD instead of two)
+    if (WPL > 4 || k_hi >= TRAIN_EAGER_CANDIDATES) train_clause<WPL, FULL, REGR, false>(X, XT, XB, gate, k_hi, a, lds, g, lane, wave);
+    else train_clause<WPL, FULL, REGR, WPL <= 4>(X, XT, XB, gate, k_hi, a, lds, g, lane, wave);
 }
 
 } // namespace tsetlin
