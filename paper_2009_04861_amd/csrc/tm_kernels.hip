@@ -10,7 +10,8 @@
 //                  ostar  uint32 [C][Qw]    previous clause outputs, 1 bit per (clause, example), Qw = qp/32
 //                  XT     uint32 [Wf][qp]   transposed features (word-major) for lane = example evaluation
 //                  XB     uint32 [2o+1][QW] literals as bit rows over the examples (row 2o all ones), QW = 64*ceil(q/2048)
-//                  lits   uint32 [C][cap]   literal lists of the clauses (cap = 128..1024), nlit int32 [C] their lengths
+//                  lits   uint32 [slots][cap] literal lists of the clauses (cap = 128..1024), interleaved by batches of eight as
+//                                           the evaluation kernel walks them (k_literal_lists), nlit int32 [slots] their lengths
 //                  gate   int32  [m][qp]    per class and launch: ascending list of (example << 1 | target) whose gate can open
 //                  fresh  int32  [C][4]     per clause: example ranges whose stored outputs may be outdated
 //                  order  int32  [C]        launch order of the clauses (outdated ones first)
@@ -86,8 +87,8 @@ struct tm_handle {
     uint32_t *ostar;
     uint32_t *XT;
     uint32_t *XB;   // [2o+1][QW] literal rows of the bound data
-    uint32_t *lits; // [C][lit_cap(d)]
-    int32_t *nlit;  // [C]
+    uint32_t *lits; // literal lists, see k_literal_lists
+    int32_t *nlit;  // their lengths
     int32_t *gate;  // [m][qp] gate lists of the current launch
     int32_t *ngate; // [m]
     int32_t *fresh;
@@ -186,6 +187,40 @@ inline int lit_cap(const Dims &d)
     return std::min(LIT_CAP_MAX, std::max(LIT_CAP_MIN, want));
 }
 
+// How k_eval_sparse splits the clauses of a class: over S workgroups (8 wavefronts each, three of
+// them per CU) of `chunk` clauses (a multiple of 16).  About 1,024 workgroups in all, but at least 256
+// clauses per workgroup (zeroing, converting and adding up a workgroup's sums costs as much as walking
+// a few hundred clauses), at least 16 per workgroup.  Measured on 10 x 2,000 clauses: 60,000 examples
+// 0.23 -> 0.19 ms against one workgroup of 16 wavefronts per CU, 10,000 examples 0.072 -> 0.054 ms.
+// A wavefront walks chunk / SP_WAVES clauses and counts their votes in SP_PLANES bit planes, so a
+// chunk holds at most (2^SP_PLANES - 1) * SP_WAVES clauses, rounded DOWN to a multiple of 16.
+// Returns false if the bound is violated (cannot happen).
+inline bool eval_shares(const Dims &d, int64_t ranges, int64_t *S_out, int64_t *chunk_out)
+{
+    const int64_t chunk_max = (((int64_t)((1 << SP_PLANES) - 1) * SP_WAVES) / 16) * 16;
+    int64_t S = (8192 / SP_WAVES + d.m * ranges - 1) / (d.m * ranges);
+    S = std::min<int64_t>(S, std::max<int64_t>(1, d.n / 256));
+    S = std::max<int64_t>(S, (d.n + chunk_max - 1) / chunk_max);
+    S = std::min<int64_t>(S, (d.n + 15) / 16);
+    const int64_t chunk = std::min<int64_t>((((d.n + S - 1) / S) + 15) & ~(int64_t)15, chunk_max);
+    S = (d.n + chunk - 1) / chunk;
+    *S_out = S;
+    *chunk_out = chunk;
+    return chunk / SP_WAVES < (1 << SP_PLANES) && S * chunk >= d.n && chunk % 16 == 0;
+}
+
+// Layout of the literal lists for q examples (see k_literal_lists): depends on how the classes are split.
+inline ListLayout list_layout(const Dims &d, int64_t q)
+{
+    int64_t S = 1, chunk = 16;
+    (void)eval_shares(d, xb_row_words(std::max<int64_t>(q, 1)) / 64, &S, &chunk);
+    ListLayout ll;
+    ll.S = (int)S; ll.chunk = (int)chunk; ll.nbatch = (int)((chunk + 63) / 64); ll.cap = lit_cap(d);
+    return ll;
+}
+inline size_t lits_bytes(const Dims &d, int64_t q) { const ListLayout ll = list_layout(d, q); return (size_t)list_slots(d.m, ll) * ll.cap * 4; }
+inline size_t nlit_bytes(const Dims &d, int64_t q) { return (size_t)list_slots(d.m, list_layout(d, q)) * 4; }
+
 struct WsLayout {
     size_t tally, ostar, xt, xb, lits, nlit, gate, ngate, fresh, order, seg_cnt, counters, flag, total;
 };
@@ -200,8 +235,8 @@ WsLayout ws_layout(const Dims &d, int64_t q)
     L.ostar = off; off += align256((size_t)d.C * Qw * 4);
     L.xt = off; off += align256((size_t)d.Wf * qp * 4);
     L.xb = off; off += align256(xb_bytes(d, q));
-    L.lits = off; off += align256((size_t)d.C * lit_cap(d) * 4);
-    L.nlit = off; off += align256((size_t)d.C * 4);
+    L.lits = off; off += align256(lits_bytes(d, q));
+    L.nlit = off; off += align256(nlit_bytes(d, q));
     L.gate = off; off += align256((size_t)d.m * qp * 4);
     L.ngate = off; off += align256((size_t)d.m * 4);
     L.fresh = off; off += align256((size_t)d.C * 16);
@@ -349,28 +384,6 @@ int build_xb(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *XB, hipStream
     return TM_OK;
 }
 
-// How k_eval_sparse splits the clauses of a class: over S workgroups (8 wavefronts each, three of
-// them per CU) of `chunk` clauses (a multiple of 16).  About 1,024 workgroups in all, but at least 256
-// clauses per workgroup (zeroing, converting and adding up a workgroup's sums costs as much as walking
-// a few hundred clauses), at least 16 per workgroup.  Measured on 10 x 2,000 clauses: 60,000 examples
-// 0.23 -> 0.19 ms against one workgroup of 16 wavefronts per CU, 10,000 examples 0.072 -> 0.054 ms.
-// A wavefront walks chunk / SP_WAVES clauses and counts their votes in SP_PLANES bit planes, so a
-// chunk holds at most (2^SP_PLANES - 1) * SP_WAVES clauses, rounded DOWN to a multiple of 16.
-// Returns false if the bound is violated (cannot happen).
-inline bool eval_shares(const Dims &d, int64_t ranges, int64_t *S_out, int64_t *chunk_out)
-{
-    const int64_t chunk_max = (((int64_t)((1 << SP_PLANES) - 1) * SP_WAVES) / 16) * 16;
-    int64_t S = (8192 / SP_WAVES + d.m * ranges - 1) / (d.m * ranges);
-    S = std::min<int64_t>(S, std::max<int64_t>(1, d.n / 256));
-    S = std::max<int64_t>(S, (d.n + chunk_max - 1) / chunk_max);
-    S = std::min<int64_t>(S, (d.n + 15) / 16);
-    const int64_t chunk = std::min<int64_t>((((d.n + S - 1) / S) + 15) & ~(int64_t)15, chunk_max);
-    S = (d.n + chunk - 1) / chunk;
-    *S_out = S;
-    *chunk_out = chunk;
-    return chunk / SP_WAVES < (1 << SP_PLANES) && S * chunk >= d.n && chunk % 16 == 0;
-}
-
 // Evaluation of all clauses on the q examples behind XB from their literal lists (rebuilt
 // here from the current masks); writes bits and/or the class sums.  With clampT > 0 the
 // sums are clamped.  acc need not be zeroed by the caller.
@@ -386,14 +399,15 @@ int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *li
     int64_t S, chunk;
     const int64_t ranges = QW / 64;
     if (!eval_shares(d, ranges, &S, &chunk)) return TM_ELIMIT; // cannot happen; guards the vote counters
-    a.S = (int)S; a.chunk = (int)chunk; a.T = (S == 1) ? clampT : 0;
+    const ListLayout ll = list_layout(d, q);
+    a.S = (int)S; a.chunk = (int)chunk; a.nbatch = ll.nbatch; a.T = (S == 1) ? clampT : 0;
     a.Tlo = d.regr ? 0 : -a.T; a.all_pos = d.regr;
     // partial sums of several workgroups are added up: they start from zero (either layout, [m][qp] or
     // [q][m]: up to the last element written), cleared by the kernel that builds the lists
     const int64_t zero_words = (acc && S > 1) ? (q - 1) * acc_si + (d.m - 1) * acc_sc + 1 : 0;
-    hipLaunchKernelGGL(k_literal_lists, dim3(blocks_for(d.C, 4)), dim3(256), 0, st, h->inc, lits, nlit, d.C, d.Wf, d.W,
-                       d.o, lit_cap(d), (uint32_t)(QW * 4), fresh, (int)h->qp, reinterpret_cast<uint32_t *>(acc),
-                       zero_words);
+    hipLaunchKernelGGL(k_literal_lists, dim3(blocks_for(list_slots(d.m, ll), 4)), dim3(256), 0, st, h->inc, lits, nlit,
+                       d.m, d.n, d.Wf, d.W, d.o, ll, (uint32_t)(QW * 4), fresh, (int)h->qp,
+                       reinterpret_cast<uint32_t *>(acc), zero_words);
     TM_HIP(h, hipGetLastError());
     int rc = timing_mark(h, timed_kind, true, st);
     if (rc) return rc;
@@ -706,7 +720,7 @@ int tm_infer_ws_bytes(const tm_config *cfg, int64_t q, size_t *out)
     if (rc) return rc;
     if (!out || q < 0) return TM_EINVAL;
     const Dims d = make_dims(cfg);
-    *out = align256(xb_bytes(d, q)) + align256((size_t)d.C * lit_cap(d) * 4) + align256((size_t)d.C * 4);
+    *out = align256(xb_bytes(d, q)) + align256(lits_bytes(d, q)) + align256(nlit_bytes(d, q));
     return TM_OK;
 }
 
@@ -724,7 +738,7 @@ static int infer_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, i
     char *base = (char *)ws;
     uint32_t *XB = (uint32_t *)base;
     uint32_t *lits = (uint32_t *)(base + align256(xb_bytes(d, q)));
-    int32_t *nlit = (int32_t *)(base + align256(xb_bytes(d, q)) + align256((size_t)d.C * lit_cap(d) * 4));
+    int32_t *nlit = (int32_t *)(base + align256(xb_bytes(d, q)) + align256(lits_bytes(d, q)));
     const int rc = build_xb(h, X, q, XB, st);
     if (rc) return rc;
     return launch_eval_sparse(h, XB, q, lits, nlit, nullptr, 0, sums, d.m, 1, d.T, pred, nullptr, timed_kind, st);

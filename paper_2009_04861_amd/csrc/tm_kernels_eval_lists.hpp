@@ -56,30 +56,56 @@ __global__ __launch_bounds__(256) void k_transpose_bits(const uint32_t *__restri
     }
 }
 
-// Literal list of every clause, one wavefront per clause: entry = byte offset of the
-// literal's row in XB; the first `cap` included literals in literal order (cap = list
-// capacity, a multiple of 4 chosen from the number of features), the rest of the cap
-// slots filled with the all-ones row so that several clauses can be walked in step.
-// nlit[g] = number of included literals (may exceed cap; such clauses are finished from
-// their masks).
+// Literal lists of the clauses, laid out for the wavefronts that walk them.  k_eval_sparse gives
+// wavefront w of the workgroup of (class c, share s) the clauses j = s*chunk + w + 8 t of the class
+// and walks them in batches of eight (t = 8 b + u, u = 0..7), four list entries of each per round.
+// The lists of a batch are therefore interleaved: for batch B = ((c*S + s)*8 + w)*nbatch + b,
+//   lits[(B*(cap/4) + k/4)*32 + u*4 + k%4] = entry k of the clause in slot u,   nlit[B*8 + u] = its length,
+// so that a round's 32 entries are 128 contiguous bytes behind one pointer (two scalar loads and one
+// pointer increment per round instead of eight of each: the kernel is sensitive to the load of
+// the CU's scalar unit).  Entry = byte offset of the literal's row in XB; the first `cap` included
+// literals in literal order (cap = list capacity, a multiple of 64), the rest of the cap slots
+// filled with the all-ones row so that the clauses of a batch can be walked in step; slots of a
+// batch beyond the clauses of the share hold the all-ones row throughout and length 0.
+// nlit = number of included literals (may exceed cap; such clauses are finished from their masks).
+// One wavefront per slot.
+struct ListLayout {
+    int S, chunk, nbatch; // shares per class, clauses per share, batches per wavefront = ceil(chunk / 64)
+    int cap;              // entries per list
+};
+
+__device__ __host__ inline int64_t list_slots(int m, const ListLayout &ll) { return (int64_t)m * ll.S * SP_WAVES * ll.nbatch * 8; }
+
 __global__ __launch_bounds__(256) void k_literal_lists(const uint32_t *__restrict__ inc, uint32_t *__restrict__ lits,
-                                                       int32_t *__restrict__ nlit, int C, int Wf, int W, int o,
-                                                       int cap, uint32_t row_bytes, int32_t *fresh, int qp,
+                                                       int32_t *__restrict__ nlit, int m, int n, int Wf, int W, int o,
+                                                       ListLayout ll, uint32_t row_bytes, int32_t *fresh, int qp,
                                                        uint32_t *zero, int64_t zero_words)
 {
     // on the side: clear the buffer in which the evaluation kernel will add up partial sums
     for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < zero_words; t += (int64_t)gridDim.x * 256) zero[t] = 0u;
+    // ahead of a tally pre-calculation: every stored output of every clause will be current
+    if (fresh)
+        for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < (int64_t)m * n; g += (int64_t)gridDim.x * 256)
+            *reinterpret_cast<int4 *>(fresh + g * 4) = make_int4(0, 0, qp, 0);
     const int lane = threadIdx.x & 63;
-    const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (g >= C) return;
-    // ahead of a tally pre-calculation: every stored output of the clause will be current
-    if (fresh && lane == 0) *reinterpret_cast<int4 *>(fresh + (int64_t)g * 4) = make_int4(0, 0, qp, 0);
-    uint32_t *L = lits + (int64_t)g * cap;
+    const int64_t slot = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (slot >= list_slots(m, ll)) return;
+    const int u = (int)(slot & 7);
+    const int64_t B = slot >> 3;
+    const int b = (int)(B % ll.nbatch);
+    const int w = (int)((B / ll.nbatch) % SP_WAVES);
+    const int cs = (int)(B / ((int64_t)ll.nbatch * SP_WAVES));
+    const int c = cs / ll.S, sh = cs - c * ll.S;
+    const int j = sh * ll.chunk + w + SP_WAVES * (8 * b + u);
+    const bool real = j < min(n, (sh + 1) * ll.chunk);
+    const int g = c * n + (real ? j : 0);
+    uint32_t *L = lits + B * (int64_t)(ll.cap / 4) * 32 + u * 4; // entry k at L[(k / 4) * 32 + k % 4]
+    const int cap = ll.cap;
     int base = 0;
-    for (int w0 = 0; w0 < W; w0 += 64) {
+    for (int w0 = 0; w0 < W && real; w0 += 64) {
         const int lw = w0 + lane;
-        uint32_t m = lw < W ? inc[(int64_t)g * W + lw] : 0u;
-        const int cnt = __builtin_popcount(m);
+        uint32_t mk = lw < W ? inc[(int64_t)g * W + lw] : 0u;
+        const int cnt = __builtin_popcount(mk);
         int incl = cnt; // inclusive prefix sum over the lanes
 #pragma unroll
         for (int dlt = 1; dlt < 64; dlt <<= 1) {
@@ -88,16 +114,16 @@ __global__ __launch_bounds__(256) void k_literal_lists(const uint32_t *__restric
         }
         int pos = base + incl - cnt;
         const uint32_t k0 = lw >= Wf ? (uint32_t)o + (uint32_t)(lw - Wf) * 32u : (uint32_t)lw * 32u; // literal of bit 0
-        while (m) {
-            const int b = __builtin_ctz(m);
-            m &= m - 1u;
-            if (pos < cap) L[pos] = (k0 + (uint32_t)b) * row_bytes;
+        while (mk) {
+            const int bit = __builtin_ctz(mk);
+            mk &= mk - 1u;
+            if (pos < cap) L[(pos >> 2) * 32 + (pos & 3)] = (k0 + (uint32_t)bit) * row_bytes;
             ++pos;
         }
         base += __shfl(incl, 63, 64);
     }
-    for (int t = min(base, cap) + lane; t < cap; t += 64) L[t] = 2u * (uint32_t)o * row_bytes;
-    if (lane == 0) nlit[g] = base;
+    for (int t = min(base, cap) + lane; t < cap; t += 64) L[(t >> 2) * 32 + (t & 3)] = 2u * (uint32_t)o * row_bytes;
+    if (lane == 0) nlit[slot] = base;
 }
 
 struct SparseArgs {
@@ -111,6 +137,7 @@ struct SparseArgs {
     int lit_cap;         // entries per literal list
     int ranges, by_xcd;  // ranges of 2048 examples; workgroup -> (range, class, share) mapping
     int S, chunk;        // clauses of a class are split over S workgroups, `chunk` (a multiple of 16) each
+    int nbatch;          // batches of eight clauses per wavefront: ceil(chunk / 64) (list layout)
     int T;               // > 0: the sums are clamped to [Tlo, T] (only with S = 1)
     int Tlo;             // -T, or 0 in regression mode
     int all_pos;         // regression mode: every clause votes +1
@@ -188,22 +215,22 @@ __global__ __launch_bounds__(64 * SP_WAVES) void k_eval_sparse(const uint32_t *_
         hi = majority3(x, y, z);
         lo = xor3(x, y, z);
     };
-    for (int j0 = j_lo + wave; j0 < j_hi; j0 += 8 * SP_WAVES) {
+    int64_t B = ((int64_t)cs * SP_WAVES + wave) * a.nbatch; // first batch of this wavefront in the list layout
+    for (int j0 = j_lo + wave; j0 < j_hi; j0 += 8 * SP_WAVES, ++B) {
         // eight clauses are walked in step, four literals each per round: 32 loads in flight
         uint32_t x[8];
-        const uint32_t *L[8];
         int nl[8], longest = 0;
+        const int4 *NL = reinterpret_cast<const int4 *>(nlit + B * 8);
+        const int4 n0 = NL[0], n1 = NL[1];
+        nl[0] = n0.x; nl[1] = n0.y; nl[2] = n0.z; nl[3] = n0.w; nl[4] = n1.x; nl[5] = n1.y; nl[6] = n1.z; nl[7] = n1.w;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int j = j0 + u * SP_WAVES;
-            const bool ok = j < j_hi;
-            const int g = c * a.n + (ok ? j : j_lo);
-            L[u] = lits + (int64_t)g * a.lit_cap;
-            nl[u] = ok ? nlit[g] : 0;
-            x[u] = ok ? valid : 0u;
+            x[u] = j < j_hi ? valid : 0u;
             longest = max(longest, min(nl[u], a.lit_cap));
         }
-        for (int k = 0; k < longest; k += 4) {
+        const uint4 *E = reinterpret_cast<const uint4 *>(lits + B * (int64_t)(a.lit_cap / 4) * 32); // [round][slot] x 4 entries
+        for (int k = 0; k < longest; k += 4, E += 8) {
             uint32_t r[8][4];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
@@ -212,7 +239,7 @@ __global__ __launch_bounds__(64 * SP_WAVES) void k_eval_sparse(const uint32_t *_
                 // load.  (Buffer loads that take the row offset as their scalar offset need no add
                 // at all, but measured 45 % slower: the list entries then sit in scalar registers
                 // until their load is issued, and too few list loads stay in flight.)
-                const uint4 e = *reinterpret_cast<const uint4 *>(L[u] + k);
+                const uint4 e = E[u];
                 r[u][0] = *reinterpret_cast<const uint32_t *>(xb_base + (e.x + word_off));
                 r[u][1] = *reinterpret_cast<const uint32_t *>(xb_base + (e.y + word_off));
                 r[u][2] = *reinterpret_cast<const uint32_t *>(xb_base + (e.z + word_off));

@@ -42,13 +42,23 @@ def test_sizes_and_validation_are_host_only():
     # tallies + one bit per example per clause + transposed X + bit rows of X + literal lists
     # + gate lists + per-clause freshness ranges + launch order + counters/flag
     qw = ((60000 + 2047) // 2048) * 64
-    need = (10 * qp * 4 + C * qp // 8 + 25 * qp * 4 + 1569 * qw * 4 + C * 128 * 4 + C * 4 + 10 * qp * 4
+
+    def list_slots(q):
+        # the lists are laid out per (class, share, wavefront of 8) in batches of 8 clauses, 64 clauses of a
+        # share per round of batches: shares * 8 * ceil(clauses per share / 64) * 8 slots per class
+        S, chunk = B.tm_eval_shares(cfg, q)
+        return 10 * S * 8 * ((chunk + 63) // 64) * 8
+
+    slots = list_slots(60000)
+    assert C <= slots <= 1.25 * C
+    need = (10 * qp * 4 + C * qp // 8 + 25 * qp * 4 + 1569 * qw * 4 + slots * 128 * 4 + slots * 4 + 10 * qp * 4
             + C * 16 + C * 4)
     assert ws >= need
     assert ws < 1.01 * need + 8192
     # inference workspace: literal rows of the examples + literal lists + their lengths
     iw = B.tm_infer_ws_bytes(cfg, 10000)
-    need_i = 1569 * ((10000 + 2047) // 2048) * 64 * 4 + C * 128 * 4 + C * 4
+    slots = list_slots(10000)
+    need_i = 1569 * ((10000 + 2047) // 2048) * 64 * 4 + slots * 128 * 4 + slots * 4
     assert need_i <= iw < need_i + 1024
     assert B.tm_infer_ws_bytes(cfg, 0) >= C * 128 * 4
     bad = [dict(m=1), dict(n=3), dict(n=0), dict(o=0), dict(N=0), dict(N=129), dict(T=0), dict(s=0.5)]
