@@ -35,10 +35,19 @@ HBM_PEAK_GBS = 8000.0
 # three-input bitwise function each count as one.  Wave-uniform work (key schedule, loop
 # control) is not counted.
 PHILOX_OPS = 40           # 10 rounds x (2 multiplies + 2 three-input xors)
-TYPE1_OPS_PER_WORD = 4 * PHILOX_OPS + 16 + 8 + 32 + 6    # 4 blocks, 16-bit comparator, 2 saturation tests,
-                                                         # 2 ripples (2 ops per plane), event masks
 TYPE2_OPS_PER_WORD = 2 + 16                              # mask + one ripple
 GATE_OPS = PHILOX_OPS + 8                                # one block + clip, error, 64-bit compare
+
+
+def type1_ops_per_word(s):
+    """Type I feedback on one word of 32 literals: the Philox blocks whose bits can decide u < thr (the
+    comparator bits below the lowest set bit of thr = round(65536 / s) never do: 4 blocks for s = 10 or 5,
+    1 block for s = 2), 4 comparator operations per block, 2 saturation tests (4 three-input operations
+    each), one pass over the 8 planes that moves both directions (2 operations per plane), event masks."""
+    thr = int(min(65536.0, max(0.0, 65536.0 / s + 0.5)))
+    tz = (thr & -thr).bit_length() - 1 if thr else 16
+    blocks = 4 - min(tz >> 2, 4)
+    return blocks * (PHILOX_OPS + 4) + 8 + 16 + 6
 
 
 # HBM traffic per launch in the timed (steady) epochs of the default workload, from two separate
@@ -81,7 +90,7 @@ def measured_traffic(key):
     return 1024.0 * (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"]), src
 
 
-def train_kernel_ops(counters, W, lits, entries, nominal=False):
+def train_kernel_ops(counters, W, lits, entries, nominal=False, s=10.0):
     """Algorithmic lane-ops of a run of the training kernel from its event counters.
 
     nominal=False counts what the kernel's own algorithm needs on this run.  A block of 64
@@ -102,7 +111,7 @@ def train_kernel_ops(counters, W, lits, entries, nominal=False):
         ev = listed * 2 * (lits + 2) + (counters["blocks_evaluated"] - listed) * 64 * (1.5 * entries + 2)
         draws = counters["gate_draws"]
     return (ev + draws * GATE_OPS
-            + counters["type1"] * W * TYPE1_OPS_PER_WORD
+            + counters["type1"] * W * (type1_ops_per_word(10.0) if nominal else type1_ops_per_word(s))   # nominal: all 16 bits
             + counters["type2_active"] * W * TYPE2_OPS_PER_WORD)
 
 
@@ -266,7 +275,7 @@ def clause_sweep(hp, seed, Xd, yd, epochs=2):
         ms, cnt, kt = time_fit_epochs(tm, epochs)
         lits, entries = clause_sparsity(tm)
         train_ms, n_train = kt["train"]
-        ops = train_kernel_ops(cnt, 2 * tm.Wf, lits, entries)
+        ops = train_kernel_ops(cnt, 2 * tm.Wf, lits, entries, s=tm.s)
         points.append({"clauses_per_class": n, "clauses_total": tm.C, "T": h2["T"], "fit_epoch_ms": ms,
                        "examples_per_s": q / (ms * 1e-3),
                        "k_train_frac_alu": ops / (train_ms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
@@ -388,8 +397,8 @@ def main():
     launch_ms = train_ms / max(1, n_train)
     # sparsity of the final state: included literals and non-zero feature words per clause
     lits, entries = clause_sparsity(tm)
-    ops = train_kernel_ops(cnt, W, lits, entries) / max(1, n_train)
-    ops_nominal = train_kernel_ops(cnt, W, lits, entries, nominal=True) / max(1, n_train)
+    ops = train_kernel_ops(cnt, W, lits, entries, s=tm.s) / max(1, n_train)
+    ops_nominal = train_kernel_ops(cnt, W, lits, entries, nominal=True, s=tm.s) / max(1, n_train)
     achieved = ops / (launch_ms * 1e-3) / 1e12
     # algorithmic HBM bytes of one training launch: TA planes in + out and include masks out for
     # every clause, the launch's share of the examples (row-major for feedback, word-major and

@@ -147,6 +147,21 @@ __device__ __forceinline__ void ripple_inc(uint32_t (&p)[8], uint32_t m)
     }
 }
 
+// +1 on the automata selected by up and -1 on those selected by dn in one pass (up and dn disjoint, none
+// of the former at the top, none of the latter at the bottom).  d marks the automata whose carry or
+// borrow is still travelling: a carry goes on where the plane bit is 1, a borrow where it is 0, i.e.
+// where the bit equals the direction.  Two operations per plane for both directions together.
+__device__ __forceinline__ void ripple_updown(uint32_t (&p)[8], uint32_t up, uint32_t dn)
+{
+    uint32_t d = up | dn;
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        const uint32_t t = (uint32_t)__builtin_amdgcn_bitop3_b32(d, p[b], up, 0x90); // d & ~(p ^ up)
+        p[b] ^= d;
+        d = t;
+    }
+}
+
 // -1 on the automata selected by m (none of them at the bottom)
 __device__ __forceinline__ void ripple_dec(uint32_t (&p)[8], uint32_t m)
 {

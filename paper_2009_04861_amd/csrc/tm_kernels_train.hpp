@@ -608,13 +608,11 @@ __device__ __forceinline__ void train_clause(const uint32_t *__restrict__ X, con
                     uint32_t sp[8];
                     get_slot(p[r], sp);
                     const uint32_t old7 = sp[7];
-                    if (Cout) { // strong: literals that are 1 move towards Include with probability (s-1)/s (1 if boosted)
-                        const uint32_t m = lit & (ge | d.boost) & ~at_value<FULL>(sp, a.sat.kmax, true);
-                        ripple_inc(sp, m);
-                    }
+                    uint32_t up = 0u; // strong: literals that are 1 move towards Include with probability (s-1)/s (1 if boosted)
+                    if (Cout) up = lit & (ge | d.boost) & ~at_value<FULL>(sp, a.sat.kmax, true);
                     // weak: everything else moves towards Exclude with probability 1/s
                     const uint32_t wk = (Cout ? ~lit : ~0u) & ~ge & valid & ~at_value<FULL>(sp, a.sat.kmin, false);
-                    ripple_dec(sp, wk);
+                    ripple_updown(sp, up, wk); // the two sets are disjoint: one pass over the planes moves both
                     changed |= sp[7] ^ old7;
                     put_slot(p[r], sp);
                     // keep the slots apart in the instruction schedule: interleaving them

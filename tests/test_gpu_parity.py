@@ -195,6 +195,27 @@ def test_sync_pass_matches(shape, device):
     assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar)
 
 
+@pytest.mark.parametrize("ranges", [24, 27, 31])
+def test_sync_pass_with_many_ranges_of_examples(ranges, device):
+    """From 24 ranges of 2,048 examples on, the workgroups of the tally pre-calculation are dealt out to the
+    eight XCDs range by range (XCD x takes the ranges x, x + 8, ...; the grid is padded to whole rounds of
+    eight): every (range, class) must still be evaluated exactly once (24: no range left over after whole
+    rounds, 27: three, 31: seven; ragged tail of examples)."""
+    m, n, o, N, T, s = 3, 6, 37, 20, 4, 3.0
+    q = 2048 * ranges - 5
+    print("many ranges", ranges, flush=True)
+    rng = np.random.default_rng(ranges)
+    ora, gpu = make_pair(m, n, o, N, T, s, 7)
+    ora.state[:] = sparse_random_state(rng, ora.C, ora.L, N, 1.5 / o)
+    push_state(gpu, ora.state)
+    X, y = rand_problem(rng, q, o, m)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    assert np.array_equal(gpu.tallies().cpu().numpy(), tally)
+    assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar)
+    assert np.array_equal(gpu.class_sums(dev_bits(gpu, X)).cpu().numpy(), ora.class_sums(X))
+
+
 def run_frozen(ora, gpu, X, y, epoch, i0, cnt, tally, ostar):
     """One frozen-snapshot step on both sides from the same starting point."""
     snap = tally.copy()
