@@ -164,3 +164,56 @@ def test_wide_feature_workloads_sampled_clauses(name, q, n_small, device):
     assert np.array_equal(sums, gpu.class_sums(Xd, lists=False).cpu().numpy())
     assert np.array_equal(gpu.predict(Xd).cpu().numpy()[ex], ora.predict(Xs))
     gpu.close()
+
+
+def test_text_like_full_size_sampled_clauses(device):
+    """The text-like workload at its full size and in the launch configuration the benchmark times (25,000
+    documents x 10,000 features, 2 x 10,000 clauses: 10,000 workgroups per launch, 16 launches per pass).
+    The machine's state is synthetic (a tiled pattern: untrained-looking clauses next to trained-looking
+    ones), the oracle follows sampled clauses through the pre-calculation and a frozen-snapshot pass."""
+    hp = dict(synth.WORKLOADS["text_like"])
+    m, n, o, N = hp["m"], hp["n"], hp["o"], hp["N"]
+    C, L, q = m * n, 2 * o, 25000
+    Xtr, ytr, _, _ = synth.text_like(q, 8)
+    rng = np.random.default_rng(3)
+    print("text-like full size: state", flush=True)
+    pattern = rng.integers(1, N + 1, size=(40, L)).astype(np.int32)            # states 1..2N; excluded everywhere ...
+    pattern[:8] = rng.integers(1, 2 * N + 1, size=(8, L))                       # 8 untrained-looking rows
+    for r in range(8, 40):                                                      # 32 rows with ten negated literals
+        pattern[r, o + rng.integers(0, o, size=10)] = rng.integers(N + 1, 2 * N + 1, size=10)
+    gpu = B.TsetlinMachine(seed=6, **hp)
+    state_u8 = np.ascontiguousarray(np.tile((pattern - 1).astype(np.uint8), (C // 40, 1)))   # stored value = state - 1
+    gpu.set_ta_state(torch.from_numpy(state_u8).to(gpu.dev))
+    ids = np.array([3, 9, n - 1, n + 8, C - 2, C - 1], dtype=np.int32)          # both classes, both kinds, both polarities
+    ora = O.Oracle(seed=6, init=False, **hp)
+    ora.state[ids] = pattern[ids % 40]
+    del state_u8
+
+    print("text-like full size: bind", flush=True)
+    gpu.bind_train(dev_bits(gpu, Xtr), dev_i32(gpu, ytr))
+    assert B.tm_train_chunk(gpu.h) == 1664
+    ostar_sub = ora.clause_outputs_subset(Xtr, ids)
+    assert 0.05 < ostar_sub[1:].mean() < 0.999
+    sel = torch.from_numpy(ids).long().to(gpu.dev)
+    assert np.array_equal(bits_to_u8(gpu.prev_outputs()[sel], q), ostar_sub)
+
+    print("text-like full size: frozen pass", flush=True)
+    vhat = rng.integers(-hp["T"], hp["T"] + 1, size=(q, m)).astype(np.int32)    # synthetic snapshot
+    B.tm_set_epoch(gpu.h, 4)
+    gpu.counters()
+    gpu.feedback_step(dev_i32(gpu, vhat), 0, q)
+    fired = ora.feedback_step_subset(Xtr, ytr, vhat, ostar_sub, 4, 0, q, ids)
+    assert fired > 1000
+    st = gpu.get_ta_state()[sel].cpu().numpy().astype(np.int32) + 1
+    assert np.array_equal(st, ora.state[ids])
+    prev = gpu.prev_outputs()
+    assert np.array_equal(bits_to_u8(prev[sel], q), ostar_sub)
+    c = gpu.counters()
+    assert c["pairs"] == q * C                     # counted on the device: 16 launches x 20,000 wavefronts
+    # at any size: the tally is the signed sum of the stored outputs (checked on 4,000 examples)
+    tally = gpu.tallies().cpu().numpy()
+    sign = np.where(np.arange(n) % 2 == 1, 1, -1).astype(np.int32)
+    for cls in range(m):
+        bits = bits_to_u8(prev[cls * n:(cls + 1) * n, :125], 4000)
+        assert np.array_equal(tally[:4000, cls], sign @ bits.astype(np.int32))
+    gpu.close()
