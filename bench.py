@@ -400,13 +400,14 @@ def main():
     ops = train_kernel_ops(cnt, W, lits, entries, s=tm.s) / max(1, n_train)
     ops_nominal = train_kernel_ops(cnt, W, lits, entries, nominal=True, s=tm.s) / max(1, n_train)
     achieved = ops / (launch_ms * 1e-3) / 1e12
-    # algorithmic HBM bytes of one training launch: TA planes in + out and include masks out for
-    # every clause, the launch's share of the examples (row-major for feedback, word-major and
+    # algorithmic HBM bytes of one training launch: include masks in for every clause, TA planes in + out
+    # and include masks out for the clauses that got feedback, the launch's share of the examples (row-major for feedback, word-major and
     # literal rows for evaluation), tallies in + out, labels, and the previous-output bits of the
     # blocks that were evaluated, in + out
     chunk = B.tm_train_chunk(tm.h)
     share = min(1.0, chunk / q)
-    hbm_bytes = (2 * C * W * 32 + C * W * 4
+    moved = cnt["automata_moved"] / max(1, n_train)      # clauses per launch whose automata were fetched and written back
+    hbm_bytes = (C * W * 4 + moved * (2 * W * 32 + W * 4)
                  + share * (2 * q * tm.Wf * 4 + 2 * tm.o * q / 8 + tm.m * q * 4 * 2 + q * 8)
                  + 2 * 8 * cnt["blocks_evaluated"] / max(1, n_train))
     headline = (args.workload == "image_like" and args.clause_groups == 1
@@ -470,6 +471,7 @@ def main():
         "nominal_lane_ops_per_launch": ops_nominal,
         "nominal_frac": ops_nominal / (launch_ms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
         "hbm_algorithmic_bytes_per_launch": hbm_bytes,
+        "clauses_with_automata_moved_per_launch": moved,
         "hbm_achieved_GBs": hbm_bytes / (launch_ms * 1e-3) / 1e9,
         "hbm_frac": hbm_bytes / (launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "mean_literals_per_clause": lits,

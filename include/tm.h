@@ -243,7 +243,7 @@ int tm_set_epoch(tm_handle *h, uint32_t epoch);
 int tm_get_epoch(tm_handle *h, uint32_t *epoch);
 
 /* Device-side event counters of the training kernel since the last call of
- * this function (or since tm_bind_train): out is HOST uint64 [9]:
+ * this function (or since tm_bind_train): out is HOST uint64 [10]:
  * [0] visited (clause, example) pairs (every wavefront of the training kernel adds the
  * number of examples of its launch that it walked for its clause), [1] fired gates, [2] Type I feedbacks,
  * [3] tally changes, [4] pairs whose class was trained for the example (gate
@@ -254,7 +254,9 @@ int tm_get_epoch(tm_handle *h, uint32_t *epoch);
  * launch and at the visit (a random draw was needed),
  * [8] those of the blocks of [6] that were evaluated 32 at a time through the
  * clause's literal list (outdated blocks of a sparse clause in which no gate
- * fired) rather than one by one from its include masks.
+ * fired) rather than one by one from its include masks,
+ * [9] (clause, launch) pairs for which the clause's automata were fetched and written
+ * back (a clause that gets no feedback in a launch only reads its include masks).
  * Synchronises the stream. */
 int tm_read_counters(tm_handle *h, uint64_t *out, void *stream);
 

@@ -220,11 +220,11 @@ def tm_read_kernel_timing(h):
 
 
 def tm_read_counters(h):
-    out = (ctypes.c_uint64 * 9)()
+    out = (ctypes.c_uint64 * 10)()
     _check(lib().tm_read_counters(h, out, _stream()), "tm_read_counters")
     return {"pairs": out[0], "fired": out[1], "type1": out[2], "tally_changes": out[3],
             "candidates": out[4], "type2_active": out[5], "blocks_evaluated": out[6],
-            "gate_draws": out[7], "blocks_listed": out[8]}
+            "gate_draws": out[7], "blocks_listed": out[8], "automata_moved": out[9]}
 
 
 class TsetlinMachine:

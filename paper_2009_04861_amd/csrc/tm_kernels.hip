@@ -919,14 +919,15 @@ int tm_read_counters(tm_handle *h, uint64_t *out, void *stream)
     unsigned long long tmp[COUNTER_SETS * COUNTER_WIDTH];
     TM_HIP(h, hipMemcpyAsync(tmp, h->counters, sizeof(tmp), hipMemcpyDeviceToHost, st));
     TM_HIP(h, hipStreamSynchronize(st));
-    uint64_t sum[9];
-    for (int k = 0; k < 9; ++k) {
+    uint64_t sum[10];
+    for (int k = 0; k < 10; ++k) {
         sum[k] = 0;
         for (int c = 0; c < COUNTER_SETS; ++c) sum[k] += tmp[c * COUNTER_WIDTH + k];
     }
     for (int k = 1; k < 8; ++k) out[k] = sum[k];
     out[0] = sum[8]; // examples walked, summed over the wavefronts (clauses) that ran
     out[8] = sum[0]; // blocks evaluated through literal lists
+    out[9] = sum[9]; // (clause, launch) pairs whose automata were moved
     return fill(h, h->counters, (size_t)COUNTER_SETS * COUNTER_WIDTH * 8, 0u, st);
 }
 

@@ -651,10 +651,11 @@ __device__ __forceinline__ void train_clause(const uint32_t *__restrict__ X, con
     n_changes += n_changes_v;
     // event counters: 64 interleaved sets, because thousands of wavefronts ending at the
     // same time on one address serialise in the L2 atomic unit (measured: ~1.7 ms per launch)
-    if (lane < 9) { // slot 4 (trained pairs) is counted by the launch preparation; slot 8: examples this clause walked
+    if (lane < 10) { // slot 4 (trained pairs) is counted by the launch preparation; slot 8: examples this clause
+                     // walked; slot 9: 1 if its automata were fetched (and written back)
         const uint32_t v = lane == 0 ? n_listed_blocks : lane == 1 ? n_fired : lane == 2 ? n_type1 : lane == 3 ? n_changes
                          : lane == 4 ? 0u : lane == 5 ? n_type2 : lane == 6 ? n_eval : lane == 7 ? n_draw
-                         : (uint32_t)(i_end - i_begin);
+                         : lane == 8 ? (uint32_t)(i_end - i_begin) : ((!LAZY || have_planes) ? 1u : 0u);
         if (v) atomicAdd(&a.counters[(g & (COUNTER_SETS - 1)) * COUNTER_WIDTH + lane], (unsigned long long)v);
     }
 }
