@@ -371,13 +371,20 @@ void launch_train_t(const TrainPtrs &p, const TrainArgs &a, bool full, hipStream
 }
 
 // XB (rows of bits over the examples, and the all-ones row) of q examples given row-major.
+// Grid of the bit transposition: QW / 2 workgroups along the examples, and enough along the feature words
+// for a few thousand wavefronts when the examples are few.
+inline void xb_grid(const Dims &d, int64_t q, int64_t *nbx, int64_t *ny)
+{
+    *nbx = xb_row_words(q) / 2;
+    *ny = std::max<int64_t>(1, std::min<int64_t>((d.Wf + 3) / 4, (2048 + *nbx - 1) / *nbx));
+}
+
 int build_xb(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *XB, hipStream_t st)
 {
     const Dims &d = h->d;
     const int64_t QW = xb_row_words(q);
-    // enough workgroups for a few thousand wavefronts: the feature words are split when the examples are few
-    const int64_t wgs_x = QW / 2;
-    const int64_t split = std::max<int64_t>(1, std::min<int64_t>((d.Wf + 3) / 4, (2048 + wgs_x - 1) / wgs_x));
+    int64_t wgs_x, split;
+    xb_grid(d, q, &wgs_x, &split);
     hipLaunchKernelGGL(k_transpose_bits, dim3((unsigned)wgs_x, (unsigned)split), dim3(256), 0, st, X, XB, q, d.Wf, d.o,
                        (int)QW);
     TM_HIP(h, hipGetLastError());
@@ -389,7 +396,7 @@ int build_xb(tm_handle *h, const uint32_t *X, int64_t q, uint32_t *XB, hipStream
 // sums are clamped.  acc need not be zeroed by the caller.
 int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *lits, int32_t *nlit, uint32_t *bits,
                        int64_t bits_stride, int32_t *acc, int64_t acc_si, int64_t acc_sc, int clampT, int32_t *pred,
-                       int32_t *fresh, int timed_kind, hipStream_t st)
+                       int32_t *fresh, int timed_kind, hipStream_t st, const uint32_t *X_rows = nullptr)
 {
     const Dims &d = h->d;
     const int64_t QW = xb_row_words(q);
@@ -405,9 +412,19 @@ int launch_eval_sparse(tm_handle *h, const uint32_t *XB, int64_t q, uint32_t *li
     // partial sums of several workgroups are added up: they start from zero (either layout, [m][qp] or
     // [q][m]: up to the last element written), cleared by the kernel that builds the lists
     const int64_t zero_words = (acc && S > 1) ? (q - 1) * acc_si + (d.m - 1) * acc_sc + 1 : 0;
-    hipLaunchKernelGGL(k_literal_lists, dim3(blocks_for(list_slots(d.m, ll), 4)), dim3(256), 0, st, h->inc, lits, nlit,
-                       d.m, d.n, d.Wf, d.W, d.o, ll, (uint32_t)(QW * 4), fresh, (int)h->qp,
-                       reinterpret_cast<uint32_t *>(acc), zero_words);
+    ListArgs la;
+    la.inc = h->inc; la.lits = lits; la.nlit = nlit; la.m = d.m; la.n = d.n; la.Wf = d.Wf; la.W = d.W; la.o = d.o;
+    la.ll = ll; la.row_bytes = (uint32_t)(QW * 4); la.fresh = fresh; la.qp = (int)h->qp;
+    la.zero = reinterpret_cast<uint32_t *>(acc); la.zero_words = zero_words;
+    const unsigned list_blocks = blocks_for(list_slots(d.m, ll), 4);
+    if (X_rows) { // XB is still to be built from the row-major examples: same launch
+        int64_t nbx, ny;
+        xb_grid(d, q, &nbx, &ny);
+        hipLaunchKernelGGL(k_rows_and_lists, dim3((unsigned)(nbx * ny) + list_blocks), dim3(256), 0, st, X_rows,
+                           const_cast<uint32_t *>(XB), q, (int)QW, (int)nbx, (int)ny, la);
+    } else {
+        hipLaunchKernelGGL(k_literal_lists, dim3(list_blocks), dim3(256), 0, st, la);
+    }
     TM_HIP(h, hipGetLastError());
     int rc = timing_mark(h, timed_kind, true, st);
     if (rc) return rc;
@@ -739,9 +756,8 @@ static int infer_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, i
     uint32_t *XB = (uint32_t *)base;
     uint32_t *lits = (uint32_t *)(base + align256(xb_bytes(d, q)));
     int32_t *nlit = (int32_t *)(base + align256(xb_bytes(d, q)) + align256(lits_bytes(d, q)));
-    const int rc = build_xb(h, X, q, XB, st);
-    if (rc) return rc;
-    return launch_eval_sparse(h, XB, q, lits, nlit, nullptr, 0, sums, d.m, 1, d.T, pred, nullptr, timed_kind, st);
+    // the bit rows of the examples and the literal lists are built by one launch
+    return launch_eval_sparse(h, XB, q, lits, nlit, nullptr, 0, sums, d.m, 1, d.T, pred, nullptr, timed_kind, st, X);
 }
 
 int tm_class_sums_ws(tm_handle *h, const uint32_t *X, int64_t q, int32_t *sums, void *ws, void *stream)

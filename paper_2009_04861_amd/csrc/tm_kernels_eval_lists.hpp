@@ -28,15 +28,16 @@ constexpr int SP_PLANES = 8;   // bit planes of a wavefront's vote counter: at m
 // feature words (blockIdx.y), each wavefront a contiguous share of the workgroup's words; the 64 ballots of bit b of a word are two words
 // of row 32 fw + b, their complement two words of row o + 32 fw + b.  Examples from q up
 // to 32 QW read as feature 0 (no clause output is taken from them).  Row 2o is set to ones.
-__global__ __launch_bounds__(256) void k_transpose_bits(const uint32_t *__restrict__ X, uint32_t *__restrict__ XB,
-                                                        int64_t q, int Wf, int o, int QW)
+// (bx, by) = workgroup of a grid of (QW / 2) x ny
+__device__ __forceinline__ void transpose_bits_block(const uint32_t *__restrict__ X, uint32_t *__restrict__ XB,
+                                                     int64_t q, int Wf, int o, int QW, int bx, int by, int ny)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t i = (int64_t)blockIdx.x * 64 + lane;
-    if (threadIdx.x == 0 && blockIdx.y == 0) // these examples' two words of the all-ones row
-        *reinterpret_cast<uint2 *>(XB + (int64_t)2 * o * QW + (int64_t)blockIdx.x * 2) = make_uint2(~0u, ~0u);
-    const int per = (Wf + 4 * (int)gridDim.y - 1) / (4 * (int)gridDim.y);
-    const int share = (int)blockIdx.y * 4 + wave;
+    const int64_t i = (int64_t)bx * 64 + lane;
+    if (threadIdx.x == 0 && by == 0) // these examples' two words of the all-ones row
+        *reinterpret_cast<uint2 *>(XB + (int64_t)2 * o * QW + (int64_t)bx * 2) = make_uint2(~0u, ~0u);
+    const int per = (Wf + 4 * ny - 1) / (4 * ny);
+    const int share = by * 4 + wave;
     const int f_end = min(Wf, (share + 1) * per);
     for (int fw = share * per; fw < f_end; ++fw) {
         const uint32_t x = (i < q) ? X[i * Wf + fw] : 0u;
@@ -48,12 +49,18 @@ __global__ __launch_bounds__(256) void k_transpose_bits(const uint32_t *__restri
         }
         const int k = fw * 32 + lane;
         if (lane < 32 && k < o) {
-            *reinterpret_cast<uint2 *>(XB + (int64_t)k * QW + (int64_t)blockIdx.x * 2) =
+            *reinterpret_cast<uint2 *>(XB + (int64_t)k * QW + (int64_t)bx * 2) =
                 make_uint2((uint32_t)r, (uint32_t)(r >> 32));
-            *reinterpret_cast<uint2 *>(XB + (int64_t)(o + k) * QW + (int64_t)blockIdx.x * 2) =
+            *reinterpret_cast<uint2 *>(XB + (int64_t)(o + k) * QW + (int64_t)bx * 2) =
                 make_uint2(~(uint32_t)r, ~(uint32_t)(r >> 32));
         }
     }
+}
+
+__global__ __launch_bounds__(256) void k_transpose_bits(const uint32_t *__restrict__ X, uint32_t *__restrict__ XB,
+                                                        int64_t q, int Wf, int o, int QW)
+{
+    transpose_bits_block(X, XB, q, Wf, o, QW, (int)blockIdx.x, (int)blockIdx.y, (int)gridDim.y);
 }
 
 // Literal lists of the clauses, laid out for the wavefronts that walk them.  k_eval_sparse gives
@@ -76,19 +83,37 @@ struct ListLayout {
 
 __device__ __host__ inline int64_t list_slots(int m, const ListLayout &ll) { return (int64_t)m * ll.S * SP_WAVES * ll.nbatch * 8; }
 
-__global__ __launch_bounds__(256) void k_literal_lists(const uint32_t *__restrict__ inc, uint32_t *__restrict__ lits,
-                                                       int32_t *__restrict__ nlit, int m, int n, int Wf, int W, int o,
-                                                       ListLayout ll, uint32_t row_bytes, int32_t *fresh, int qp,
-                                                       uint32_t *zero, int64_t zero_words)
+struct ListArgs {
+    const uint32_t *inc;
+    uint32_t *lits;
+    int32_t *nlit;
+    int m, n, Wf, W, o;
+    ListLayout ll;
+    uint32_t row_bytes; // bytes per row of XB
+    int32_t *fresh;     // or null
+    int qp;
+    uint32_t *zero;     // partial sums to clear on the side
+    int64_t zero_words;
+};
+
+// block = workgroup index within the nblocks workgroups that build the lists
+__device__ __forceinline__ void literal_lists_block(const ListArgs &a, int64_t block, int64_t nblocks)
 {
+    const uint32_t *__restrict__ inc = a.inc;
+    uint32_t *__restrict__ lits = a.lits;
+    int32_t *__restrict__ nlit = a.nlit;
+    const int m = a.m, n = a.n, Wf = a.Wf, W = a.W, o = a.o, qp = a.qp;
+    const ListLayout ll = a.ll;
+    const uint32_t row_bytes = a.row_bytes;
+    int32_t *fresh = a.fresh;
     // on the side: clear the buffer in which the evaluation kernel will add up partial sums
-    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < zero_words; t += (int64_t)gridDim.x * 256) zero[t] = 0u;
+    for (int64_t t = block * 256 + threadIdx.x; t < a.zero_words; t += nblocks * 256) a.zero[t] = 0u;
     // ahead of a tally pre-calculation: every stored output of every clause will be current
     if (fresh)
-        for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < (int64_t)m * n; g += (int64_t)gridDim.x * 256)
+        for (int64_t g = block * 256 + threadIdx.x; g < (int64_t)m * n; g += nblocks * 256)
             *reinterpret_cast<int4 *>(fresh + g * 4) = make_int4(0, 0, qp, 0);
     const int lane = threadIdx.x & 63;
-    const int64_t slot = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t slot = block * 4 + (threadIdx.x >> 6);
     if (slot >= list_slots(m, ll)) return;
     const int u = (int)(slot & 7);
     const int64_t B = slot >> 3;
@@ -124,6 +149,23 @@ __global__ __launch_bounds__(256) void k_literal_lists(const uint32_t *__restric
     }
     for (int t = min(base, cap) + lane; t < cap; t += 64) L[(t >> 2) * 32 + (t & 3)] = 2u * (uint32_t)o * row_bytes;
     if (lane == 0) nlit[slot] = base;
+}
+
+__global__ __launch_bounds__(256) void k_literal_lists(const ListArgs a)
+{
+    literal_lists_block(a, (int64_t)blockIdx.x, (int64_t)gridDim.x);
+}
+
+// Both preparations of an inference call in one launch (they are independent of each other): the first
+// nbx * ny workgroups turn the examples into bit rows, the rest build the literal lists.
+__global__ __launch_bounds__(256) void k_rows_and_lists(const uint32_t *__restrict__ X, uint32_t *__restrict__ XB, int64_t q,
+                                                        int QW, int nbx, int ny, const ListArgs a)
+{
+    const int64_t nt = (int64_t)nbx * ny;
+    if ((int64_t)blockIdx.x < nt)
+        transpose_bits_block(X, XB, q, a.Wf, a.o, QW, (int)(blockIdx.x % nbx), (int)(blockIdx.x / nbx), ny);
+    else
+        literal_lists_block(a, (int64_t)blockIdx.x - nt, (int64_t)gridDim.x - nt);
 }
 
 struct SparseArgs {
