@@ -51,18 +51,18 @@ def type1_ops_per_word(s):
 
 
 # HBM traffic per launch in the timed (steady) epochs of the default workload, from two separate
-# `rocprofv3 --pmc` runs of this program (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch, averaged
-# over the timed launches).  The scale factors come from the same counters read for a plain
+# `rocprofv3 --pmc` runs of this program with --steps 20 --warmup 5 (FETCH_SIZE, then WRITE_SIZE, KiB per
+# dispatch, averaged over the 20 timed launches).  The scale factors come from the same counters read for a plain
 # 1 GiB device copy in the same runs (--calibration-copy): FETCH_SIZE reads 524,309 KiB for
 # 1,048,576 KiB fetched, WRITE_SIZE reads 1,048,576 KiB for 1,048,576 KiB written.  The figures
 # belong to the kernel sources whose digest is recorded with them (kernel_sources_digest() at the
 # time of the profile runs); with other sources `traffic` is reported as null.
 MEASURED_TRAFFIC = {
     "profile": "profiles/image_like_default_benchmark.txt",
-    "kernel_sources_sha256": "",
-    "image_like_train": {"fetch_kib": 149544.0, "fetch_scale": 2.0, "write_kib": 95014.0, "write_scale": 1.0},
+    "kernel_sources_sha256": "becc7b494d364bb598ffbd124b0d07f444391cb5f3dbb807a8fff7d995b9aae6",
+    "image_like_train": {"fetch_kib": 51215.0, "fetch_scale": 2.0, "write_kib": 36352.0, "write_scale": 1.0},
     # k_eval_sparse in tm_sync_tallies
-    "image_like_precalc": {"fetch_kib": 56142.0, "fetch_scale": 2.0, "write_kib": 165313.0, "write_scale": 1.0},
+    "image_like_precalc": {"fetch_kib": 59278.0, "fetch_scale": 2.0, "write_kib": 165312.0, "write_scale": 1.0},
 }
 
 
