@@ -218,9 +218,10 @@ int tm_get_prev_outputs(tm_handle *h, uint32_t *bits, void *stream);
 int tm_feedback_step(tm_handle *h, const int32_t *tally_snapshot, int64_t i0, int64_t cnt,
                      void *stream);
 
-/* tm_fit_epoch cuts the pass into consecutive ranges of this many examples, one
- * launch of the training kernel each, so that a range's slice of the
- * transposed features stays resident in L2 (measurement aid). */
+/* tm_fit_epoch cuts the pass of Algorithm 1 over the bound examples into consecutive
+ * ranges of this many examples, one launch of the training kernel each, so that a
+ * range's slice of the transposed features stays resident in L2 (measurement aid;
+ * the cut is also where Section 3.1's recorded tallies are re-read for the gate lists). */
 int tm_train_chunk(tm_handle *h, int64_t *examples_per_launch);
 
 /* Schedule knob: every launch of the training kernel is split into `groups`
@@ -232,13 +233,16 @@ int tm_train_chunk(tm_handle *h, int64_t *examples_per_launch);
  * (tm_feedback_step) do not depend on it. */
 int tm_set_clause_groups(tm_handle *h, int32_t groups);
 
-/* How the literal-list evaluation splits the n clauses of a class for q examples: into
+/* How the literal-list evaluation of Eq. 1 / Eq. 3 (tm_class_sums_ws, tm_predict_ws, the tally
+ * pre-calculation of Section 3.1) splits the n clauses of a class for q examples: into
  * `shares` workgroups of `clauses_per_share` clauses each (host-only; measurement and test
  * aid).  A wavefront counts the votes of an eighth of a share in 8 bit planes, so
  * clauses_per_share <= 2032 always. */
 int tm_eval_shares(const tm_config *cfg, int64_t q, int32_t *shares, int32_t *clauses_per_share);
 
-/* Epoch counter used for the random counter of the next tm_fit_epoch. */
+/* Epoch counter: part of the counter of the random generator behind Algorithm 1's rand()
+ * (gate, Type I, negative class), used by the next tm_fit_epoch / tm_fit_batch /
+ * tm_feedback_step; tm_fit_epoch advances it by one. */
 int tm_set_epoch(tm_handle *h, uint32_t epoch);
 int tm_get_epoch(tm_handle *h, uint32_t *epoch);
 

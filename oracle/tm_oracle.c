@@ -48,6 +48,19 @@
  * Everything else (clause evaluation, Type I / II tables, tally refresh, random
  * streams) is shared with classification.
  *
+ * What pins this file (tests that run without a GPU): the worked examples, Table 1 and
+ * Table 2 of the paper cell by cell, brute force on sets for Eq. 1 - Eq. 3, exact end points
+ * and frequencies of the gate, the training loops (synchronous, Algorithm 1 in both loop
+ * orders, in batches, under a frozen snapshot) against a restatement in pure Python on sets,
+ * the gate / negative-class / initial-state draws against raw Philox words, Philox itself
+ * against an independent engine.
+ * PARITY UNPINNED against the paper, because it prints nothing to pin them to: the
+ * regression rule (otm_gate_regression and role 3 of the loops: taken from the cited
+ * publication and pinned only against that rule's own closed forms); the choice of one
+ * negative class per example (otm_neg_class), of the initial states (otm_init), of the output
+ * of an empty clause, and of refreshing every visited pair (visit); and the accuracy any
+ * of the training loops reaches (only compared with each other).
+ *
  * Randomness: Philox4x32-10 (Salmon et al., SC'11), key = seed, counter
  *   ( blk | stream<<28 , g , i mod 2^32 , epoch | (i>>32)<<24 ).
  * Streams: 0 initial states, 1 gate, 2 Type I, 3 negative class.
