@@ -193,13 +193,22 @@ __device__ __forceinline__ uint32_t clause_from_masks(const uint32_t *__restrict
 {
     uint32_t accv = valid;
     const uint32_t row_bytes = (uint32_t)a.QW * 4u;
+    const uint32_t ones_row = 2u * (uint32_t)a.o * row_bytes;
     for (int lw = 0; lw < a.W; ++lw) {
         uint32_t m = inc[(int64_t)g * a.W + lw];
         const uint32_t k0 = lw >= a.Wf ? (uint32_t)a.o + (uint32_t)(lw - a.Wf) * 32u : (uint32_t)lw * 32u;
-        while (m) {
-            const int b = __builtin_ctz(m);
-            m &= m - 1u;
-            accv &= *reinterpret_cast<const uint32_t *>(xb_lane + (k0 + (uint32_t)b) * row_bytes);
+        while (m) { // four literals of the word per step: four independent loads (the all-ones row where the word runs out)
+            uint32_t off[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                off[t] = m ? (k0 + (uint32_t)__builtin_ctz(m)) * row_bytes : ones_row;
+                m &= m - 1u; // stays 0 once it is 0
+            }
+            const uint32_t x0 = *reinterpret_cast<const uint32_t *>(xb_lane + off[0]);
+            const uint32_t x1 = *reinterpret_cast<const uint32_t *>(xb_lane + off[1]);
+            const uint32_t x2 = *reinterpret_cast<const uint32_t *>(xb_lane + off[2]);
+            const uint32_t x3 = *reinterpret_cast<const uint32_t *>(xb_lane + off[3]);
+            accv &= x0 & x1 & x2 & x3;
         }
         if (ballot(accv != 0u) == 0) return 0u;
     }
