@@ -29,6 +29,8 @@ if ROOT not in sys.path:
 # 32-bit integer lane-operation per lane per clock
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 HBM_PEAK_GBS = 8000.0
+# vector L1 of a CU: 64 bytes per clock
+L1_PEAK_TBS = 256 * 64 * 2.4e9 / 1e12
 
 # Algorithmic 32-bit lane-operations of the training kernel, per unit of work.  An operation is
 # one 32-bit integer instruction on one lane as gfx950 has them: a 32x32->64 multiply and a
@@ -480,8 +482,11 @@ def main():
     # Literal-list evaluation kernel in the tally pre-calculation.  Algorithmic HBM bytes: every
     # literal row once, the literal lists, previous-output bits and tallies out.  Algorithmic
     # lane-ops: per clause and word of 32 examples one AND per literal and about 3 for the vote
-    # count.  Neither is what binds it: the kernel runs at the rate at which a CU can issue
-    # 4-byte-per-lane loads (about 9.5 clocks each), `l1_bytes_per_launch` is what passes through.
+    # count.  Neither is what binds it: every (clause, literal, 32 examples) is one 4-byte word that
+    # passes through a CU's vector L1 (`l1_bytes_per_launch`, lists padded to whole rounds of four),
+    # and that cache delivers 64 bytes per clock and CU: `l1_frac` is the fraction of that rate
+    # (256 CUs x 64 B x 2.4 GHz = 39.3 TB/s).  Eight-byte loads per lane were measured at half the
+    # bytes per clock of four-byte ones, so the width of the loads is not a way round it.
     pre_ms, n_pre = kt["precalc"]
     pre_launch_ms = pre_ms / max(1, n_pre)
     words = (q + 31) // 32
@@ -510,6 +515,8 @@ def main():
         "nominal_lane_ops_per_launch": float(q) * C * W,
         "nominal_alu_frac": float(q) * C * W / (pre_launch_ms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
         "l1_bytes_per_launch": C * words * (4 * ((lits + 3) // 4)) * 4,
+        "l1_peak_TBs": L1_PEAK_TBS,
+        "l1_frac": C * words * (4 * ((lits + 3) // 4)) * 4 / (pre_launch_ms * 1e-3) / 1e12 / L1_PEAK_TBS,
         "clause_evals_per_s": q * C / (pre_launch_ms * 1e-3),
     }
     inf_ms, n_inf = kt["infer"]

@@ -19,6 +19,12 @@ namespace tsetlin {
 // example in the lane = clause kernels above.  This is the GPU counterpart of indexing
 // clauses by their literals.  An untrained clause includes about half of all literals,
 // but then some literal is false on every example after a few loads and the loop stops.
+// What bounds the kernel is the cache path: every (clause, literal, word of 32 examples) is four
+// bytes through the CU's vector L1, which delivers 64 bytes per clock (measured: 0.7 of that rate
+// on trained image-like clauses, with 3 of 10 accesses going on to the L2).  Two words per lane
+// (8-byte loads, 512 contiguous bytes per wavefront) ran at half the bytes per clock of 4-byte
+// loads, with all 32 loads of a round in flight as well as with the registers re-used early: the
+// load width is no way round it.
 
 constexpr int LIT_CAP_MIN = 128, LIT_CAP_MAX = 1024; // bounds of the list capacity (entries per clause)
 constexpr int SP_WAVES = 8;    // wavefronts per workgroup of k_eval_sparse
