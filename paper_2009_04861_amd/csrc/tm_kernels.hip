@@ -352,7 +352,7 @@ struct TrainPtrs {
     const int32_t *gate, *ngate;
 };
 
-template <int WPL>
+template <int WPL, bool NARROW = false>
 void launch_train_t(const TrainPtrs &p, const TrainArgs &a, bool full, hipStream_t st)
 {
     // Clauses (wavefronts) per workgroup; the wavefronts of a workgroup do not interact.  Two are best once
@@ -364,10 +364,10 @@ void launch_train_t(const TrainPtrs &p, const TrainArgs &a, bool full, hipStream
     const size_t lds = (size_t)a.lds_wave_words * tw * 4;
     const dim3 grid((unsigned)((a.slot_hi - a.slot_lo + tw - 1) / tw)), block(64 * tw);
     const bool regr = a.y_regr != nullptr;
-    if (full && !regr) hipLaunchKernelGGL((k_train<WPL, true, false>), grid, block, lds, st, p.X, p.XT, p.XB, p.gate, p.ngate, a);
-    else if (!regr) hipLaunchKernelGGL((k_train<WPL, false, false>), grid, block, lds, st, p.X, p.XT, p.XB, p.gate, p.ngate, a);
-    else if (full) hipLaunchKernelGGL((k_train<WPL, true, true>), grid, block, lds, st, p.X, p.XT, p.XB, p.gate, p.ngate, a);
-    else hipLaunchKernelGGL((k_train<WPL, false, true>), grid, block, lds, st, p.X, p.XT, p.XB, p.gate, p.ngate, a);
+    if (full && !regr) hipLaunchKernelGGL((k_train<WPL, true, false, NARROW>), grid, block, lds, st, p.X, p.XT, p.XB, p.gate, p.ngate, a);
+    else if (!regr) hipLaunchKernelGGL((k_train<WPL, false, false, NARROW>), grid, block, lds, st, p.X, p.XT, p.XB, p.gate, p.ngate, a);
+    else if (full) hipLaunchKernelGGL((k_train<WPL, true, true, NARROW>), grid, block, lds, st, p.X, p.XT, p.XB, p.gate, p.ngate, a);
+    else hipLaunchKernelGGL((k_train<WPL, false, true, NARROW>), grid, block, lds, st, p.X, p.XT, p.XB, p.gate, p.ngate, a);
 }
 
 // XB (rows of bits over the examples, and the all-ones row) of q examples given row-major.
@@ -502,7 +502,11 @@ int launch_train(tm_handle *h, const int32_t *vhat, int64_t i_begin, int64_t i_e
         TM_HIP(h, hipGetLastError());
         int rc = timing_mark(h, TIMED_TRAIN, true, st);
         if (rc) return rc;
-        if (wpl <= 1) launch_train_t<1>(p, a, full, st);
+        // at most 16 literal words and a Type I comparison that needs several Philox blocks (the lowest set bit
+        // of the threshold lies below bit 12): the blocks are drawn side by side in the idle lanes
+        const bool narrow = d.W <= 16 && d.thr != 0 && __builtin_ctz(d.thr) < 12;
+        if (wpl <= 1 && narrow) launch_train_t<1, true>(p, a, full, st);
+        else if (wpl <= 1) launch_train_t<1>(p, a, full, st);
         else if (wpl <= 2) launch_train_t<2>(p, a, full, st);
         else if (wpl <= 3) launch_train_t<3>(p, a, full, st);
         else if (wpl <= 4) launch_train_t<4>(p, a, full, st);

@@ -170,7 +170,7 @@ constexpr int TRAIN_WAVES_MAX = 4; // most clauses (wavefronts) per workgroup of
 // LAZY: the automata (all planes but the include masks) are fetched only when the first feedback
 // is due and written back only if there was one; otherwise they are loaded up front.  The kernel
 // holds both versions of the loop and picks per clause (see k_train).
-template <int WPL, bool FULL, bool REGR, bool LAZY>
+template <int WPL, bool FULL, bool REGR, bool LAZY, bool NARROW>
 __device__ __forceinline__ void train_clause(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
                                              const uint32_t *__restrict__ XB, const int32_t *__restrict__ gate,
                                              const int k_hi, const TrainArgs &a, uint32_t *lds, const int g,
@@ -227,6 +227,13 @@ __device__ __forceinline__ void train_clause(const uint32_t *__restrict__ X, con
     const int tz = d.thr ? __builtin_ctz(d.thr) : 16;
     const int first_blk = min(tz >> 2, 4);
     const uint32_t ge_init = d.thr >= 65536u ? 0u : ~0u;
+    // NARROW (chosen by the host for clauses of at most 16 literal words whose comparison needs more
+    // than one Philox block): such clauses leave three quarters of the lanes idle while the 16 word lanes
+    // draw up to four blocks each, one after the other, and an epoch of so small a machine costs the
+    // latency of its feedback events and nothing else.  Here lane 16 t + w draws block t of word w (one
+    // Philox call for all of them) and the word lanes collect the four partial comparisons.  A version of
+    // its own because the extra registers would cost the general one-slot kernel a wavefront per SIMD.
+    const uint32_t thr_nibble_n = NARROW ? ~(d.thr >> (4 * (lane >> 4))) : 0u; // complement of the four thr bits of this lane's block
 
     // per-wavefront event counts of one launch fit 32 bits (at most 2^30 examples per launch)
     uint32_t n_fired = 0, n_type1 = 0, n_changes = 0, n_type2 = 0, n_eval = 0, n_draw = 0, n_listed_blocks = 0;
@@ -583,23 +590,46 @@ __device__ __forceinline__ void train_clause(const uint32_t *__restrict__ X, con
                     RngKey key = d.key;
                     uint32_t thr = d.thr;
                     if (WPL <= 2) asm volatile("" : "+s"(key.seed_lo), "+s"(key.seed_hi), "+s"(thr));
+                    if constexpr (NARROW) {
+                        // Over the four planes of one block the comparison is "the value that went in if
+                        // the four bits equal those of thr, else decided": two runs of the chain, from 0
+                        // and from 1, give what is decided (d0) and where the input passes (d0 ^ d1).
+                        const U4 R = draw(key, STREAM_TYPE1, 4u * (uint32_t)(lane & 15) + (uint32_t)(lane >> 4), (uint32_t)g,
+                                          (uint64_t)(uint32_t)ii, a.epoch);
+                        const uint32_t w[4] = {R.x, R.y, R.z, R.w};
+                        uint32_t d0 = 0u, d1 = ~0u;
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        if (t >= first_blk) {
-                            // With one or two slots, key and threshold are laundered as well (above):
-                            // their derived constants (20 round keys, 16 comparator masks) are then
-                            // computed by scalar instructions per slot instead of being kept for the
-                            // whole kernel - kept, they overflow the scalar registers and come back
-                            // through readlane, a vector instruction each, in the loop that is bound by
-                            // vector issue (-5 % per epoch of an untrained machine).  With many slots the
-                            // scalar work per slot costs more than the spills (measured +8 .. +20 %).
-                            const U4 R = draw(key, STREAM_TYPE1, 4u * lw + (uint32_t)t, (uint32_t)g,
-                                              (uint64_t)(uint32_t)ii, a.epoch);
-                            const uint32_t w[4] = {R.x, R.y, R.z, R.w};
+                        for (int k = 0; k < 4; ++k) {
+                            const uint32_t K = (uint32_t)__builtin_amdgcn_sbfe((int)thr_nibble_n, k, 1); // thr bit 1: 0, 0: ~0
+                            d0 = majority3(w[k], d0, K);
+                            d1 = majority3(w[k], d1, K);
+                        }
+                        const uint32_t pass = d0 ^ d1;
 #pragma unroll
-                            for (int k = 0; k < 4; ++k) {
-                                const uint32_t K = ((thr >> (4 * t + k)) & 1u) ? 0u : ~0u;
-                                ge = majority3(w[k], ge, K);
+                        for (int t = 0; t < 4; ++t) { // least significant block first; lanes 16.. compute nothing that is used
+                            const int src = (lane & 15) + 16 * t;
+                            const uint32_t dt = (uint32_t)__shfl((int)d0, src, 64), pt = (uint32_t)__shfl((int)pass, src, 64);
+                            ge = dt | (pt & ge);
+                        }
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            if (t >= first_blk) {
+                                // With one or two slots, key and threshold are laundered as well (above):
+                                // their derived constants (20 round keys, 16 comparator masks) are then
+                                // computed by scalar instructions per slot instead of being kept for the
+                                // whole kernel - kept, they overflow the scalar registers and come back
+                                // through readlane, a vector instruction each, in the loop that is bound by
+                                // vector issue (-5 % per epoch of an untrained machine).  With many slots the
+                                // scalar work per slot costs more than the spills (measured +8 .. +20 %).
+                                const U4 R = draw(key, STREAM_TYPE1, 4u * lw + (uint32_t)t, (uint32_t)g,
+                                                  (uint64_t)(uint32_t)ii, a.epoch);
+                                const uint32_t w[4] = {R.x, R.y, R.z, R.w};
+#pragma unroll
+                                for (int k = 0; k < 4; ++k) {
+                                    const uint32_t K = ((thr >> (4 * t + k)) & 1u) ? 0u : ~0u;
+                                    ge = majority3(w[k], ge, K);
+                                }
                             }
                         }
                     }
@@ -666,7 +696,7 @@ __device__ __forceinline__ void train_clause(const uint32_t *__restrict__ X, con
 // clauses get none, and the lazy version saves moving their automata (16 % of a quiet epoch).
 constexpr int TRAIN_EAGER_CANDIDATES = 256;
 
-template <int WPL, bool FULL, bool REGR>
+template <int WPL, bool FULL, bool REGR, bool NARROW = false>
 __global__ __launch_bounds__(64 * TRAIN_WAVES_MAX) void k_train(const uint32_t *__restrict__ X, const uint32_t *__restrict__ XT,
                                                             const uint32_t *__restrict__ XB,
                                                             const int32_t *__restrict__ gate,
@@ -681,8 +711,8 @@ __global__ __launch_bounds__(64 * TRAIN_WAVES_MAX) void k_train(const uint32_t *
     const int k_hi = __builtin_amdgcn_readfirstlane(ngate[g / a.d.n]);
     // wide clauses keep to the one version: the lazy one holds the addresses of all their register slots
     // alive through the loop (36 more registers with 10 slots: one wavefront per SIMD instead of two)
-    if (WPL > 4 || k_hi >= TRAIN_EAGER_CANDIDATES) train_clause<WPL, FULL, REGR, false>(X, XT, XB, gate, k_hi, a, lds, g, lane, wave);
-    else train_clause<WPL, FULL, REGR, WPL <= 4>(X, XT, XB, gate, k_hi, a, lds, g, lane, wave);
+    if (WPL > 4 || k_hi >= TRAIN_EAGER_CANDIDATES) train_clause<WPL, FULL, REGR, false, NARROW>(X, XT, XB, gate, k_hi, a, lds, g, lane, wave);
+    else train_clause<WPL, FULL, REGR, WPL <= 4, NARROW>(X, XT, XB, gate, k_hi, a, lds, g, lane, wave);
 }
 
 } // namespace tsetlin

@@ -24,6 +24,7 @@ SHAPES = [
     (2, 4, 2500, 128, 3, 10.0),     # 158 literal words -> 3 slots, 3 mask chunks in evaluation
     (2, 4, 10000, 128, 20, 2.0),    # text-like feature count: 626 literal words -> 10 slots
     (2, 2, 20000, 128, 10, 5.0),    # stress feature count: 1250 literal words -> 20 slots
+    (2, 6, 250, 50, 8, 10.0),       # 16 literal words, ragged tail: the widest clause whose Type I blocks are drawn side by side
 ]
 
 
