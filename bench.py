@@ -61,10 +61,10 @@ def type1_ops_per_word(s):
 # time of the profile runs); with other sources `traffic` is reported as null.
 MEASURED_TRAFFIC = {
     "profile": "profiles/image_like_default_benchmark.txt",
-    "kernel_sources_sha256": "becc7b494d364bb598ffbd124b0d07f444391cb5f3dbb807a8fff7d995b9aae6",
-    "image_like_train": {"fetch_kib": 51215.0, "fetch_scale": 2.0, "write_kib": 36352.0, "write_scale": 1.0},
+    "kernel_sources_sha256": "7108b094e49bc33ba5d4d676eb46508e42dfb56ae6e1b42f8c44a9c5986d08d2",
+    "image_like_train": {"fetch_kib": 48688.8, "fetch_scale": 2.0, "write_kib": 35457.0, "write_scale": 1.0},
     # k_eval_sparse in tm_sync_tallies
-    "image_like_precalc": {"fetch_kib": 59278.0, "fetch_scale": 2.0, "write_kib": 165312.0, "write_scale": 1.0},
+    "image_like_precalc": {"fetch_kib": 58987.1, "fetch_scale": 2.0, "write_kib": 165312.5, "write_scale": 1.0},
 }
 
 
