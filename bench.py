@@ -61,10 +61,10 @@ def type1_ops_per_word(s):
 # time of the profile runs); with other sources `traffic` is reported as null.
 MEASURED_TRAFFIC = {
     "profile": "profiles/image_like_default_benchmark.txt",
-    "kernel_sources_sha256": "7108b094e49bc33ba5d4d676eb46508e42dfb56ae6e1b42f8c44a9c5986d08d2",
-    "image_like_train": {"fetch_kib": 48688.8, "fetch_scale": 2.0, "write_kib": 35457.0, "write_scale": 1.0},
+    "kernel_sources_sha256": "afa39eda67cb19317671b3f76f0a61a749ab3cbd14b934bb30e78f54ec0d82bf",
+    "image_like_train": {"fetch_kib": 49186.0, "fetch_scale": 2.0, "write_kib": 33430.1, "write_scale": 1.0},
     # k_eval_sparse in tm_sync_tallies
-    "image_like_precalc": {"fetch_kib": 58987.1, "fetch_scale": 2.0, "write_kib": 165312.5, "write_scale": 1.0},
+    "image_like_precalc": {"fetch_kib": 59079.0, "fetch_scale": 2.0, "write_kib": 165312.5, "write_scale": 1.0},
 }
 
 
@@ -369,38 +369,66 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
+    # Events between kernels cost the stream about 5 us each, so the timed region carries only the two
+    # that bracket the launches of the kernel with the larger share (found on the last warm-up step; both
+    # main kernels with fewer than two warm-up steps).  Everything else - time per call, the other kernels - comes from a
+    # second pass of the same number of steps, with events around every call and every main kernel.
+    live = None
+    for k in range(args.warmup):
+        if k == args.warmup - 1:
+            B.tm_kernel_timing(tm.h, True)
         step()
     torch.cuda.synchronize()
+    if args.warmup:
+        kw = B.tm_read_kernel_timing(tm.h)
+        if args.warmup >= 2:   # the first epoch (an untrained machine) says nothing about the later ones
+            live = "train" if kw["train"][0] >= kw["precalc"][0] else "precalc"
     tm.counters()  # reset the device counters
-    B.tm_kernel_timing(tm.h, True)
+    B.tm_kernel_timing(tm.h, {None: B.TIMED_TRAIN | B.TIMED_PRECALC, "train": B.TIMED_TRAIN,
+                              "precalc": B.TIMED_PRECALC}[live])
 
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall = t1 - t0
+    cnt_live = tm.counters()
+    kt_live = B.tm_read_kernel_timing(tm.h)   # events around every launch of the kernel(s) timed live
+    if hp.get("regression"):   # mean absolute error as a fraction of the target range instead of accuracy
+        acc = float(np.abs(pred.cpu().numpy() - yte).mean() / tm.T)
+    else:
+        acc = float((pred.cpu().numpy() == yte).mean())
+
+    # second pass: the same steps again with events around every call and every main kernel
+    B.tm_kernel_timing(tm.h, True)
     evs = [[ev() for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
         step(evs[k])
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    wall = t1 - t0
-    cnt = tm.counters()
-    if hp.get("regression"):   # mean absolute error as a fraction of the target range instead of accuracy
-        acc = float(np.abs(pred.cpu().numpy() - yte).mean() / tm.T)
-    else:
-        acc = float((pred.cpu().numpy() == yte).mean())
-
+    wall_second = time.perf_counter() - t0
+    cnt_second = tm.counters()
+    kt_second = B.tm_read_kernel_timing(tm.h)
+    B.tm_kernel_timing(tm.h, False)
     fit_ms = [e[0].elapsed_time(e[1]) for e in evs]
     sync_ms = [e[1].elapsed_time(e[2]) for e in evs]
     pred_ms = [e[2].elapsed_time(e[3]) for e in evs]
     fit_avg = float(np.mean(fit_ms))
-    kt = B.tm_read_kernel_timing(tm.h)   # events around every launch of the two main kernels
-    B.tm_kernel_timing(tm.h, False)
+    train_live = live in (None, "train")
+    pre_live = live in (None, "precalc")
+    kt = {"train": (kt_live if train_live else kt_second)["train"],
+          "precalc": (kt_live if pre_live else kt_second)["precalc"], "infer": kt_second["infer"]}
+    cnt = cnt_live                                  # the counters of the timed region describe the regime
+    cnt_train = cnt_live if train_live else cnt_second   # those of the pass in which k_train was timed count its work
     train_ms, n_train = kt["train"]
     launch_ms = train_ms / max(1, n_train)
     # sparsity of the final state: included literals and non-zero feature words per clause
     lits, entries = clause_sparsity(tm)
-    ops = train_kernel_ops(cnt, W, lits, entries, s=tm.s) / max(1, n_train)
-    ops_nominal = train_kernel_ops(cnt, W, lits, entries, nominal=True, s=tm.s) / max(1, n_train)
+    ops = train_kernel_ops(cnt_train, W, lits, entries, s=tm.s) / max(1, n_train)
+    ops_nominal = train_kernel_ops(cnt_train, W, lits, entries, nominal=True, s=tm.s) / max(1, n_train)
     achieved = ops / (launch_ms * 1e-3) / 1e12
     # algorithmic HBM bytes of one training launch: include masks in for every clause, TA planes in + out
     # and include masks out for the clauses that got feedback, the launch's share of the examples (row-major for feedback, word-major and
@@ -408,10 +436,10 @@ def main():
     # blocks that were evaluated, in + out
     chunk = B.tm_train_chunk(tm.h)
     share = min(1.0, chunk / q)
-    moved = cnt["automata_moved"] / max(1, n_train)      # clauses per launch whose automata were fetched and written back
+    moved = cnt_train["automata_moved"] / max(1, n_train)      # clauses per launch whose automata were fetched and written back
     hbm_bytes = (C * W * 4 + moved * (2 * W * 32 + W * 4)
                  + share * (2 * q * tm.Wf * 4 + 2 * tm.o * q / 8 + tm.m * q * 4 * 2 + q * 8)
-                 + 2 * 8 * cnt["blocks_evaluated"] / max(1, n_train))
+                 + 2 * 8 * cnt_train["blocks_evaluated"] / max(1, n_train))
     headline = (args.workload == "image_like" and args.clause_groups == 1
                 and not (args.small or args.clauses_per_class or args.q_train))
     traffic, traffic_src = (measured_traffic("image_like_train") if headline
@@ -435,6 +463,12 @@ def main():
             "m": tm.m, "n": tm.n, "o": tm.o, "N": tm.N, "T": tm.T, "s": tm.s, "q_train": q, "q_test": qt,
             "clauses_total": C, "pairs_per_epoch": q * C,
             "fit_epoch_ms": fit_avg, "sync_tallies_ms": float(np.mean(sync_ms)), "predict_ms": float(np.mean(pred_ms)),
+            "per_call_ms_from": "second pass of %d steps (epochs %d..%d) with events around every call and every main "
+                                "kernel: %.4f ms per step; the timed region carries only the events around %s"
+                                % (args.steps, args.warmup + args.steps + 1, args.warmup + 2 * args.steps,
+                                   1e3 * wall_second / max(1, args.steps),
+                                   {None: "k_train and k_eval_sparse", "train": "k_train",
+                                    "precalc": "k_eval_sparse in the tally pre-calculation"}[live]),
             "bind_train_ms": bind_ms,
             "train_kernel_launches_per_epoch": n_train // max(1, args.steps),
             "train_pairs_per_s": q * C / (fit_avg * 1e-3),
@@ -467,6 +501,7 @@ def main():
         "traffic_source": traffic_src,
         "avg_launch_ms": launch_ms,
         "launches": n_train,
+        "timed_in": "timed region" if train_live else "second pass",
         "share_of_timed_region": train_ms / (1e3 * wall),
         "examples_per_launch": min(chunk, q),
         "algorithmic_lane_ops_per_launch": ops,
@@ -505,6 +540,7 @@ def main():
         "traffic_source": pre_traffic_src,
         "avg_launch_ms": pre_launch_ms,
         "launches": n_pre,
+        "timed_in": "timed region" if pre_live else "second pass",
         "share_of_timed_region": pre_ms / (1e3 * wall),
         "hbm_algorithmic_bytes_per_launch": pre_bytes,
         "algorithmic_lane_ops_per_launch": pre_ops,

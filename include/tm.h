@@ -264,15 +264,18 @@ int tm_get_epoch(tm_handle *h, uint32_t *epoch);
  * Synchronises the stream. */
 int tm_read_counters(tm_handle *h, uint64_t *out, void *stream);
 
-/* Kernel timing (measurement aid).  While enabled, every launch of the training
- * kernel (kind 0) and of the literal-list evaluation kernel (kind 1: in the
- * tally pre-calculation, kind 2: in tm_class_sums_ws / tm_predict_ws) is
- * bracketed by two events on its stream.  tm_read_kernel_timing waits for the
- * recorded events and returns, per kind, the summed kernel time in ms[3] and
- * the number of launches in launches[3] (both HOST arrays) since the last read
- * or enable, and forgets them.  Enabling or disabling forgets what was
- * recorded. */
-int tm_kernel_timing(tm_handle *h, int enable);
+/* Kernel timing (measurement aid).  `kinds` is a bit mask: while bit 0 is set
+ * every launch of the training kernel is bracketed by two events on its stream,
+ * with bit 1 every launch of the literal-list evaluation kernel in the tally
+ * pre-calculation, with bit 2 every such launch in tm_class_sums_ws /
+ * tm_predict_ws; 0 switches timing off, 7 times all three (an event between
+ * two kernels costs the stream a few microseconds, so a caller that times a
+ * whole step asks only for the kernel it wants).  tm_read_kernel_timing waits
+ * for the recorded events and returns, per kind, the summed kernel time in
+ * ms[3] and the number of launches in launches[3] (both HOST arrays) since the
+ * last read or change of the mask, and forgets them.  Changing the mask forgets
+ * what was recorded.  TM_EINVAL for a mask outside 0..7. */
+int tm_kernel_timing(tm_handle *h, int kinds);
 int tm_read_kernel_timing(tm_handle *h, double *ms, int64_t *launches);
 
 /* Text for an error code; hipError_t of the last failed HIP call on a handle. */

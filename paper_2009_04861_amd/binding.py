@@ -207,8 +207,13 @@ def tm_get_epoch(h):
     return e.value
 
 
-def tm_kernel_timing(h, enable):
-    _check(lib().tm_kernel_timing(h, ctypes.c_int(1 if enable else 0)), "tm_kernel_timing")
+TIMED_TRAIN, TIMED_PRECALC, TIMED_INFER, TIMED_ALL = 1, 2, 4, 7
+
+
+def tm_kernel_timing(h, kinds):
+    """kinds: bit mask of TIMED_TRAIN | TIMED_PRECALC | TIMED_INFER (True = all three, False / 0 = off)."""
+    mask = TIMED_ALL if kinds is True else int(kinds or 0)
+    _check(lib().tm_kernel_timing(h, ctypes.c_int(mask)), "tm_kernel_timing")
 
 
 def tm_read_kernel_timing(h):

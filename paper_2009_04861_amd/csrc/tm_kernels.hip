@@ -100,7 +100,7 @@ struct tm_handle {
     int clause_groups; // sub-launches of consecutive clause ranges per training launch
     int last_hip;
     // kernel timing (measurement aid): event pairs around the launches of the two main kernels
-    bool timing;
+    int timing_kinds;                 // bit k: launches of kind k are bracketed by events
     std::vector<hipEvent_t> ev_pool;  // events created so far, reused
     size_t ev_used;                   // events of the pool handed out since timing was switched on
     std::vector<int> ev_kind;         // kind of the k-th recorded pair (events 2k, 2k+1)
@@ -268,7 +268,7 @@ enum { TIMED_TRAIN = 0, TIMED_PRECALC = 1, TIMED_INFER = 2, TIMED_KINDS = 3 };
 // and after the launch of a timed kernel.
 int timing_mark(tm_handle *h, int kind, bool first, hipStream_t st)
 {
-    if (!h->timing || kind < 0) return TM_OK;
+    if (kind < 0 || !((h->timing_kinds >> kind) & 1)) return TM_OK;
     if (h->ev_used == h->ev_pool.size()) {
         hipEvent_t e;
         TM_HIP(h, hipEventCreate(&e));
@@ -900,10 +900,11 @@ int tm_get_epoch(tm_handle *h, uint32_t *epoch)
     return TM_OK;
 }
 
-int tm_kernel_timing(tm_handle *h, int enable)
+int tm_kernel_timing(tm_handle *h, int kinds)
 {
     if (!h) return TM_EINVAL;
-    h->timing = enable != 0;
+    if (kinds < 0 || kinds >= (1 << TIMED_KINDS)) return TM_EINVAL;
+    h->timing_kinds = kinds;
     h->ev_used = 0;
     h->ev_kind.clear();
     return TM_OK;
