@@ -434,6 +434,21 @@ __device__ __forceinline__ void train_clause(const uint32_t *__restrict__ X, con
         if constexpr (REGR) return ent >= 0 ? a.y_regr[ent >> 1] : 0;
         else return 0;
     };
+    // Slot geometry held in registers for the widths whose register budget has room for it (two per slot):
+    // which bits of the slot's word are literals at all, and whether they are negated ones.
+    constexpr bool GEOM = WPL >= 6 && WPL <= 10;
+    uint32_t geom_valid[GEOM ? WPL : 1], geom_neg[GEOM ? WPL : 1];
+    if constexpr (GEOM) {
+#pragma unroll
+        for (int r = 0; r < WPL; ++r) {
+            const uint32_t lw = (uint32_t)(r * 64 + lane);
+            const bool act = lw < (uint32_t)d.W;
+            const bool neg = lw >= (uint32_t)d.Wf;
+            const uint32_t fw = neg ? lw - (uint32_t)d.Wf : lw;
+            geom_valid[r] = act ? (fw == (uint32_t)d.Wf - 1u ? d.tailmask : ~0u) : 0u;
+            geom_neg[r] = neg ? ~0u : 0u;
+        }
+    }
     int ent_cur = load_ent(k_lo);
     int v_cur = load_v(ent_cur);
     int y_cur = load_y(ent_cur);
@@ -563,7 +578,13 @@ __device__ __forceinline__ void train_clause(const uint32_t *__restrict__ X, con
                         uint32_t lw = (uint32_t)(r * 64 + lane);
                         asm volatile("" : "+v"(lw));
                         uint32_t valid;
-                        const uint32_t lit = literal(lw, xw[r], valid);
+                        uint32_t lit;
+                        if constexpr (GEOM) {
+                            valid = geom_valid[r];
+                            lit = (xw[r] ^ geom_neg[r]) & valid;
+                        } else {
+                            lit = literal(lw, xw[r], valid);
+                        }
                         uint32_t sp[8];
                         get_slot(p[r], sp);
                         const uint32_t old7 = sp[7];
@@ -634,7 +655,13 @@ __device__ __forceinline__ void train_clause(const uint32_t *__restrict__ X, con
                         }
                     }
                     uint32_t valid;
-                    const uint32_t lit = literal(lw, xw[r], valid);
+                    uint32_t lit;
+                    if constexpr (GEOM) {
+                        valid = geom_valid[r];
+                        lit = (xw[r] ^ geom_neg[r]) & valid;
+                    } else {
+                        lit = literal(lw, xw[r], valid);
+                    }
                     uint32_t sp[8];
                     get_slot(p[r], sp);
                     const uint32_t old7 = sp[7];
