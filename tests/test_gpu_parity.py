@@ -248,6 +248,33 @@ def test_feedback_step_matches_bit_exactly(shape, device):
     assert c["fired"] == total_fired
 
 
+# one feature count per width the training kernel is compiled for (literal words -> register slots per
+# lane: 4, 6, 8, 12 and 16; 1, 2, 3, 10 and 20 are among SHAPES), ragged last feature word
+@pytest.mark.parametrize("o,N,s,regression", [(4001, 128, 5.0, False), (6003, 64, 3.0, False), (8005, 128, 10.0, False),
+                                              (12007, 128, 2.0, False), (16009, 100, 4.0, False), (8005, 128, 1.5, True)])
+def test_feedback_step_in_every_kernel_width(o, N, s, regression, device):
+    print("feedback, kernel width", o, N, s, regression, flush=True)
+    m, n, T, q = (1, 6, 6, 150) if regression else (2, 2, 3, 150)
+    rng = np.random.default_rng(o)
+    ora = O.Oracle(m, n, o, N, T, s, 17, regression=regression)
+    gpu = B.TsetlinMachine(m, n, o, N, T, s, 17, regression=regression)
+    X = (rng.random((q, o)) < 0.05).astype(np.uint8)
+    y = rng.integers(0, (T + 1) if regression else m, size=q).astype(np.int32)
+    gpu.bind_train(dev_bits(gpu, X), dev_i32(gpu, y))
+    tally, ostar = ora.sync_tallies(X)
+    assert np.array_equal(gpu.tallies().cpu().numpy(), tally)
+    fired = 0
+    for step, (i0, cnt) in enumerate([(0, 70), (70, 80), (0, q), (0, q)]):
+        B.tm_set_epoch(gpu.h, step)
+        fired += run_frozen(ora, gpu, X, y, step, i0, cnt, tally, ostar)
+        assert np.array_equal(gpu_state_as_oracle(gpu), ora.state), step
+        assert np.array_equal(gpu.tallies().cpu().numpy(), tally), step
+        assert np.array_equal(bits_to_u8(gpu.prev_outputs(), q), ostar), step
+    assert fired > 20
+    assert np.array_equal(gpu.class_sums(dev_bits(gpu, X)).cpu().numpy(), ora.class_sums(X))
+    gpu.close()
+
+
 @pytest.mark.parametrize("s", [1.0, 2.0, 4.0, 3.9, 25.0])
 @pytest.mark.parametrize("N", [3, 100, 128])
 def test_feedback_saturation_and_threshold_paths(s, N, device):
